@@ -1,0 +1,172 @@
+/*
+ * scap.h -- C ABI of the MI355X (gfx950) library for the decode-time sparse fully-connected
+ * layer of SCAP, "Statistical Calibrated Activation Pruning" (arXiv 2412.07174).
+ *
+ * The layer, in the paper's notation (Section 2 Eq. 1-3, Section 3 Eq. 4-6, Appendix B Alg. 3):
+ *
+ *     d    = x - eta                      eta: per-layer scalar mode estimate ("m" below)
+ *     keep = |d| > tau                    tau: per-layer scalar threshold (strict compare, Eq. 2)
+ *     y    = (d * keep) W + b_fused       b_fused = b + eta * (column sums of W)      (Eq. 6)
+ *
+ * W is the paper's IC x OC matrix stored K-major: element (i, o) of a K x N matrix is at
+ * W[i*N + o], so a pruned input channel is one contiguous row that is never fetched.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are HIP device pointers owned by the caller; pointers marked HOST are
+ *     ordinary host pointers.  The library allocates and frees no device memory and keeps no state
+ *     between calls other than what lives in the caller's workspace.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls marked ASYNC only
+ *     enqueue work on it and return; calls marked SYNC wait for the stream before returning.
+ *   - Every call returns a scap_status.  Arguments are validated on the host before anything is
+ *     enqueued; on an error nothing is launched and no output is written.  No call throws, aborts
+ *     or prints.
+ *   - Device pointers of W, x, y, bias, col_scale and the workspace must be 16-byte aligned.  N must
+ *     be a multiple of 8 (16-bit weights) or 16 (int8 weights).
+ *   - A workspace is a caller-allocated device buffer of at least scap_workspace_bytes(...) bytes
+ *     that has been passed once to scap_workspace_init().  Kernels leave it ready for the next
+ *     call.  Two calls that share one workspace must not overlap in time (use one workspace per
+ *     stream).
+ */
+#ifndef SCAP_H
+#define SCAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SCAP_OK = 0,
+    SCAP_ERR_NULL = -1,      /* a required pointer is NULL */
+    SCAP_ERR_SHAPE = -2,     /* K, N, B or n out of range, or N not a multiple of the vector width */
+    SCAP_ERR_DTYPE = -3,     /* unknown dtype / estimator code, or a combination not supported */
+    SCAP_ERR_ALIGN = -4,     /* a device pointer is not 16-byte aligned */
+    SCAP_ERR_VALUE = -5,     /* tau negative or NaN, m not finite, target sparsity outside [0, 1) */
+    SCAP_ERR_WORKSPACE = -6, /* workspace NULL or smaller than scap_workspace_bytes() */
+    SCAP_ERR_HIP = -7,       /* a HIP runtime call or launch reported an error */
+    SCAP_ERR_UNIMPL = -8,    /* valid request that this build does not implement */
+    SCAP_ERR_CONFIG = -9     /* invalid scap_launch_cfg */
+} scap_status;
+
+/* storage types of weights and activations */
+typedef enum {
+    SCAP_F16 = 0,         /* IEEE binary16 */
+    SCAP_BF16 = 1,        /* bfloat16 */
+    SCAP_I8_COLSCALE = 2  /* weights only: symmetric int8, w[i,o] = col_scale[o] * q[i,o], fp16 scales */
+} scap_dtype;
+
+/* mode estimators (Section 3, "Determination of mode value") */
+typedef enum {
+    SCAP_MODE_ZERO = 0,   /* m = 0: inputs already centred (GLU blocks, Section 4 "Implementation") */
+    SCAP_MODE_MEAN = 1,   /* mean of the pooled sample */
+    SCAP_MODE_MEDIAN = 2, /* median of the pooled sample (mean of the two middle values if even) */
+    SCAP_MODE_HIST = 3    /* histogram stand-in for a density-estimate mode: 2048 bins between the
+                             0.001 and 0.999 order statistics, 5-bin box smoothing, fullest bin */
+} scap_mode_est;
+
+/* Optional launch shape of the GEMV kernels (for tuning sweeps).  Zero fields mean "choose". */
+typedef struct {
+    int32_t waves_per_group; /* 4, 8 or 16 wavefronts per workgroup */
+    int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */
+    int32_t unroll;          /* weight rows in flight per wavefront: 4, 8 or 16 */
+    int32_t reserved;
+} scap_launch_cfg;
+
+/* Static, NUL-terminated description of a status code.  Never freed. */
+const char* scap_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int scap_version(void);
+
+/*
+ * Bytes of workspace that scap_sparse_fc / scap_dense_fc / scap_fold_bias need for a K x N layer and
+ * B tokens, and that scap_calibrate needs for an n x K sample (pass N = 0, B = n).  Returns 0 for
+ * arguments out of range.
+ */
+size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B);
+
+/*
+ * ASYNC.  Prepares a freshly allocated workspace (clears its counters with a fill kernel).  Must be
+ * called once before the workspace is first used, and again after any call that failed with
+ * SCAP_ERR_HIP.
+ *   workspace  DEVICE, 16-byte aligned, workspace_bytes >= 4096.
+ */
+int scap_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * SYNC, offline.  Calibration of one layer (Eq. 2: tau = Quantile(|X_calib|, s); Section 3: the mode
+ * is estimated first and the threshold is taken on the centred sample).
+ *   X_calib          DEVICE  [n, K] row-major activations captured at the layer input, dtype xdt
+ *                            (SCAP_F16 or SCAP_BF16); all n*K values are pooled.
+ *   target_sparsity  s in [0, 1).
+ *   est              scap_mode_est.
+ *   m_out, tau_out   HOST    receive the mode estimate and the threshold (fp32).
+ *                            tau is the k-th smallest of |fp32(x) - m| over the pool, k = ceil(s*n*K),
+ *                            no interpolation (k = 0 gives tau = 0); |.| is formed exactly as
+ *                            scap_sparse_fc forms it, so the sample's own sparsity is >= s.
+ *   workspace        DEVICE  scap_workspace_bytes(K, 0, n) bytes, initialised.
+ * NaN samples rank above every number.
+ */
+int scap_calibrate(const void* X_calib, int64_t n, int64_t K, int xdt, float target_sparsity, int est,
+                   float* m_out, float* tau_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ASYNC, offline.  Fused bias of Eq. 6: b_fused[o] = bias[o] + m * sum_i W[i,o].
+ *   W            DEVICE  [K, N] K-major, dtype wdt.
+ *   col_scale    DEVICE  fp16 [N] when wdt == SCAP_I8_COLSCALE, else NULL.
+ *   bias         DEVICE  fp32 [N] or NULL (= zeros; Alg. 2 is bias-free).
+ *   b_fused_out  DEVICE  fp32 [N].
+ */
+int scap_fold_bias(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const float* bias,
+                   float m, float* b_fused_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ASYNC, the decode-time hot path (Alg. 3 with the strict compare of Eq. 2; Eq. 3 / Eq. 6).
+ * One launch: centre, threshold, compact the kept channels, read only their weight rows, reduce.
+ *   W, col_scale   as in scap_fold_bias.
+ *   x              DEVICE  [B, K] row-major, dtype xdt (SCAP_F16 or SCAP_BF16).
+ *   m, tau         layer constants from scap_calibrate (tau >= 0, both finite).
+ *   b_fused        DEVICE  fp32 [N] from scap_fold_bias, or NULL (= zeros).
+ *   y              DEVICE  fp32 [B, N]; fully overwritten.
+ *   idx_out        DEVICE  int32 [B, K] or NULL: token b's kept channels, ascending, in
+ *                          idx_out[b*K .. b*K + nnz_out[b]); entries past nnz are left untouched.
+ *   nnz_out        DEVICE  int32 [B] or NULL (required when idx_out is given).
+ *   union_nnz_out  DEVICE  int32 [1] or NULL: number of distinct weight rows read (union of the B
+ *                          masks, Appendix C; equals nnz_out[0] for B = 1).
+ * Each token has its own mask (Eq. 2 is elementwise); a row in the union contributes zero to tokens
+ * that pruned it.  d = fp32(x) - m is one fp32 subtraction; products accumulate in fp32.
+ * NaN inputs are pruned (the compare is false); infinities are kept and propagate.
+ * B is limited to SCAP_MAX_TOKENS.
+ */
+#define SCAP_MAX_TOKENS 16
+int scap_sparse_fc(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                   int64_t B, float m, float tau, const float* b_fused, float* y, int32_t* idx_out,
+                   int32_t* nnz_out, int32_t* union_nnz_out, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/* Same as scap_sparse_fc with an explicit launch shape (cfg may be NULL). */
+int scap_sparse_fc_ex(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x,
+                      int xdt, int64_t B, float m, float tau, const float* b_fused, float* y, int32_t* idx_out,
+                      int32_t* nnz_out, int32_t* union_nnz_out, void* workspace, size_t workspace_bytes,
+                      void* stream, const scap_launch_cfg* cfg);
+
+/*
+ * ASYNC.  Dense baseline on the same kernels (Eq. 1): y[b,o] = bias[o] + sum_i x[b,i] W[i,o] over every
+ * channel, nothing centred or pruned.  Arguments as in scap_sparse_fc; cfg may be NULL.
+ */
+int scap_dense_fc(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                  int64_t B, const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream,
+                  const scap_launch_cfg* cfg);
+
+/*
+ * ASYNC.  Streaming-read probe used to measure the HBM read ceiling of the box: sums `bytes` bytes at
+ * `src` (DEVICE, 16-byte aligned, bytes a multiple of 16) into out[0] (DEVICE, uint32 checksum).
+ */
+int scap_read_probe(const void* src, size_t bytes, uint32_t* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCAP_H */

@@ -1,0 +1,197 @@
+"""ctypes binding of libscap.so.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libscap.so")
+
+F16, BF16, I8 = 0, 1, 2
+MODE_ZERO, MODE_MEAN, MODE_MEDIAN, MODE_HIST = 0, 1, 2, 3
+MAX_TOKENS = 16
+
+_TORCH_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8}
+
+EXPORTS = (
+    "scap_status_string", "scap_version", "scap_workspace_bytes", "scap_workspace_init", "scap_calibrate",
+    "scap_fold_bias", "scap_sparse_fc", "scap_sparse_fc_ex", "scap_dense_fc", "scap_read_probe",
+)
+
+
+class ScapError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class LaunchCfg(ctypes.Structure):
+    _fields_ = [("waves_per_group", ctypes.c_int32), ("rows_per_group", ctypes.c_int32),
+                ("unroll", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libscap.so from the package directory.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it first (python -m paper_2412_07174_amd.build, or "
+            "__graft_entry__.build()).  There is no fallback path.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.scap_status_string.restype = ctypes.c_char_p
+    lib.scap_status_string.argtypes = [i32]
+    lib.scap_version.restype = i32
+    lib.scap_version.argtypes = []
+    lib.scap_workspace_bytes.restype = sz
+    lib.scap_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.scap_workspace_init.restype = i32
+    lib.scap_workspace_init.argtypes = [vp, sz, vp]
+    lib.scap_calibrate.restype = i32
+    lib.scap_calibrate.argtypes = [vp, i64, i64, i32, f32, i32, ctypes.POINTER(f32), ctypes.POINTER(f32), vp, sz, vp]
+    lib.scap_fold_bias.restype = i32
+    lib.scap_fold_bias.argtypes = [vp, vp, i64, i64, i32, vp, f32, vp, vp, sz, vp]
+    fc = [vp, vp, i64, i64, i32, vp, i32, i64, f32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.scap_sparse_fc.restype = i32
+    lib.scap_sparse_fc.argtypes = fc
+    lib.scap_sparse_fc_ex.restype = i32
+    lib.scap_sparse_fc_ex.argtypes = fc + [ctypes.POINTER(LaunchCfg)]
+    lib.scap_dense_fc.restype = i32
+    lib.scap_dense_fc.argtypes = [vp, vp, i64, i64, i32, vp, i32, i64, vp, vp, vp, sz, vp, ctypes.POINTER(LaunchCfg)]
+    lib.scap_read_probe.restype = i32
+    lib.scap_read_probe.argtypes = [vp, sz, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().scap_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().scap_version())
+
+
+def workspace_bytes(K: int, N: int, B: int = 1) -> int:
+    return int(load_library().scap_workspace_bytes(K, N, B))
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise ScapError(rc, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _code(t: torch.Tensor, what: str) -> int:
+    try:
+        return _TORCH_CODE[t.dtype]
+    except KeyError:
+        raise TypeError(f"{what}: dtype {t.dtype} is not float16, bfloat16 or int8") from None
+
+
+def _cfg(cfg):
+    if cfg is None:
+        return None
+    if isinstance(cfg, LaunchCfg):
+        return ctypes.byref(cfg)
+    waves, rows, unroll = cfg
+    return ctypes.byref(LaunchCfg(int(waves), int(rows), int(unroll), 0))
+
+
+class Workspace:
+    """Caller-owned scratch for one stream: a torch byte buffer passed once to scap_workspace_init."""
+
+    def __init__(self, K: int, N: int, B: int = 1, device="cuda", stream=None):
+        nbytes = workspace_bytes(K, N, B)
+        if nbytes == 0:
+            raise ScapError(-2, "scap_workspace_bytes")
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.nbytes = nbytes
+        self.shape = (K, N, B)
+        _check(load_library().scap_workspace_init(_ptr(self.buf), nbytes, _stream(stream)), "scap_workspace_init")
+
+    def fits(self, K: int, N: int, B: int) -> bool:
+        return workspace_bytes(K, N, B) <= self.nbytes
+
+
+def calibrate(X_calib: torch.Tensor, target_sparsity: float, est: int = MODE_MEDIAN, *, workspace: Workspace,
+              stream=None) -> Tuple[float, float]:
+    """(m, tau) of one layer from its calibration activations [n, K] (device tensor, fp16/bf16)."""
+    lib = load_library()
+    n, K = X_calib.shape
+    m, tau = ctypes.c_float(0), ctypes.c_float(0)
+    rc = lib.scap_calibrate(_ptr(X_calib), n, K, _code(X_calib, "X_calib"), float(target_sparsity), int(est),
+                            ctypes.byref(m), ctypes.byref(tau), _ptr(workspace.buf), workspace.nbytes, _stream(stream))
+    _check(rc, "scap_calibrate")
+    return float(m.value), float(tau.value)
+
+
+def fold_bias(W: torch.Tensor, m: float, bias: Optional[torch.Tensor] = None, *, col_scale=None,
+              out: Optional[torch.Tensor] = None, workspace: Workspace, stream=None) -> torch.Tensor:
+    lib = load_library()
+    K, N = W.shape
+    if out is None:
+        out = torch.empty(N, dtype=torch.float32, device=W.device)
+    rc = lib.scap_fold_bias(_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(bias), float(m), _ptr(out),
+                            _ptr(workspace.buf), workspace.nbytes, _stream(stream))
+    _check(rc, "scap_fold_bias")
+    return out
+
+
+def sparse_fc(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_fused: Optional[torch.Tensor] = None, *,
+              col_scale=None, y: Optional[torch.Tensor] = None, idx_out=None, nnz_out=None, union_nnz_out=None,
+              workspace: Workspace, cfg=None, stream=None) -> torch.Tensor:
+    """y[B,N] = ((x - m) masked by |x - m| > tau) @ W + b_fused.  x is [K] or [B, K]."""
+    lib = load_library()
+    K, N = W.shape
+    B = 1 if x.dim() == 1 else x.shape[0]
+    if y is None:
+        y = torch.empty((B, N), dtype=torch.float32, device=W.device)
+    args = [_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(x), _code(x, "x"), B, float(m), float(tau),
+            _ptr(b_fused), _ptr(y), _ptr(idx_out), _ptr(nnz_out), _ptr(union_nnz_out), _ptr(workspace.buf),
+            workspace.nbytes, _stream(stream)]
+    if cfg is None:
+        rc = lib.scap_sparse_fc(*args)
+    else:
+        rc = lib.scap_sparse_fc_ex(*args, _cfg(cfg))
+    _check(rc, "scap_sparse_fc")
+    return y
+
+
+def dense_fc(W: torch.Tensor, x: torch.Tensor, bias: Optional[torch.Tensor] = None, *, col_scale=None,
+             y: Optional[torch.Tensor] = None, workspace: Workspace, cfg=None, stream=None) -> torch.Tensor:
+    lib = load_library()
+    K, N = W.shape
+    B = 1 if x.dim() == 1 else x.shape[0]
+    if y is None:
+        y = torch.empty((B, N), dtype=torch.float32, device=W.device)
+    rc = lib.scap_dense_fc(_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(x), _code(x, "x"), B, _ptr(bias),
+                           _ptr(y), _ptr(workspace.buf), workspace.nbytes, _stream(stream), _cfg(cfg))
+    _check(rc, "scap_dense_fc")
+    return y
+
+
+def read_probe(src: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    rc = load_library().scap_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(out), _stream(stream))
+    _check(rc, "scap_read_probe")

@@ -1,0 +1,169 @@
+// extern "C" entry points of libscap: argument validation and dispatch.  See include/scap.h.
+#include <math.h>
+
+#include "scap_internal.hpp"
+
+using namespace scap;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool weight_dtype_ok(int wdt) { return wdt == SCAP_F16 || wdt == SCAP_BF16 || wdt == SCAP_I8_COLSCALE; }
+bool act_dtype_ok(int xdt) { return xdt == SCAP_F16 || xdt == SCAP_BF16; }
+
+int check_layer(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt) {
+    if (!W) return SCAP_ERR_NULL;
+    if (!weight_dtype_ok(wdt)) return SCAP_ERR_DTYPE;
+    if (wdt == SCAP_I8_COLSCALE && !col_scale) return SCAP_ERR_NULL;
+    if (K < 1 || N < 1 || K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19)) return SCAP_ERR_SHAPE;
+    const int64_t vec = (wdt == SCAP_I8_COLSCALE) ? 16 : 8;
+    if (N % vec != 0) return SCAP_ERR_SHAPE;
+    if (!aligned16(W) || (col_scale && !aligned16(col_scale))) return SCAP_ERR_ALIGN;
+    return SCAP_OK;
+}
+
+int check_workspace(void* ws, size_t bytes, int64_t K, int64_t N, int64_t B) {
+    if (!ws) return SCAP_ERR_WORKSPACE;
+    if (!aligned16(ws)) return SCAP_ERR_ALIGN;
+    const size_t need = scap_workspace_bytes(K, N, B);
+    if (need == 0 || bytes < need) return SCAP_ERR_WORKSPACE;
+    return SCAP_OK;
+}
+
+void fill_workspace_ptrs(GemvArgs& a, void* ws, int64_t K, int64_t B) {
+    char* base = static_cast<char*>(ws);
+    a.counters = reinterpret_cast<int32_t*>(base + kOffCounters);
+    a.seg_cnt = reinterpret_cast<int32_t*>(base + kOffSegCnt);
+    a.seg_idx = reinterpret_cast<int32_t*>(base + kOffSegIdx);
+    a.partial = reinterpret_cast<float*>(base + kOffSegIdx + seg_idx_bytes(K, B));
+}
+
+int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+              int64_t B, float m, float tau, const float* bias, float* y, int32_t* idx_out, int32_t* nnz_out,
+              int32_t* union_nnz_out, void* workspace, size_t workspace_bytes, void* stream, const scap_launch_cfg* cfg) {
+    int rc = check_layer(W, col_scale, K, N, wdt);
+    if (rc != SCAP_OK) return rc;
+    if (!y) return SCAP_ERR_NULL;
+    if (mode != kModeFold) {
+        if (!x) return SCAP_ERR_NULL;
+        if (!act_dtype_ok(xdt)) return SCAP_ERR_DTYPE;
+        if (!aligned16(x)) return SCAP_ERR_ALIGN;
+    }
+    if (B < 1 || B > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
+    if (!aligned16(y) || (bias && !aligned16(bias))) return SCAP_ERR_ALIGN;
+    if (idx_out && !nnz_out) return SCAP_ERR_NULL;
+    if (mode == kModeSparse) {
+        if (!(tau >= 0.f) || !isfinite(tau) || !isfinite(m)) return SCAP_ERR_VALUE;
+    } else if (mode == kModeFold) {
+        if (!isfinite(m)) return SCAP_ERR_VALUE;
+    }
+    rc = check_workspace(workspace, workspace_bytes, K, N, B);
+    if (rc != SCAP_OK) return rc;
+
+    GemvArgs a{};
+    a.W = W;
+    a.col_scale = static_cast<const uint16_t*>(col_scale);
+    a.x = static_cast<const uint16_t*>(x);
+    a.bias = bias;
+    a.y = y;
+    a.idx_out = idx_out;
+    a.nnz_out = nnz_out;
+    a.union_nnz_out = union_nnz_out;
+    a.K = (int)K;
+    a.N = (int)N;
+    a.B = (int)B;
+    a.mode = mode;
+    a.xdt = xdt;
+    a.m = m;
+    a.tau = tau;
+    fill_workspace_ptrs(a, workspace, K, B);
+    return launch_gemv(a, wdt, cfg, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* scap_status_string(int status) {
+    switch (status) {
+        case SCAP_OK: return "ok";
+        case SCAP_ERR_NULL: return "a required pointer is NULL";
+        case SCAP_ERR_SHAPE: return "shape out of range or N not a multiple of the vector width";
+        case SCAP_ERR_DTYPE: return "unknown or unsupported dtype / estimator code";
+        case SCAP_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case SCAP_ERR_VALUE: return "tau negative or NaN, m not finite, or sparsity outside [0,1)";
+        case SCAP_ERR_WORKSPACE: return "workspace missing or too small";
+        case SCAP_ERR_HIP: return "HIP runtime error";
+        case SCAP_ERR_UNIMPL: return "not implemented in this build";
+        case SCAP_ERR_CONFIG: return "invalid launch configuration";
+    }
+    return "unknown status";
+}
+
+int scap_version(void) { return 100; }
+
+size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B) {
+    if (K < 1 || N < 0 || B < 1) return 0;
+    if (N == 0) return kOffSegCnt;  // calibration only uses the fixed header
+    if (K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19) || B > SCAP_MAX_TOKENS) return 0;
+    return kOffSegIdx + seg_idx_bytes(K, B) + 4 * (size_t)B * partial_capacity(N);
+}
+
+int scap_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (!workspace) return SCAP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SCAP_ERR_ALIGN;
+    if (workspace_bytes < 4096) return SCAP_ERR_WORKSPACE;
+    return launch_zero_words(static_cast<int32_t*>(workspace), kMaxTiles, static_cast<hipStream_t>(stream));
+}
+
+int scap_calibrate(const void* X_calib, int64_t n, int64_t K, int xdt, float target_sparsity, int est, float* m_out,
+                   float* tau_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X_calib || !m_out || !tau_out) return SCAP_ERR_NULL;
+    if (!act_dtype_ok(xdt)) return SCAP_ERR_DTYPE;
+    if (est < SCAP_MODE_ZERO || est > SCAP_MODE_HIST) return SCAP_ERR_DTYPE;
+    if (n < 1 || K < 1 || K > ((int64_t)1 << 24) || n > ((int64_t)1 << 34) / K) return SCAP_ERR_SHAPE;
+    if (!(target_sparsity >= 0.f && target_sparsity < 1.f)) return SCAP_ERR_VALUE;
+    if (!aligned16(X_calib)) return SCAP_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kOffSegCnt) return SCAP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SCAP_ERR_ALIGN;
+    return run_calibrate(static_cast<const uint16_t*>(X_calib), n * K, xdt, target_sparsity, est, m_out, tau_out,
+                         workspace, static_cast<hipStream_t>(stream));
+}
+
+int scap_fold_bias(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const float* bias, float m,
+                   float* b_fused_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return fc_common(kModeFold, W, col_scale, K, N, wdt, nullptr, SCAP_BF16, 1, m, 0.f, bias, b_fused_out, nullptr,
+                     nullptr, nullptr, workspace, workspace_bytes, stream, nullptr);
+}
+
+int scap_sparse_fc_ex(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                      int64_t B, float m, float tau, const float* b_fused, float* y, int32_t* idx_out,
+                      int32_t* nnz_out, int32_t* union_nnz_out, void* workspace, size_t workspace_bytes, void* stream,
+                      const scap_launch_cfg* cfg) {
+    return fc_common(kModeSparse, W, col_scale, K, N, wdt, x, xdt, B, m, tau, b_fused, y, idx_out, nnz_out,
+                     union_nnz_out, workspace, workspace_bytes, stream, cfg);
+}
+
+int scap_sparse_fc(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                   int64_t B, float m, float tau, const float* b_fused, float* y, int32_t* idx_out, int32_t* nnz_out,
+                   int32_t* union_nnz_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return fc_common(kModeSparse, W, col_scale, K, N, wdt, x, xdt, B, m, tau, b_fused, y, idx_out, nnz_out,
+                     union_nnz_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int scap_dense_fc(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                  int64_t B, const float* bias, float* y, void* workspace, size_t workspace_bytes, void* stream,
+                  const scap_launch_cfg* cfg) {
+    return fc_common(kModeDense, W, col_scale, K, N, wdt, x, xdt, B, 0.f, 0.f, bias, y, nullptr, nullptr, nullptr,
+                     workspace, workspace_bytes, stream, cfg);
+}
+
+int scap_read_probe(const void* src, size_t bytes, uint32_t* out, void* stream) {
+    if (!src || !out) return SCAP_ERR_NULL;
+    if (!aligned16(src)) return SCAP_ERR_ALIGN;
+    if (bytes == 0 || bytes % 16 != 0) return SCAP_ERR_SHAPE;
+    return launch_read_probe(src, bytes, out, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

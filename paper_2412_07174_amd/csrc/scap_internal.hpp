@@ -1,0 +1,84 @@
+// Host-side internals of libscap: workspace layout, kernel argument blocks, launcher prototypes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/scap.h"
+
+namespace scap {
+
+// dtype codes, numerically equal to scap_dtype
+constexpr int kF16 = SCAP_F16;
+constexpr int kBF16 = SCAP_BF16;
+constexpr int kI8 = SCAP_I8_COLSCALE;
+
+// GEMV input modes
+constexpr int kModeSparse = 0;  // d = x - m, keep = |d| > tau        (Alg. 3)
+constexpr int kModeDense = 1;   // d = x, every channel kept          (Eq. 1)
+constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, eta * column sums)
+
+// ---------------------------------------------------------------------------------------------
+// Workspace layout (byte offsets into the caller's buffer)
+//   [0, 4096)            int32 counters[1024]    arrival counters, one per column tile; zero at rest
+//   [4096, 20480)        uint64 hist[2048]       calibration histograms
+//   [20480, 28672)       double sums[1024]       calibration partial sums
+//   [65536, +32768)      int32 seg_cnt[17][256]  kept-channel counts per (token | union, K split)
+//   [98304, +4*B*K)      int32 seg_idx[B][K]     per-split kept-channel lists (only for idx_out)
+//   [.., +4*B*cap)       float partial[B][S][T][tile]   split-K partial sums
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kOffCounters = 0;
+constexpr size_t kOffHist = 4096;
+constexpr size_t kOffSums = 20480;
+constexpr size_t kOffSegCnt = 65536;
+constexpr size_t kOffSegIdx = 98304;
+constexpr int kMaxTiles = 1024;
+constexpr int kMaxSplits = 256;
+constexpr int kHistBins = 2048;
+constexpr int kSumSlots = 1024;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// columns rounded up to whole 1024-column blocks (covers the 512- and 1024-column tiles)
+inline size_t padded_cols(int64_t N) { return align_up((size_t)N, 1024); }
+
+// floats of split-K partial storage per token
+inline size_t partial_capacity(int64_t N) {
+    const size_t np = padded_cols(N);
+    const size_t cap = np * 16;
+    return cap > ((size_t)1 << 20) ? cap : ((size_t)1 << 20);
+}
+
+inline size_t seg_idx_bytes(int64_t K, int64_t B) { return align_up((size_t)K * (size_t)B * 4, 256); }
+
+struct GemvArgs {
+    const void* W;
+    const uint16_t* col_scale;
+    const uint16_t* x;
+    const float* bias;
+    float* y;
+    int32_t* idx_out;
+    int32_t* nnz_out;
+    int32_t* union_nnz_out;
+    int32_t* counters;
+    int32_t* seg_cnt;
+    int32_t* seg_idx;
+    float* partial;
+    int K, N, B, Kc, S, T, mode, xdt;
+    float m, tau;
+};
+
+// Enqueue one GEMV (sparse / dense / fold mode).  Returns a scap_status.
+int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+
+// Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).
+int launch_zero_words(int32_t* p, size_t n, hipStream_t stream);
+
+int launch_read_probe(const void* src, size_t bytes, uint32_t* out, hipStream_t stream);
+
+// Calibration (synchronous; returns a scap_status).
+int run_calibrate(const uint16_t* X, int64_t M, int xdt, float s, int est, float* m_out, float* tau_out,
+                  void* workspace, hipStream_t stream);
+
+}  // namespace scap

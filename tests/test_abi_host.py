@@ -1,0 +1,110 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header declares, and
+rejects bad arguments before anything is launched (no GPU needed: validation never dereferences)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2412_07174_amd as scap
+from paper_2412_07174_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000   # 16-byte aligned, never dereferenced: every call below fails validation first
+ODD = FAKE + 2
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(scap.lib_path()):
+        from paper_2412_07174_amd import build
+        build.build(verbose=False)
+    return scap.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "scap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(scap_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings_and_version(lib):
+    assert scap.version() >= 100
+    assert scap.status_string(0) == "ok"
+    seen = {scap.status_string(c) for c in range(-9, 1)}
+    assert len(seen) == 10 and "unknown status" not in seen
+    assert scap.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    assert scap.workspace_bytes(14336, 4096, 1) >= 98304 + 4 * 14336 + 4 * (1 << 20)
+    assert scap.workspace_bytes(1024, 0, 256) == 65536          # calibration-only
+    assert scap.workspace_bytes(0, 4096, 1) == 0
+    assert scap.workspace_bytes(4096, 4096, 17) == 0
+    assert scap.workspace_bytes(4096, 4096, 16) > scap.workspace_bytes(4096, 4096, 1)
+
+
+def _fc(lib, **kw):
+    a = dict(W=FAKE, col_scale=None, K=1024, N=4096, wdt=1, x=FAKE, xdt=1, B=1, m=0.0, tau=0.5, b=None, y=FAKE,
+             idx=None, nnz=None, unz=None, ws=FAKE, wsb=1 << 30, stream=None)
+    a.update(kw)
+    return lib.scap_sparse_fc(a["W"], a["col_scale"], a["K"], a["N"], a["wdt"], a["x"], a["xdt"], a["B"], a["m"],
+                              a["tau"], a["b"], a["y"], a["idx"], a["nnz"], a["unz"], a["ws"], a["wsb"], a["stream"])
+
+
+def test_sparse_fc_argument_validation(lib):
+    assert _fc(lib, W=None) == -1
+    assert _fc(lib, x=None) == -1
+    assert _fc(lib, y=None) == -1
+    assert _fc(lib, wdt=2) == -1                      # int8 without column scales
+    assert _fc(lib, idx=FAKE) == -1                   # idx_out needs nnz_out
+    assert _fc(lib, N=4100) == -2                     # not a multiple of 8
+    assert _fc(lib, wdt=2, col_scale=FAKE, N=4104) == -2   # int8 wants multiples of 16
+    assert _fc(lib, K=0) == -2
+    assert _fc(lib, B=0) == -2 and _fc(lib, B=17) == -2
+    assert _fc(lib, wdt=7) == -3 and _fc(lib, xdt=2) == -3
+    assert _fc(lib, W=ODD) == -4 and _fc(lib, x=ODD) == -4 and _fc(lib, y=ODD) == -4 and _fc(lib, b=ODD) == -4
+    assert _fc(lib, tau=-0.1) == -5
+    assert _fc(lib, tau=float("nan")) == -5 and _fc(lib, tau=float("inf")) == -5
+    assert _fc(lib, m=float("inf")) == -5
+    assert _fc(lib, ws=None) == -6
+    assert _fc(lib, wsb=1000) == -6
+    assert _fc(lib, ws=ODD) == -4
+
+
+def test_other_entry_points_validate(lib):
+    f = ctypes.c_float(0)
+    p = ctypes.byref(f)
+    assert lib.scap_calibrate(None, 4, 8, 1, 0.5, 2, p, p, FAKE, 65536, None) == -1
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 2, None, p, FAKE, 65536, None) == -1
+    assert lib.scap_calibrate(FAKE, 4, 8, 2, 0.5, 2, p, p, FAKE, 65536, None) == -3
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 9, p, p, FAKE, 65536, None) == -3
+    assert lib.scap_calibrate(FAKE, 0, 8, 1, 0.5, 2, p, p, FAKE, 65536, None) == -2
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 1.0, 2, p, p, FAKE, 65536, None) == -5
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, -0.1, 2, p, p, FAKE, 65536, None) == -5
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 2, p, p, FAKE, 100, None) == -6
+    assert lib.scap_fold_bias(None, None, 8, 8, 1, None, 0.0, FAKE, FAKE, 1 << 30, None) == -1
+    assert lib.scap_fold_bias(FAKE, None, 8, 8, 1, None, float("nan"), FAKE, FAKE, 1 << 30, None) == -5
+    assert lib.scap_fold_bias(FAKE, None, 8, 12, 1, None, 0.0, FAKE, FAKE, 1 << 30, None) == -2
+    assert lib.scap_dense_fc(FAKE, None, 8, 8, 1, None, 1, 1, None, FAKE, FAKE, 1 << 30, None, None) == -1
+    assert lib.scap_workspace_init(None, 1 << 20, None) == -6
+    assert lib.scap_workspace_init(FAKE, 16, None) == -6
+    assert lib.scap_read_probe(None, 1024, FAKE, None) == -1
+    assert lib.scap_read_probe(FAKE, 1000, FAKE, None) == -2
+
+
+def test_product_package_does_not_touch_the_oracle():
+    """The product path must not import, link or call the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2412_07174_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "scap_oracle" not in text, f

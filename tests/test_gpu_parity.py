@@ -1,0 +1,300 @@
+"""GPU parity: every call goes through the C ABI of libscap.so and is compared with the CPU oracle on
+the same seeded inputs -- kept-channel lists and counts bit-exact, y within max-abs 1e-2 and rel-L2 2e-3."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_07174_amd as scap
+import workloads as wl
+from workloads import BF16, F16, I8
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import Layer, assert_y_close, check_against_oracle, f32_dev, gpu_sparse_fc, to_dev
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def _calib(site, s, est="median"):
+    return oracle.calibrate(site.calib(), site.xdt, s, oracle.EST[est])
+
+
+# ------------------------------------------------------------------ small shapes: tiles, splits, ragged tails
+SMALL = [
+    # K, N: below one wave, ragged chunk, several splits, several column tiles, ragged last tile
+    (1, 8), (63, 8), (64, 512), (65, 520), (200, 1032), (1000, 4096), (1024, 4104), (4099, 1544), (2048, 72),
+]
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("K,N", SMALL)
+def test_small_shapes(dt, K, N):
+    W = wl.weights(K, N, 100 + K, dt)
+    layer = Layer(W, dt, B=1)
+    X = wl.laplace(3, K, 200 + K, dt, loc=0.2, scale=0.6)
+    bf = np.random.default_rng(K).standard_normal(N).astype(np.float32)
+    for tau in (0.0, 0.41, 1.4, 1e6):
+        for b in range(X.shape[0]):
+            say(f"small K={K} N={N} dt={dt} tau={tau} vec={b}")
+            check_against_oracle(layer, X[b], dt, 0.2, tau, bf, what=f"K={K} N={N} tau={tau}")
+
+
+@pytest.mark.parametrize("waves,unroll", [(4, 4), (4, 8), (4, 16), (8, 4), (8, 8), (8, 16), (16, 4), (16, 8), (16, 16)])
+def test_every_launch_shape(waves, unroll):
+    K, N = 3000, 1544
+    W = wl.weights(K, N, 301, BF16)
+    layer = Layer(W, BF16, B=1)
+    x = wl.swiglu(1, K, 302, BF16)[0]
+    bf = np.random.default_rng(303).standard_normal(N).astype(np.float32)
+    for rows in (64, 192, 512, 1024, 3008):
+        for tau in (0.05, 0.6):
+            say(f"launch shape waves={waves} unroll={unroll} rows={rows} tau={tau}")
+            check_against_oracle(layer, x, BF16, 0.0, tau, bf, cfg=(waves, rows, unroll), what=f"{waves}/{rows}/{unroll}")
+
+
+def test_invalid_launch_shape_is_rejected():
+    layer = Layer(wl.weights(256, 512, 1, BF16), BF16, B=1)
+    x = to_dev(wl.swiglu(1, 256, 2, BF16)[0], BF16)
+    for cfg in [(3, 128, 8), (8, 100, 8), (8, 128, 5)]:
+        with pytest.raises(scap.ScapError) as e:
+            scap.sparse_fc(layer.W, x, 0.0, 0.1, None, workspace=layer.ws, cfg=cfg)
+        assert e.value.status == -9
+
+
+# ------------------------------------------------------------------ exact integer cases (bit-exact y)
+@pytest.mark.parametrize("dt", [F16, BF16])
+def test_integer_cases_are_bit_exact(dt):
+    K, N = 96, 16
+    rng = np.random.default_rng(7)
+    xi, Wi, bi = rng.integers(-6, 7, size=K), rng.integers(-4, 5, size=(K, N)), rng.integers(-9, 10, size=N)
+    layer = Layer(wl.encode(Wi.astype(np.float32), dt), dt, B=1)
+    x = wl.encode(xi.astype(np.float32), dt)
+    for eta in (0, 2, -3):
+        bf_int = bi + eta * Wi.sum(axis=0)
+        bfd = scap.fold_bias(layer.W, float(eta), f32_dev(bi.astype(np.float32)), workspace=layer.ws)
+        assert bfd.cpu().numpy().tolist() == [float(v) for v in bf_int]
+        for tau in range(0, 10):
+            say(f"integer case dt={dt} eta={eta} tau={tau}")
+            keep = [i for i in range(K) if abs(int(xi[i]) - eta) > tau]
+            want = [int(bf_int[o]) + sum((int(xi[i]) - eta) * int(Wi[i, o]) for i in keep) for o in range(N)]
+            got = gpu_sparse_fc(layer, x, dt, float(eta), float(tau), bf_int.astype(np.float32))
+            assert got["idx"][0].tolist() == keep and int(got["nnz"][0]) == len(keep)
+            assert got["y"][0].tolist() == [float(v) for v in want]
+
+
+def test_ties_nonfinite_and_empty_mask():
+    K, N = 256, 64
+    W = wl.weights(K, N, 401, BF16)
+    layer = Layer(W, BF16, B=1)
+    xs = np.random.default_rng(402).choice(np.array([0.5, -0.5, 0.50390625, 0.25, 1.0, -2.0], dtype=np.float32), size=K)
+    x = wl.encode(xs, BF16)
+    say("ties at |d| == tau")
+    got, want = check_against_oracle(layer, x, BF16, 0.0, 0.5, None, what="ties")
+    assert int(want["nnz"][0]) == int((np.abs(xs) > 0.5).sum())
+    xs2 = xs.copy()
+    xs2[3], xs2[77] = np.nan, np.inf
+    say("NaN and Inf inputs")
+    check_against_oracle(layer, wl.encode(xs2, BF16), BF16, 0.0, 0.5, None, what="nonfinite")
+    say("nothing kept")
+    bf = np.random.default_rng(403).standard_normal(N).astype(np.float32)
+    got = gpu_sparse_fc(layer, x, BF16, 0.0, 100.0, bf)
+    assert int(got["nnz"][0]) == 0 and got["union_nnz"] == 0
+    assert np.array_equal(got["y"][0], bf)
+
+
+def test_rerun_is_bit_identical_and_workspace_is_reusable():
+    site = wl.sites(1)[0]
+    W = site.make_weights()
+    layer = Layer(W, site.wdt, B=1)
+    X = site.test_vectors(4)
+    ys = []
+    for rep in range(3):
+        for b in range(4):
+            say(f"rerun rep={rep} vec={b}")
+            ys.append(gpu_sparse_fc(layer, X[b], site.xdt, 0.1, 0.3466, None)["y"])
+    for b in range(4):
+        assert np.array_equal(ys[b], ys[4 + b]) and np.array_equal(ys[b], ys[8 + b])
+    # a smaller layer through the same (larger) workspace
+    W2 = wl.weights(320, 1032, 5, site.wdt)
+    small = Layer(W2, site.wdt, B=1)
+    small.ws = layer.ws
+    check_against_oracle(small, wl.laplace(1, 320, 6, site.wdt)[0], site.xdt, 0.1, 0.3, None, what="shared workspace")
+
+
+# ------------------------------------------------------------------ the benchmark configurations at full size
+def test_config1_all_vectors():
+    site = wl.sites(1)[0]
+    layer = Layer(site.make_weights(), site.wdt, B=1)
+    m, tau = _calib(site, 0.5)
+    bf = oracle.fold_bias(layer.W_host, m, None, site.wdt)
+    X = site.test_vectors(64)
+    tot = 0
+    for b in range(64):
+        say(f"config1 vec={b}")
+        got, _ = check_against_oracle(layer, X[b], site.xdt, m, tau, bf, what=f"cfg1 vec {b}")
+        tot += int(got["nnz"][0])
+    assert abs(1 - tot / (64 * site.K) - 0.5) < 0.02
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_config2_llama_sites(which):
+    site = wl.sites(2)[which]
+    layer = Layer(site.make_weights(), site.wdt, B=1)
+    X = site.test_vectors(3)
+    calib = site.calib()
+    for s in site.targets:
+        m, tau = oracle.calibrate(calib, site.xdt, s, oracle.MODE_MEDIAN)
+        bf = oracle.fold_bias(layer.W_host, m, None, site.wdt)
+        for b in range(X.shape[0]):
+            say(f"config2 {site.name} s={s} vec={b}")
+            check_against_oracle(layer, X[b], site.xdt, m, tau, bf, what=f"{site.name} s={s}")
+
+
+@pytest.mark.parametrize("which", [0, 1, 2, 3])
+def test_config3_mistral_layers(which):
+    site = wl.sites(3)[which]
+    layer = Layer(site.make_weights(), site.wdt, B=1)
+    m, tau = _calib(site, 0.5)
+    bf = oracle.fold_bias(layer.W_host, m, None, site.wdt)
+    X = site.test_vectors(2)
+    for b in range(2):
+        say(f"config3 {site.name} vec={b}")
+        check_against_oracle(layer, X[b], site.xdt, m, tau, bf, what=site.name)
+
+
+def test_headline_layer_three_sparsities_and_dense():
+    site = wl.sites(4)[1]          # 14336 -> 4096, bf16
+    W = site.make_weights()
+    layer = Layer(W, site.wdt, B=1)
+    X = site.test_vectors(2)
+    calib = site.calib()
+    for s in (0.5, 0.7, 0.9):
+        _, tau = oracle.calibrate(calib, site.xdt, s, oracle.MODE_ZERO)
+        for b in range(2):
+            say(f"headline s={s} vec={b}")
+            got, _ = check_against_oracle(layer, X[b], site.xdt, 0.0, tau, None, what=f"headline s={s}")
+            assert abs(1 - got["nnz"][0] / site.K - s) < 0.03
+    say("headline dense baseline")
+    bias = np.random.default_rng(9).standard_normal(site.N).astype(np.float32)
+    y = scap.dense_fc(layer.W, to_dev(X[0], site.xdt), f32_dev(bias), workspace=layer.ws)
+    torch.cuda.synchronize()
+    assert_y_close(y.cpu().numpy(), oracle.dense_fc(W, X[0], bias, site.wdt, site.xdt), "dense")
+
+
+# ------------------------------------------------------------------ several tokens: own masks, union of rows
+@pytest.mark.parametrize("B", [2, 3, 4, 8, 16])
+def test_batched_tokens_moderate(B):
+    K, N = 2500, 1032
+    W = wl.weights(K, N, 501, BF16)
+    layer = Layer(W, BF16, B=16)
+    X = wl.swiglu(B, K, 502 + B, BF16)
+    bf = np.random.default_rng(503).standard_normal(N).astype(np.float32)
+    for tau in (0.0, 0.15, 0.8, 50.0):
+        say(f"batched B={B} tau={tau}")
+        check_against_oracle(layer, X, BF16, 0.0, tau, bf, what=f"B={B} tau={tau}")
+
+
+@pytest.mark.parametrize("which,B", [(0, 4), (1, 4), (1, 16)])
+def test_config4_batched_full_size(which, B):
+    site = wl.sites(4)[which]
+    layer = Layer(site.make_weights(), site.wdt, B=16)
+    calib = site.calib()
+    X = site.draw(B, site.seed_test + 77)
+    for s in (0.7, 0.9):
+        _, tau = oracle.calibrate(calib, site.xdt, s, oracle.MODE_ZERO)
+        say(f"config4 {site.name} B={B} s={s}")
+        got, want = check_against_oracle(layer, X, site.xdt, 0.0, tau, None, what=f"{site.name} B={B} s={s}")
+        if site.kind == "swiglu":
+            dens = want["union_nnz"] / site.K
+            assert abs(dens - (1 - s ** B)) < 0.02
+
+
+# ------------------------------------------------------------------ int8 weights with column scales
+@pytest.mark.parametrize("K,N,B", [(700, 2064, 1), (4096, 1024, 1), (1500, 3088, 4)])
+def test_int8_weights(K, N, B):
+    q, scale = wl.quantize_i8(K, N, 601)
+    layer = Layer(q, I8, col_scale_bits=scale, B=16)
+    X = wl.swiglu(B, K, 602, BF16)
+    for tau in (0.0, 0.3):
+        say(f"int8 K={K} N={N} B={B} tau={tau}")
+        check_against_oracle(layer, X, BF16, 0.0, tau, None, what=f"int8 {K}x{N}")
+    bf_want = oracle.fold_bias(q, 0.25, None, I8, col_scale=scale)
+    bf = scap.fold_bias(layer.W, 0.25, None, col_scale=layer.scale, workspace=layer.ws)
+    torch.cuda.synchronize()
+    assert np.allclose(bf.cpu().numpy(), bf_want, rtol=1e-5, atol=1e-5)
+
+
+def test_config5_expert_down_projection():
+    site = wl.sites(5)[1]          # expert 0, down 14336 -> 4096, int8
+    q, scale = wl.quantize_i8(site.K, site.N, site.seed_w)
+    layer = Layer(q, I8, col_scale_bits=scale, B=16)
+    calib = wl.swiglu(128, site.K, site.seed_calib, BF16)
+    m, tau = oracle.calibrate(calib, BF16, 0.7, oracle.MODE_MEDIAN)
+    bf = oracle.fold_bias(q, m, None, I8, col_scale=scale)
+    for B in (1, 8):
+        X = wl.swiglu(B, site.K, site.seed_test + B, BF16)
+        say(f"config5 expert down B={B}")
+        check_against_oracle(layer, X, BF16, m, tau, bf, what=f"cfg5 B={B}")
+
+
+# ------------------------------------------------------------------ fold_bias, dense, calibrate
+@pytest.mark.parametrize("dt,K,N", [(F16, 1024, 4096), (BF16, 11008, 4096), (BF16, 333, 1544)])
+def test_fold_bias(dt, K, N):
+    W = wl.weights(K, N, 701, dt)
+    layer = Layer(W, dt, B=1)
+    bias = np.random.default_rng(702).standard_normal(N).astype(np.float32)
+    for m, b in ((0.1, bias), (-3.7, None)):
+        say(f"fold_bias dt={dt} K={K} N={N} m={m}")
+        got = scap.fold_bias(layer.W, m, f32_dev(b), workspace=layer.ws)
+        torch.cuda.synchronize()
+        want = oracle.fold_bias(W, m, b, dt)
+        assert np.abs(got.cpu().numpy() - want).max() <= 2e-5 * max(1.0, abs(m) * math.sqrt(K) * 0.02 * 50)
+
+
+@pytest.mark.parametrize("dt,K,N,B", [(F16, 1024, 4096, 1), (BF16, 4096, 6144, 1), (BF16, 999, 1032, 5)])
+def test_dense_fc(dt, K, N, B):
+    W = wl.weights(K, N, 801, dt)
+    layer = Layer(W, dt, B=16)
+    X = wl.prenorm(B, K, 802, dt, chan_seed=803)
+    bias = np.random.default_rng(804).standard_normal(N).astype(np.float32)
+    say(f"dense dt={dt} K={K} N={N} B={B}")
+    y = scap.dense_fc(layer.W, to_dev(X, dt), f32_dev(bias), workspace=layer.ws)
+    torch.cuda.synchronize()
+    assert_y_close(y.cpu().numpy(), oracle.dense_fc(W, X, bias, dt, dt), "dense")
+
+
+@pytest.mark.parametrize("cfg,which", [(1, 0), (2, 0), (2, 1)])
+def test_calibrate_matches_oracle_bit_for_bit(cfg, which):
+    site = wl.sites(cfg)[which]
+    X = site.calib()
+    Xd = to_dev(X, site.xdt)
+    ws = scap.Workspace(site.K, 0, X.shape[0])
+    for est in ("zero", "median", "hist", "mean"):
+        for s in (0.0, 0.5, 0.7, 0.9):
+            say(f"calibrate {site.name} est={est} s={s}")
+            m_g, t_g = scap.calibrate(Xd, s, oracle.EST[est], workspace=ws)
+            m_o, t_o = oracle.calibrate(X, site.xdt, s, oracle.EST[est])
+            if est == "mean":
+                assert abs(m_g - m_o) <= abs(m_o) * 2 ** -22 + 1e-9
+                assert abs(t_g - t_o) <= 1e-5
+            else:
+                assert m_g == m_o, f"{est}: m {m_g} vs {m_o}"
+                assert t_g == t_o, f"{est}: tau {t_g} vs {t_o}"
+
+
+def test_calibrate_odd_count_and_small_sample():
+    X = wl.laplace(3, 333, 901, F16, loc=-0.4, scale=0.2)
+    Xd = to_dev(X, F16)
+    ws = scap.Workspace(333, 0, 3)
+    for est in ("median", "zero"):
+        for s in (0.001, 0.25, 0.999):
+            say(f"calibrate odd est={est} s={s}")
+            assert scap.calibrate(Xd, s, oracle.EST[est], workspace=ws) == oracle.calibrate(X, F16, s, oracle.EST[est])
