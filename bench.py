@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-time sparse FC (SCAP Alg. 3) on one MI355X.
+
+A step is one pass of the whole hot path -- centre, threshold, compact, gathered GEMV, reduction --
+for one token through one layer: a single `scap_sparse_fc` launch.  The headline workload is the
+Mistral-7B down projection (14336 -> 4096, bf16, batch 1) at 50 % target sparsity on SiLU(g)*u
+inputs; the same run also reports 70 % / 90 %, the dense GEMV on the same kernels, a streaming-read
+ceiling, and the CPU oracle on the host cores.
+
+Timing protocol: weights rotate through R distinct device copies (R * bytes >= 1 GiB) so that neither
+L2 nor the memory-side cache serves them; the 64 seeded test vectors cycle, so masks differ from
+launch to launch; the K timed launches are captured once into a HIP graph and replayed, which keeps
+the Python/ctypes call overhead out of the timed region (use --eager to time direct calls).
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known
+# size), keyed by workload; filled in from the summaries under profiles/.  None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes(nnz_rows: float, K: int, N: int, B: int, wbytes: int) -> float:
+    """Weight rows actually read + input + fused bias + output (index lists and split-K partials are
+    overhead, not algorithmic traffic)."""
+    return nnz_rows * N * wbytes + B * K * 2 + N * 4 + B * N * 4
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--eager", action="store_true", help="time direct calls instead of a HIP graph replay")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-sweep", action="store_true", help="only the headline point")
+    ap.add_argument("--cfg", type=str, default="", help="launch shape waves,rows,unroll (tuning)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2412_07174_amd as scap
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = tuple(int(v) for v in args.cfg.split(",")) if args.cfg else None
+
+    site = wl.sites(4)[1]  # mistral_down: 14336 -> 4096, bf16, SiLU(g)*u inputs
+    K, N = site.K, site.N
+    W_host = site.make_weights()
+    X_host = site.test_vectors(64)
+    calib_host = site.calib()
+
+    def dev16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    W0 = dev16(W_host)
+    wbytes_total = W0.numel() * 2
+    R = max(2, -(-(1 << 30) // wbytes_total))
+    Ws = [W0] + [W0.clone() for _ in range(R - 1)]
+    X = dev16(X_host)
+    calib = dev16(calib_host)
+    ws = scap.Workspace(K, N, 1)
+    ws_cal = scap.Workspace(K, 0, calib.shape[0])
+    y = torch.empty((1, N), dtype=torch.float32, device=dev)
+    nnz_buf = torch.zeros(64, dtype=torch.int32, device=dev)
+
+    # offline part through the library: (m, tau) per target, fused bias
+    layer = {}
+    for s in site.targets:
+        m, tau = scap.calibrate(calib, s, scap.MODE_MEDIAN, workspace=ws_cal)
+        bf = scap.fold_bias(W0, m, None, workspace=ws)
+        layer[s] = (m, tau, bf)
+    torch.cuda.synchronize()
+
+    def measured_nnz(s):
+        m, tau, bf = layer[s]
+        for i in range(64):
+            scap.sparse_fc(Ws[0], X[i], m, tau, bf, y=y, nnz_out=nnz_buf[i:i + 1], workspace=ws, cfg=cfg)
+        torch.cuda.synchronize()
+        return nnz_buf.cpu().numpy().astype(np.float64)
+
+    def launcher(s):
+        if s is None:
+            return lambda i: scap.dense_fc(Ws[i % R], X[i % 64], None, y=y, workspace=ws, cfg=cfg)
+        m, tau, bf = layer[s]
+        return lambda i: scap.sparse_fc(Ws[i % R], X[i % 64], m, tau, bf, y=y, workspace=ws, cfg=cfg)
+
+    def time_steps(fn, steps, warmup):
+        """Returns (wall ms per step, event ms per step) over exactly `steps` launches."""
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if args.eager:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            for i in range(steps):
+                fn(warmup + i)
+            e1.record()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        else:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):  # the binding launches on torch's current (capture) stream
+                for i in range(steps):
+                    fn(warmup + i)
+            g.replay()  # untimed replay: uploads the graph
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    # ---- headline: 50 % target sparsity
+    s_head = 0.5
+    nnz_head = measured_nnz(s_head)
+    wall_ms, ev_ms = time_steps(launcher(s_head), args.steps, args.warmup)
+    mean_nnz = float(nnz_head.mean())
+    abytes = algorithmic_bytes(mean_nnz, K, N, 1, 2)
+    gbs = abytes / (ev_ms * 1e-3) / 1e9
+
+    sweep = []
+    read_ceiling = None
+    if not args.no_sweep:
+        sub_steps = max(200, args.steps // 4)
+        for s in (None, 0.5, 0.7, 0.9):
+            nn = float(K) if s is None else float(measured_nnz(s).mean())
+            w_ms, e_ms = time_steps(launcher(s), sub_steps, 50)
+            ab = algorithmic_bytes(nn, K, N, 1, 2)
+            sweep.append({"target_sparsity": s, "density": round(nn / K, 4), "us": round(e_ms * 1e3, 3),
+                          "GBps": round(ab / (e_ms * 1e-3) / 1e9, 1),
+                          "frac_of_8TBps": round(ab / (e_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+        # streaming-read ceiling of this machine: read the R weight copies once per launch
+        chk = torch.zeros(2048, dtype=torch.int32, device=dev)
+        w_ms, e_ms = time_steps(lambda i: scap.read_probe(Ws[i % R], chk), sub_steps, 50)
+        read_ceiling = round(wbytes_total / (e_ms * 1e-3) / 1e9, 1)
+        # latency vs density: t = t0 + rho * t1
+        rho = np.array([r["density"] for r in sweep])
+        tt = np.array([r["us"] for r in sweep])
+        A = np.stack([np.ones_like(rho), rho], axis=1)
+        coef, res, *_ = np.linalg.lstsq(A, tt, rcond=None)
+        ss_tot = float(((tt - tt.mean()) ** 2).sum())
+        r2 = 1.0 - float(((A @ coef - tt) ** 2).sum()) / ss_tot if ss_tot > 0 else 1.0
+        fit = {"t0_us": round(float(coef[0]), 3), "t1_us": round(float(coef[1]), 3), "r2": round(r2, 5)}
+    else:
+        fit = None
+
+    # ---- CPU oracle on the host cores (baseline, not the target)
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        m, tau, bf = layer[s_head]
+        bf_host = bf.cpu().numpy()
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        n1, t0 = 0, time.perf_counter()
+        while n1 < 64 and time.perf_counter() - t0 < 6.0:
+            oracle.sparse_fc(W_host, X_host[n1], m, tau, bf_host, site.wdt, site.xdt, nthreads=1)
+            n1 += 1
+        us_1 = (time.perf_counter() - t0) / n1 * 1e6
+        nm, t0 = 0, time.perf_counter()
+        while nm < 256 and time.perf_counter() - t0 < 10.0:
+            oracle.sparse_fc(W_host, X_host[nm % 64], m, tau, bf_host, site.wdt, site.xdt, nthreads=cores)
+            nm += 1
+        us_m = (time.perf_counter() - t0) / nm * 1e6
+        cpu = {"value": round(us_m, 1), "unit": "us/token", "cores": cores, "kind": "oracle",
+               "sample": f"{nm} tokens of the headline workload, output columns split over {cores} threads; "
+                         f"single thread: {round(us_1, 1)} us/token over {n1} tokens",
+               "single_thread_us": round(us_1, 1)}
+
+    workload = "mistral7b_down_14336x4096_bf16_b1_s50"
+    out = {
+        "metric": "sparse_fc_us_per_token",
+        "value": round(wall_ms * 1e3, 3),
+        "unit": "us/token",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": workload, "K": K, "N": N, "batch": 1, "target_sparsity": s_head,
+                   "measured_density": round(mean_nnz / K, 4), "weight_copies_rotated": R,
+                   "launch": "eager" if args.eager else "hipgraph", "launch_cfg": args.cfg or "default"},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(workload),
+                     "kernel": "scap::gemv_kernel<bf16>", "us_per_launch": round(ev_ms * 1e3, 3),
+                     "algorithmic_bytes_per_launch": int(abytes)},
+        "cpu_baseline": cpu,
+        "sweep": sweep,
+        "read_ceiling_GBps": read_ceiling,
+        "latency_vs_density_fit": fit,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

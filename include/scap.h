@@ -88,9 +88,9 @@ int scap_version(void);
 size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B);
 
 /*
- * ASYNC.  Prepares a freshly allocated workspace (clears its counters with a fill kernel).  Must be
- * called once before the workspace is first used, and again after any call that failed with
- * SCAP_ERR_HIP.
+ * ASYNC.  Prepares a freshly allocated workspace: clears its arrival counters with a fill kernel.
+ * Must be called once before the workspace is first used, and again after any call that failed
+ * with SCAP_ERR_HIP.
  *   workspace  DEVICE, 16-byte aligned, workspace_bytes >= 4096.
  */
 int scap_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
@@ -131,7 +131,7 @@ int scap_fold_bias(const void* W, const void* col_scale, int64_t K, int64_t N, i
  *   b_fused        DEVICE  fp32 [N] from scap_fold_bias, or NULL (= zeros).
  *   y              DEVICE  fp32 [B, N]; fully overwritten.
  *   idx_out        DEVICE  int32 [B, K] or NULL: token b's kept channels, ascending, in
- *                          idx_out[b*K .. b*K + nnz_out[b]); entries past nnz are left untouched.
+ *                          idx_out[b*K .. b*K + nnz_out[b]); entries past nnz are unspecified.
  *   nnz_out        DEVICE  int32 [B] or NULL (required when idx_out is given).
  *   union_nnz_out  DEVICE  int32 [1] or NULL: number of distinct weight rows read (union of the B
  *                          masks, Appendix C; equals nnz_out[0] for B = 1).
@@ -161,9 +161,11 @@ int scap_dense_fc(const void* W, const void* col_scale, int64_t K, int64_t N, in
                   const scap_launch_cfg* cfg);
 
 /*
- * ASYNC.  Streaming-read probe used to measure the HBM read ceiling of the box: sums `bytes` bytes at
- * `src` (DEVICE, 16-byte aligned, bytes a multiple of 16) into out[0] (DEVICE, uint32 checksum).
+ * ASYNC.  Streaming-read probe used to measure the HBM read ceiling of the box: reads `bytes` bytes at
+ * `src` (DEVICE, 16-byte aligned, bytes a multiple of 16) with 2048 workgroups and stores one uint32
+ * checksum per workgroup to out (DEVICE, uint32 [SCAP_PROBE_SLOTS]).
  */
+#define SCAP_PROBE_SLOTS 2048
 int scap_read_probe(const void* src, size_t bytes, uint32_t* out, void* stream);
 
 #ifdef __cplusplus

@@ -115,8 +115,8 @@ def _cfg(cfg):
         return None
     if isinstance(cfg, LaunchCfg):
         return ctypes.byref(cfg)
-    waves, rows, unroll = cfg
-    return ctypes.byref(LaunchCfg(int(waves), int(rows), int(unroll), 0))
+    waves, rows, unroll, *rest = cfg
+    return ctypes.byref(LaunchCfg(int(waves), int(rows), int(unroll), int(rest[0]) if rest else 0))
 
 
 class Workspace:

@@ -31,12 +31,11 @@ int check_workspace(void* ws, size_t bytes, int64_t K, int64_t N, int64_t B) {
     return SCAP_OK;
 }
 
-void fill_workspace_ptrs(GemvArgs& a, void* ws, int64_t K, int64_t B) {
+void fill_workspace_ptrs(GemvArgs& a, void* ws) {
     char* base = static_cast<char*>(ws);
     a.counters = reinterpret_cast<int32_t*>(base + kOffCounters);
     a.seg_cnt = reinterpret_cast<int32_t*>(base + kOffSegCnt);
-    a.seg_idx = reinterpret_cast<int32_t*>(base + kOffSegIdx);
-    a.partial = reinterpret_cast<float*>(base + kOffSegIdx + seg_idx_bytes(K, B));
+    a.partial = reinterpret_cast<float*>(base + kOffPartial);
 }
 
 int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
@@ -77,7 +76,7 @@ int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t
     a.xdt = xdt;
     a.m = m;
     a.tau = tau;
-    fill_workspace_ptrs(a, workspace, K, B);
+    fill_workspace_ptrs(a, workspace);
     return launch_gemv(a, wdt, cfg, static_cast<hipStream_t>(stream));
 }
 
@@ -107,14 +106,14 @@ size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B) {
     if (K < 1 || N < 0 || B < 1) return 0;
     if (N == 0) return kOffSegCnt;  // calibration only uses the fixed header
     if (K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19) || B > SCAP_MAX_TOKENS) return 0;
-    return kOffSegIdx + seg_idx_bytes(K, B) + 4 * (size_t)B * partial_capacity(N);
+    return kOffPartial + 4 * (size_t)B * partial_capacity(N);
 }
 
 int scap_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
     if (!workspace) return SCAP_ERR_WORKSPACE;
     if (!aligned16(workspace)) return SCAP_ERR_ALIGN;
     if (workspace_bytes < 4096) return SCAP_ERR_WORKSPACE;
-    return launch_zero_words(static_cast<int32_t*>(workspace), kMaxTiles, static_cast<hipStream_t>(stream));
+    return launch_workspace_init(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 int scap_calibrate(const void* X_calib, int64_t n, int64_t K, int xdt, float target_sparsity, int est, float* m_out,

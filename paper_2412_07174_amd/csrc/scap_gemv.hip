@@ -11,13 +11,51 @@
 //   3. the wavefronts' sums are added through LDS and stored as one split-K partial;
 //   4. the last workgroup to arrive at a tile (device-scope counter) adds the S partials in split order
 //      -- a fixed order, so y is bit-reproducible -- plus the fused bias, and resets the counter.
-// The last arrival of tile 0 also concatenates the per-split index lists into idx_out / nnz_out.
+// The last arrival of tile 0 also closes the gaps between the per-split index lists that the splits
+// left in idx_out, and writes nnz_out.
 #include "scap_device.hpp"
 #include "scap_internal.hpp"
 
 namespace scap {
 
 constexpr int kHdrBytes = 2048;  // LDS header: per-wave counts + flags
+
+// Data handed from one workgroup to another inside a launch (split-K partials, per-split index lists,
+// arrival counters) bypasses the non-coherent cache levels: device-scope relaxed atomics for single
+// words, buffer loads/stores with the device-coherent cache policy for the 16-byte partial sums.
+// Such stores write through to the device's coherence point and such loads read from it, so no
+// workgroup has to write back or invalidate its whole L2 -- on an 8-XCD part one device-scope fence
+// per workgroup costs several times the GEMV itself.  A compute unit pulls coherent data at only a few
+// tens of GB/s, so these accesses are kept few and wide.
+// Ordering: every thread waits until its own stores are acknowledged (s_waitcnt vmcnt(0)), the workgroup
+// barriers, then one thread takes the arrival ticket; the last arrival barriers again before anyone
+// reads.
+
+constexpr int kAuxDeviceCoherent = 1 << 4;  // "sc1" bit of the buffer cache policy
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_raw_buffer(void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, float4 v) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t t = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)byte_off, 0, kAuxDeviceCoherent);
+}
+__device__ __forceinline__ float4 load_coherent16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+    const auto t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kAuxDeviceCoherent);
+    return make_float4(__uint_as_float(t[0]), __uint_as_float(t[1]), __uint_as_float(t[2]), __uint_as_float(t[3]));
+}
+// all of this thread's earlier memory operations have completed
+__device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <typename T>
+__device__ __forceinline__ void store_dev(T* p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T load_dev(const T* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // 16 bytes of weight row `row` at this lane's columns.  `row` is wave-uniform, so the row base is
 // formed on the scalar unit and the load takes a scalar base plus a 32-bit lane offset.
@@ -148,26 +186,26 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
                 s_idx[pos] = k;
 #pragma unroll
                 for (int b = 0; b < BT; ++b) s_d[b * a.Kc + pos] = keep[b] ? d[b] : 0.f;
-                if (BT == 1 && want_idx) a.seg_idx[k0 + pos] = k;
+                if (BT == 1 && want_idx) store_dev(&a.idx_out[k0 + pos], k);
             }
             ubase += __popcll(ub);
             if (BT > 1 && per_token) {
 #pragma unroll
                 for (int b = 0; b < BT; ++b) {
                     const uint64_t tb = __ballot(keep[b]);
-                    if (want_idx && keep[b]) a.seg_idx[(int64_t)b * a.K + k0 + tbase[b] + lanes_below(tb)] = k;
+                    if (want_idx && keep[b]) store_dev(&a.idx_out[(int64_t)b * a.K + k0 + tbase[b] + lanes_below(tb)], k);
                     tbase[b] += __popcll(tb);
                 }
             }
         }
         if (tile == 0 && tid == 0) {
-            a.seg_cnt[a.B * a.S + split] = cnt;  // union
+            store_dev(&a.seg_cnt[a.B * a.S + split], cnt);  // union
             if (BT == 1) {
-                a.seg_cnt[split] = cnt;
+                store_dev(&a.seg_cnt[split], cnt);
             } else if (per_token) {
 #pragma unroll
                 for (int b = 0; b < BT; ++b)
-                    if (b < a.B) a.seg_cnt[b * a.S + split] = ttotal[b];
+                    if (b < a.B) store_dev(&a.seg_cnt[b * a.S + split], ttotal[b]);
             }
         }
     }
@@ -224,6 +262,28 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
     }
 
     // ------------------------------------------------------------------ 3. add the wavefronts' sums
+    constexpr int GROUPS = TILE / 4;  // 4-column groups of a tile
+    auto finish_columns = [&](int b, int g, float4 s) {  // scale, add the fused bias, store y
+        const int col = tile * TILE + 4 * g;
+        if (col >= a.N) return;  // N is a multiple of 8: a group is inside or outside as a whole
+        if (WDT == kI8) {
+            s.x *= f16_bits_to_f32(a.col_scale[col]);
+            s.y *= f16_bits_to_f32(a.col_scale[col + 1]);
+            s.z *= f16_bits_to_f32(a.col_scale[col + 2]);
+            s.w *= f16_bits_to_f32(a.col_scale[col + 3]);
+        }
+        if (a.bias) {
+            const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
+            s.x += bv.x;
+            s.y += bv.y;
+            s.z += bv.z;
+            s.w += bv.w;
+        }
+        *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
+    };
+
+    // split-K partials of this call: [B][S][T][TILE] floats, addressed by byte offset
+    const __amdgpu_buffer_rsrc_t pbuf = make_raw_buffer(a.partial, (uint32_t)a.B * a.S * a.T * TILE * 4u);
     __syncthreads();  // the list is no longer needed; its LDS becomes the reduction buffer
 #pragma unroll
     for (int b = 0; b < BT; ++b) {
@@ -233,54 +293,94 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
             for (int j = 0; j < ELEMS / 4; ++j)
                 dst[j] = make_float4(acc[b][4 * j], acc[b][4 * j + 1], acc[b][4 * j + 2], acc[b][4 * j + 3]);
             __syncthreads();
-            for (int c = tid; c < TILE; c += NT) {
-                float s = 0.f;
+            for (int g = tid; g < GROUPS; g += NT) {
+                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                for (int i = 0; i < WAVES; ++i) s += s_red[i * TILE + c];
-                const int col = tile * TILE + c;
-                if (a.S == 1) {
-                    if (col < a.N) {
-                        if (WDT == kI8) s *= f16_bits_to_f32(a.col_scale[col]);
-                        a.y[(int64_t)b * a.N + col] = (a.bias ? a.bias[col] : 0.f) + s;
-                    }
-                } else {
-                    a.partial[(((int64_t)b * a.S + split) * a.T + tile) * TILE + c] = s;
+                for (int i = 0; i < WAVES; ++i) {
+                    const float4 v = *reinterpret_cast<const float4*>(s_red + i * TILE + 4 * g);
+                    s.x += v.x;
+                    s.y += v.y;
+                    s.z += v.z;
+                    s.w += v.w;
                 }
+                if (a.S == 1)
+                    finish_columns(b, g, s);
+                else
+                    store_coherent16(pbuf, (uint32_t)((((b * a.S + split) * a.T + tile) * TILE + 4 * g) * 4), s);
             }
             __syncthreads();
         }
     }
 
     // ------------------------------------------------------------------ 4. last arrival finishes the tile
-    bool last = true;
+    const bool wants_lists = tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr || a.union_nnz_out != nullptr);
     if (a.S > 1) {
-        __threadfence();  // partials and segment lists visible device-wide before the arrival count
+        wait_memory_ops();  // my coherent stores have been acknowledged
         __syncthreads();
         if (tid == 0) {
-            const int old = atomicAdd(&a.counters[tile], 1);
+            const int old = __hip_atomic_fetch_add(&a.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_flag[0] = (old == a.S - 1);
         }
         __syncthreads();
-        last = s_flag[0] != 0;
-        if (!last) return;
-        __threadfence();
+        if (s_flag[0] == 0) return;
+        // The S partials of a 4-column group are shared out over Q threads (splits q, q+Q, ...), each adds
+        // its share in ascending split order, then the Q shares are added in ascending q: a fixed
+        // association, so y does not depend on which workgroup arrived last or when.
+        constexpr int Q = (NT / GROUPS) > 0 ? (NT / GROUPS) : 1;
+        constexpr int PASSES = (GROUPS + NT - 1) / NT;  // > 1 only when a workgroup has fewer threads than groups
+        const uint32_t pstride = (uint32_t)a.T * TILE * 4u;  // bytes between consecutive splits
         for (int b = 0; b < a.B; ++b) {
-            for (int c = tid; c < TILE; c += NT) {
-                const int col = tile * TILE + c;
-                if (col >= a.N) continue;
-                float s = 0.f;
-                for (int sp = 0; sp < a.S; ++sp) s += a.partial[(((int64_t)b * a.S + sp) * a.T + tile) * TILE + c];
-                if (WDT == kI8) s *= f16_bits_to_f32(a.col_scale[col]);
-                a.y[(int64_t)b * a.N + col] = (a.bias ? a.bias[col] : 0.f) + s;
+#pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass) {
+                const int g = (tid % GROUPS) + pass * NT;
+                const int q = (PASSES > 1) ? 0 : tid / GROUPS;
+                if (g < GROUPS && q < Q) {
+                    const uint32_t pc = (uint32_t)(((b * a.S * a.T + tile) * TILE + 4 * g) * 4);
+                    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int sp0 = q; sp0 < a.S; sp0 += 8 * Q) {  // 8 loads in flight
+                        float4 v[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int sp = sp0 + j * Q;
+                            v[j] = sp < a.S ? load_coherent16(pbuf, pc + sp * pstride) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            s.x += v[j].x;
+                            s.y += v[j].y;
+                            s.z += v[j].z;
+                            s.w += v[j].w;
+                        }
+                    }
+                    *reinterpret_cast<float4*>(s_red + q * TILE + 4 * g) = s;
+                }
             }
+            __syncthreads();
+            for (int g = tid; g < GROUPS; g += NT) {
+                float4 s = *reinterpret_cast<const float4*>(s_red + 4 * g);
+#pragma unroll
+                for (int q = 1; q < Q; ++q) {
+                    const float4 v = *reinterpret_cast<const float4*>(s_red + q * TILE + 4 * g);
+                    s.x += v.x;
+                    s.y += v.y;
+                    s.z += v.z;
+                    s.w += v.w;
+                }
+                finish_columns(b, g, s);
+            }
+            __syncthreads();
         }
-        if (tid == 0) a.counters[tile] = 0;  // ready for the next call
+        if (tid == 0) store_dev(&a.counters[tile], 0);  // ready for the next call
     }
 
     // ------------------------------------------------------------------ index lists (tile 0 only)
-    if (tile != 0 || (a.nnz_out == nullptr && a.idx_out == nullptr && a.union_nnz_out == nullptr)) return;
+    if (!wants_lists) return;
+    // Each split left its ascending list in place at idx_out[b*K + split*Kc ...]; close the gaps.
+    // Every entry moves left or stays, so reading a block of source positions, synchronising, then
+    // writing it, block after block from the left, never overwrites an entry that is still to be read.
     __syncthreads();
-    int* s_off = s_idx;  // [S] exclusive offsets; S <= 256 fits in the header-adjacent space
+    int* s_off = s_idx;               // [S] exclusive offsets
+    int* s_cnt = s_idx + kMaxSplits;  // [S] counts
     const int nlist = a.B + 1;
     for (int l = 0; l < nlist; ++l) {
         const bool is_union = l == a.B;
@@ -292,9 +392,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
             int run = 0;
             for (int s0 = 0; s0 < a.S; s0 += kWave) {
                 const int sp = s0 + lane;
-                const int v = sp < a.S ? a.seg_cnt[(is_union ? a.B : src_l) * a.S + sp] : 0;
+                const int v = sp < a.S ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.S + sp]) : 0;
                 const int inc = wave_inclusive_scan(v);
-                if (sp < a.S) s_off[sp] = run + inc - v;
+                if (sp < a.S) {
+                    s_off[sp] = run + inc - v;
+                    s_cnt[sp] = v;
+                }
                 run += __shfl(inc, kWave - 1, kWave);
             }
             if (lane == 0) {
@@ -305,13 +408,30 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
             }
         }
         __syncthreads();
-        if (!is_union && a.idx_out != nullptr) {
-            for (int sp = w; sp < a.S; sp += WAVES) {
-                const int n = a.seg_cnt[src_l * a.S + sp];
-                const int off = s_off[sp];
-                const int32_t* src = a.seg_idx + (int64_t)src_l * a.K + (int64_t)sp * a.Kc;
-                int32_t* dst = a.idx_out + (int64_t)l * a.K + off;
-                for (int j = lane; j < n; j += kWave) dst[j] = src[j];
+        if (!is_union && a.idx_out != nullptr && a.S > 1) {
+            int32_t* base = a.idx_out + (int64_t)l * a.K;
+            constexpr int PER = 16;
+            for (int c0 = 0; c0 < a.K; c0 += NT * PER) {
+                int vals[PER], dsts[PER];
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    const int p = c0 + j * NT + tid;
+                    dsts[j] = -1;
+                    vals[j] = 0;
+                    if (p < a.K) {
+                        const int seg = p / a.Kc;
+                        const int r = p - seg * a.Kc;
+                        if (r < s_cnt[seg]) {
+                            vals[j] = load_dev(&base[p]);
+                            dsts[j] = s_off[seg] + r;
+                        }
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < PER; ++j)
+                    if (dsts[j] >= 0) base[dsts[j]] = vals[j];
+                __syncthreads();
             }
         }
     }
@@ -324,7 +444,7 @@ static int launch_one(const GemvArgs& a, hipStream_t stream) {
     constexpr int TILE = kWave * ELEMS;
     const size_t list_bytes = (size_t)a.Kc * 4 * (1 + BT);
     const size_t red_bytes = (size_t)WAVES * TILE * 4;
-    const size_t off_bytes = (size_t)kMaxSplits * 4;
+    const size_t off_bytes = (size_t)kMaxSplits * 8;
     size_t body = list_bytes > red_bytes ? list_bytes : red_bytes;
     if (body < off_bytes) body = off_bytes;
     const size_t lds = kHdrBytes + body;
@@ -385,8 +505,9 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (a.T > kMaxTiles) return SCAP_ERR_SHAPE;
 
     if (kc == 0) {
-        // enough workgroups to put about two on every compute unit, at least 128 rows each
-        const int want_groups = 512;
+        // about one workgroup per compute unit (256): more splits only lengthen the final reduction,
+        // fewer leave compute units -- each limited to ~100 GB/s of misses -- without work
+        const int want_groups = 256;
         int s = (want_groups + a.T - 1) / a.T;
         if (s < 1) s = 1;
         kc = (int)align_up((size_t)((a.K + s - 1) / s), kWave);
@@ -422,20 +543,32 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
 }
 
 // ---------------------------------------------------------------------------------------------- helpers
-__global__ void zero_words_kernel(int32_t* p, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0;
+__global__ void fill_words_kernel(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
 
-int launch_zero_words(int32_t* p, size_t n, hipStream_t stream) {
+static int launch_fill_words(uint32_t* p, size_t n, uint32_t v, hipStream_t stream) {
     if (n == 0) return SCAP_OK;
     size_t blocks = (n + 255) / 256;
-    if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, n);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, n, v);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
-// Streaming read of `nvec` 16-byte vectors; a checksum keeps the loads alive.
+int launch_zero_words(int32_t* p, size_t n, hipStream_t stream) {
+    return launch_fill_words(reinterpret_cast<uint32_t*>(p), n, 0u, stream);
+}
+
+int launch_workspace_init(void* workspace, size_t bytes, hipStream_t stream) {
+    // the fixed header holds the arrival counters, calibration scratch and segment counts
+    const size_t head = bytes < kOffPartial ? bytes : kOffPartial;
+    return launch_fill_words(static_cast<uint32_t*>(workspace), head / 4, 0u, stream);
+}
+
+// Streaming read of `nvec` 16-byte vectors; a per-workgroup checksum keeps the loads alive.
+constexpr int kProbeGroups = 2048;
 __global__ __launch_bounds__(512) void read_probe_kernel(const uint4* __restrict__ src, size_t nvec, uint32_t* out) {
+    __shared__ uint32_t sh[8];
     uint32_t acc = 0;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -451,13 +584,19 @@ __global__ __launch_bounds__(512) void read_probe_kernel(const uint4* __restrict
         acc += v.x ^ v.y ^ v.z ^ v.w;
     }
     acc = (uint32_t)wave_sum((int)acc);
-    if (lane_id() == 0 && acc != 0) atomicAdd(out, acc);
+    if (lane_id() == 0) sh[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int w = 0; w < 8; ++w) t += sh[w];
+        out[blockIdx.x] = t;
+    }
 }
 
 int launch_read_probe(const void* src, size_t bytes, uint32_t* out, hipStream_t stream) {
     const size_t nvec = bytes / 16;
-    hipLaunchKernelGGL(read_probe_kernel, dim3(256 * 8), dim3(512), 0, stream, reinterpret_cast<const uint4*>(src), nvec,
-                       out);
+    hipLaunchKernelGGL(read_probe_kernel, dim3(kProbeGroups), dim3(512), 0, stream, reinterpret_cast<const uint4*>(src),
+                       nvec, out);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 

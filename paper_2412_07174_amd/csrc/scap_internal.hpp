@@ -25,14 +25,13 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 //   [4096, 20480)        uint64 hist[2048]       calibration histograms
 //   [20480, 28672)       double sums[1024]       calibration partial sums
 //   [65536, +32768)      int32 seg_cnt[17][256]  kept-channel counts per (token | union, K split)
-//   [98304, +4*B*K)      int32 seg_idx[B][K]     per-split kept-channel lists (only for idx_out)
-//   [.., +4*B*cap)       float partial[B][S][T][tile]   split-K partial sums
+//   [98304, +4*B*cap)         float partial[B][S][T][tile]   split-K partial sums
 // ---------------------------------------------------------------------------------------------
 constexpr size_t kOffCounters = 0;
 constexpr size_t kOffHist = 4096;
 constexpr size_t kOffSums = 20480;
 constexpr size_t kOffSegCnt = 65536;
-constexpr size_t kOffSegIdx = 98304;
+constexpr size_t kOffPartial = 98304;
 constexpr int kMaxTiles = 1024;
 constexpr int kMaxSplits = 256;
 constexpr int kHistBins = 2048;
@@ -50,8 +49,6 @@ inline size_t partial_capacity(int64_t N) {
     return cap > ((size_t)1 << 20) ? cap : ((size_t)1 << 20);
 }
 
-inline size_t seg_idx_bytes(int64_t K, int64_t B) { return align_up((size_t)K * (size_t)B * 4, 256); }
-
 struct GemvArgs {
     const void* W;
     const uint16_t* col_scale;
@@ -63,7 +60,6 @@ struct GemvArgs {
     int32_t* union_nnz_out;
     int32_t* counters;
     int32_t* seg_cnt;
-    int32_t* seg_idx;
     float* partial;
     int K, N, B, Kc, S, T, mode, xdt;
     float m, tau;
@@ -74,6 +70,9 @@ int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStrea
 
 // Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).
 int launch_zero_words(int32_t* p, size_t n, hipStream_t stream);
+
+// Zero the fixed header of a workspace (arrival counters, calibration scratch, segment counts).
+int launch_workspace_init(void* workspace, size_t bytes, hipStream_t stream);
 
 int launch_read_probe(const void* src, size_t bytes, uint32_t* out, hipStream_t stream);
 
