@@ -31,7 +31,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known
 # size), keyed by workload; filled in from the summaries under profiles/.  None = not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/gemv_kernel_bf16_mistral_down_hbm_traffic.txt
+    "mistral7b_down_14336x4096_bf16_b1_s50": 60125769,
+}
 
 
 def algorithmic_bytes(nnz_rows: float, K: int, N: int, B: int, wbytes: int) -> float:
@@ -49,6 +52,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sweep", action="store_true", help="only the headline point")
     ap.add_argument("--cfg", type=str, default="", help="launch shape waves,rows,unroll (tuning)")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="for rocprofv3 --pmc runs: a few eager launches of a copy of known size, the headline "
+                         "sparse FC and the dense FC, then exit (no timing, no JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -107,6 +113,23 @@ def main() -> int:
             return lambda i: scap.dense_fc(Ws[i % R], X[i % 64], None, y=y, workspace=ws, cfg=cfg)
         m, tau, bf = layer[s]
         return lambda i: scap.sparse_fc(Ws[i % R], X[i % 64], m, tau, bf, y=y, workspace=ws, cfg=cfg)
+
+    if args.counter_pass:
+        # reference for scaling the byte counters: torch copies W (reads and writes wbytes_total each)
+        dst = torch.empty_like(W0)
+        for i in range(10):
+            dst.copy_(Ws[i % R])
+        torch.cuda.synchronize()
+        fn_s, fn_d = launcher(0.5), launcher(None)
+        for i in range(50):
+            fn_s(i)
+        torch.cuda.synchronize()
+        for i in range(20):
+            fn_d(i)
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_pass": True, "copy_bytes_each_way": wbytes_total,
+                          "sparse_launches": 50, "dense_launches": 20}))
+        return 0
 
     def time_steps(fn, steps, warmup):
         """Returns (wall ms per step, event ms per step) over exactly `steps` launches."""
