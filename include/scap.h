@@ -71,7 +71,8 @@ typedef struct {
     int32_t waves_per_group; /* 4, 8 or 16 wavefronts per workgroup */
     int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */
     int32_t unroll;          /* weight rows in flight per wavefront: 4, 8 or 16 */
-    int32_t reserved;
+    int32_t lanes_per_row;   /* lanes sharing one weight row per load: 64 or 32 (column tile =
+                                lanes_per_row x 8 columns, x 16 for int8); batch > 1 supports 64 only */
 } scap_launch_cfg;
 
 /* Static, NUL-terminated description of a status code.  Never freed. */

@@ -30,7 +30,7 @@ class ScapError(RuntimeError):
 
 class LaunchCfg(ctypes.Structure):
     _fields_ = [("waves_per_group", ctypes.c_int32), ("rows_per_group", ctypes.c_int32),
-                ("unroll", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("unroll", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32)]
 
 
 _lib = None

@@ -72,10 +72,14 @@ __device__ __forceinline__ uint4 load_row_vec(const char* __restrict__ wbase, ui
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-template <int WDT, int WAVES, int UNROLL, int BT>
+// LPR = lanes that share one weight row: 64 (a wavefront reads 1 KB of one row per load) or 32 (it reads
+// 512 bytes of each of 2 rows).  Fewer lanes per row make the column tile narrower, so the same
+// number of workgroups needs fewer K splits and the final reduction reads less.
+template <int WDT, int WAVES, int UNROLL, int BT, int LPR>
 __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
     constexpr int ELEMS = Vec<WDT>::kElems;
-    constexpr int TILE = kWave * ELEMS;
+    constexpr int TILE = LPR * ELEMS;
+    constexpr int RPI = kWave / LPR;  // rows per load instruction
     constexpr int NT = WAVES * kWave;
 
     extern __shared__ uint4 smem_raw[];
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
     int* s_flag = s_hdr + (1 + BT) * WAVES;                 // [0] last-arrival flag
     int* s_idx = reinterpret_cast<int*>(smem + kHdrBytes);  // [Kc]
     float* s_d = reinterpret_cast<float*>(s_idx + a.Kc);    // [BT][Kc]
-    float* s_red = reinterpret_cast<float*>(smem + kHdrBytes);  // [WAVES][TILE], reuses the list space
+    float* s_red = reinterpret_cast<float*>(smem + kHdrBytes);  // [WAVES*RPI][TILE], reuses the list space
 
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
@@ -218,44 +222,79 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
 #pragma unroll
         for (int j = 0; j < ELEMS; ++j) acc[b][j] = 0.f;
 
-    const int col0 = tile * TILE + lane * ELEMS;
+    const int sub_row = lane / LPR;  // which of the RPI rows of a load this lane reads
+    const int col0 = tile * TILE + (lane % LPR) * ELEMS;
     const bool col_ok = col0 < a.N;
     const uint32_t lane_off = col_ok ? (uint32_t)col0 * Vec<WDT>::kBytes : 0u;
     const uint32_t row_bytes = (uint32_t)a.N * Vec<WDT>::kBytes;
     const char* wbase = reinterpret_cast<const char*>(a.W);
 
-    const int n_w = (cnt > w) ? (cnt - w + WAVES - 1) / WAVES : 0;  // entries w, w+WAVES, ...
-    for (int i0 = 0; i0 < n_w; i0 += kWave) {
-        const int e = w + WAVES * (i0 + lane);
-        const bool in = e < cnt;
-        const int vidx = in ? s_idx[e] : 0;
-        float vd[BT];
+    if constexpr (LPR == kWave) {
+        const int n_w = (cnt > w) ? (cnt - w + WAVES - 1) / WAVES : 0;  // entries w, w+WAVES, ...
+        for (int i0 = 0; i0 < n_w; i0 += kWave) {
+            const int e = w + WAVES * (i0 + lane);
+            const bool in = e < cnt;
+            const int vidx = in ? s_idx[e] : 0;
+            float vd[BT];
 #pragma unroll
-        for (int b = 0; b < BT; ++b) vd[b] = in ? s_d[b * a.Kc + e] : 0.f;
-        const int nb = min(kWave, n_w - i0);
-        for (int u = 0; u < nb; u += UNROLL) {
-            const int rem = nb - u;  // wave-uniform
-            // Issue UNROLL row loads together.  In a ragged last group the spare slots re-read the
-            // group's last row (same cache lines, no extra HBM traffic) and are not accumulated.
-            uint4 r[UNROLL];
-#pragma unroll
-            for (int q = 0; q < UNROLL; ++q) {
-                const uint32_t row = (uint32_t)__builtin_amdgcn_readlane(vidx, min(u + q, nb - 1));
-                r[q] = load_row_vec(wbase, row, row_bytes, lane_off);
-            }
-            if (rem >= UNROLL) {
+            for (int b = 0; b < BT; ++b) vd[b] = in ? s_d[b * a.Kc + e] : 0.f;
+            const int nb = min(kWave, n_w - i0);
+            for (int u = 0; u < nb; u += UNROLL) {
+                const int rem = nb - u;  // wave-uniform
+                // Issue UNROLL row loads together.  In a ragged last group the spare slots re-read the
+                // group's last row (same cache lines, no extra HBM traffic) and are not accumulated.
+                uint4 r[UNROLL];
 #pragma unroll
                 for (int q = 0; q < UNROLL; ++q) {
-#pragma unroll
-                    for (int b = 0; b < BT; ++b) fma_vec<WDT>(acc[b], r[q], read_lane_f(vd[b], u + q));
+                    const uint32_t row = (uint32_t)__builtin_amdgcn_readlane(vidx, min(u + q, nb - 1));
+                    r[q] = load_row_vec(wbase, row, row_bytes, lane_off);
                 }
-            } else {
+                if (rem >= UNROLL) {
 #pragma unroll
-                for (int q = 0; q < UNROLL - 1; ++q) {
-                    if (q < rem) {
+                    for (int q = 0; q < UNROLL; ++q) {
 #pragma unroll
                         for (int b = 0; b < BT; ++b) fma_vec<WDT>(acc[b], r[q], read_lane_f(vd[b], u + q));
                     }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < UNROLL - 1; ++q) {
+                        if (q < rem) {
+#pragma unroll
+                            for (int b = 0; b < BT; ++b) fma_vec<WDT>(acc[b], r[q], read_lane_f(vd[b], u + q));
+                        }
+                    }
+                }
+            }
+        }
+    } else {
+        // The list is consumed in blocks of RPI consecutive entries, blocks round-robin over the
+        // wavefronts; lane group `sub_row` of a wavefront takes entry sub_row of the block.  Lanes past
+        // the end of the list are masked off for the load and the accumulation alike.
+        const int n_blocks = (cnt + RPI - 1) / RPI;
+        const int n_w = (n_blocks > w) ? (n_blocks - w + WAVES - 1) / WAVES : 0;
+        for (int i0 = 0; i0 < n_w; i0 += UNROLL) {
+            uint4 r[UNROLL];
+            float dv[UNROLL][BT];
+            bool ok[UNROLL];
+#pragma unroll
+            for (int q = 0; q < UNROLL; ++q) {
+                const int e = (w + WAVES * (i0 + q)) * RPI + sub_row;
+                ok[q] = (i0 + q < n_w) && (e < cnt);
+                r[q] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) dv[q][b] = 0.f;
+                if (ok[q]) {
+                    const uint32_t row = (uint32_t)s_idx[e];
+                    r[q] = *reinterpret_cast<const uint4*>(wbase + (uint64_t)row * row_bytes + lane_off);
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) dv[q][b] = s_d[b * a.Kc + e];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < UNROLL; ++q) {
+                if (ok[q]) {
+#pragma unroll
+                    for (int b = 0; b < BT; ++b) fma_vec<WDT>(acc[b], r[q], dv[q][b]);
                 }
             }
         }
@@ -288,7 +327,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
 #pragma unroll
     for (int b = 0; b < BT; ++b) {
         if (b < a.B) {
-            float4* dst = reinterpret_cast<float4*>(s_red + w * TILE + lane * ELEMS);
+            // lane group sub_row of wavefront w holds the sums of row slot (w*RPI + sub_row)
+            float4* dst = reinterpret_cast<float4*>(s_red + (w * RPI + sub_row) * TILE + (lane % LPR) * ELEMS);
 #pragma unroll
             for (int j = 0; j < ELEMS / 4; ++j)
                 dst[j] = make_float4(acc[b][4 * j], acc[b][4 * j + 1], acc[b][4 * j + 2], acc[b][4 * j + 3]);
@@ -296,7 +336,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
             for (int g = tid; g < GROUPS; g += NT) {
                 float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                for (int i = 0; i < WAVES; ++i) {
+                for (int i = 0; i < WAVES * RPI; ++i) {
                     const float4 v = *reinterpret_cast<const float4*>(s_red + i * TILE + 4 * g);
                     s.x += v.x;
                     s.y += v.y;
@@ -318,7 +358,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
         wait_memory_ops();  // my coherent stores have been acknowledged
         __syncthreads();
         if (tid == 0) {
-            const int old = __hip_atomic_fetch_add(&a.counters[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int old = __hip_atomic_fetch_add(&a.counters[tile * kCounterStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_flag[0] = (old == a.S - 1);
         }
         __syncthreads();
@@ -370,7 +410,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
             }
             __syncthreads();
         }
-        if (tid == 0) store_dev(&a.counters[tile], 0);  // ready for the next call
+        if (tid == 0) store_dev(&a.counters[tile * kCounterStride], 0);  // ready for the next call
     }
 
     // ------------------------------------------------------------------ index lists (tile 0 only)
@@ -438,12 +478,11 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------- launch
-template <int WDT, int WAVES, int UNROLL, int BT>
+template <int WDT, int WAVES, int UNROLL, int BT, int LPR>
 static int launch_one(const GemvArgs& a, hipStream_t stream) {
     constexpr int ELEMS = Vec<WDT>::kElems;
-    constexpr int TILE = kWave * ELEMS;
     const size_t list_bytes = (size_t)a.Kc * 4 * (1 + BT);
-    const size_t red_bytes = (size_t)WAVES * TILE * 4;
+    const size_t red_bytes = (size_t)WAVES * kWave * ELEMS * 4;
     const size_t off_bytes = (size_t)kMaxSplits * 8;
     size_t body = list_bytes > red_bytes ? list_bytes : red_bytes;
     if (body < off_bytes) body = off_bytes;
@@ -451,37 +490,46 @@ static int launch_one(const GemvArgs& a, hipStream_t stream) {
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
     const dim3 grid((unsigned)(a.S * a.T));
     const dim3 block(WAVES * kWave);
-    hipLaunchKernelGGL((gemv_kernel<WDT, WAVES, UNROLL, BT>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((gemv_kernel<WDT, WAVES, UNROLL, BT, LPR>), grid, block, lds, stream, a);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
+template <int WDT, int WAVES, int UNROLL>
+static int launch_lpr(const GemvArgs& a, int lpr, hipStream_t stream) {
+    switch (lpr) {
+        case 64: return launch_one<WDT, WAVES, UNROLL, 1, 64>(a, stream);
+        case 32: return launch_one<WDT, WAVES, UNROLL, 1, 32>(a, stream);
+    }
+    return SCAP_ERR_CONFIG;
+}
+
 template <int WDT, int BT>
-static int launch_bt(const GemvArgs& a, int waves, int unroll, hipStream_t stream) {
+static int launch_bt(const GemvArgs& a, int waves, int unroll, int lpr, hipStream_t stream) {
     if constexpr (BT == 1) {
 #define SCAP_CASE(WV, UN) \
-    if (waves == WV && unroll == UN) return launch_one<WDT, WV, UN, 1>(a, stream);
+    if (waves == WV && unroll == UN) return launch_lpr<WDT, WV, UN>(a, lpr, stream);
         SCAP_CASE(4, 4) SCAP_CASE(4, 8) SCAP_CASE(4, 16)
         SCAP_CASE(8, 4) SCAP_CASE(8, 8) SCAP_CASE(8, 16)
         SCAP_CASE(16, 4) SCAP_CASE(16, 8) SCAP_CASE(16, 16)
 #undef SCAP_CASE
         return SCAP_ERR_CONFIG;
     } else if constexpr (BT <= 4) {
-        if (waves == 8 && unroll == 8) return launch_one<WDT, 8, 8, BT>(a, stream);
+        if (waves == 8 && unroll == 8 && lpr == 64) return launch_one<WDT, 8, 8, BT, 64>(a, stream);
         return SCAP_ERR_CONFIG;
     } else {
-        if (waves == 8 && unroll == 4) return launch_one<WDT, 8, 4, BT>(a, stream);
+        if (waves == 8 && unroll == 4 && lpr == 64) return launch_one<WDT, 8, 4, BT, 64>(a, stream);
         return SCAP_ERR_CONFIG;
     }
 }
 
 template <int WDT>
-static int launch_wdt(const GemvArgs& a, int bt, int waves, int unroll, hipStream_t stream) {
+static int launch_wdt(const GemvArgs& a, int bt, int waves, int unroll, int lpr, hipStream_t stream) {
     switch (bt) {
-        case 1: return launch_bt<WDT, 1>(a, waves, unroll, stream);
-        case 2: return launch_bt<WDT, 2>(a, waves, unroll, stream);
-        case 4: return launch_bt<WDT, 4>(a, waves, unroll, stream);
-        case 8: return launch_bt<WDT, 8>(a, waves, unroll, stream);
-        case 16: return launch_bt<WDT, 16>(a, waves, unroll, stream);
+        case 1: return launch_bt<WDT, 1>(a, waves, unroll, lpr, stream);
+        case 2: return launch_bt<WDT, 2>(a, waves, unroll, lpr, stream);
+        case 4: return launch_bt<WDT, 4>(a, waves, unroll, lpr, stream);
+        case 8: return launch_bt<WDT, 8>(a, waves, unroll, lpr, stream);
+        case 16: return launch_bt<WDT, 16>(a, waves, unroll, lpr, stream);
     }
     return SCAP_ERR_SHAPE;
 }
@@ -492,17 +540,19 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     while (bt < a.B) bt <<= 1;
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
-    int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0;
+    int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0, lpr = 64;
     if (cfg) {
         if (cfg->waves_per_group) waves = cfg->waves_per_group;
         if (cfg->unroll) unroll = cfg->unroll;
         if (cfg->rows_per_group) kc = cfg->rows_per_group;
+        if (cfg->lanes_per_row) lpr = cfg->lanes_per_row;
         if (kc < 0 || (kc % kWave) != 0) return SCAP_ERR_CONFIG;
+        if (lpr != 64 && lpr != 32) return SCAP_ERR_CONFIG;
     }
     const int elems = (wdt == kI8) ? 16 : 8;
-    const int tile = kWave * elems;
+    const int tile = lpr * elems;
     a.T = (int)((a.N + tile - 1) / tile);
-    if (a.T > kMaxTiles) return SCAP_ERR_SHAPE;
+    if (a.T > kMaxTiles) return (cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : SCAP_ERR_SHAPE;
 
     if (kc == 0) {
         // about one workgroup per compute unit (256): more splits only lengthen the final reduction,
@@ -535,9 +585,9 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     a.S = s;
 
     switch (wdt) {
-        case kF16: return launch_wdt<kF16>(a, bt, waves, unroll, stream);
-        case kBF16: return launch_wdt<kBF16>(a, bt, waves, unroll, stream);
-        case kI8: return launch_wdt<kI8>(a, bt, waves, unroll, stream);
+        case kF16: return launch_wdt<kF16>(a, bt, waves, unroll, lpr, stream);
+        case kBF16: return launch_wdt<kBF16>(a, bt, waves, unroll, lpr, stream);
+        case kI8: return launch_wdt<kI8>(a, bt, waves, unroll, lpr, stream);
     }
     return SCAP_ERR_DTYPE;
 }

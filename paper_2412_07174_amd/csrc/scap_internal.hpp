@@ -21,17 +21,19 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 
 // ---------------------------------------------------------------------------------------------
 // Workspace layout (byte offsets into the caller's buffer)
-//   [0, 4096)            int32 counters[1024]    arrival counters, one per column tile; zero at rest
 //   [4096, 20480)        uint64 hist[2048]       calibration histograms
 //   [20480, 28672)       double sums[1024]       calibration partial sums
 //   [65536, +32768)      int32 seg_cnt[17][256]  kept-channel counts per (token | union, K split)
-//   [98304, +4*B*cap)         float partial[B][S][T][tile]   split-K partial sums
+//   [131072, +1 MiB)     int32 counter per column tile, one every 1 KiB so that the arrival tickets of
+//                        different tiles go to different memory channels; zero at rest
+//   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums
 // ---------------------------------------------------------------------------------------------
-constexpr size_t kOffCounters = 0;
 constexpr size_t kOffHist = 4096;
 constexpr size_t kOffSums = 20480;
 constexpr size_t kOffSegCnt = 65536;
-constexpr size_t kOffPartial = 98304;
+constexpr size_t kOffCounters = 131072;
+constexpr int kCounterStride = 256;  // int32 words between the counters of neighbouring tiles
+constexpr size_t kOffPartial = kOffCounters + 1024 * (size_t)kCounterStride * 4;
 constexpr int kMaxTiles = 1024;
 constexpr int kMaxSplits = 256;
 constexpr int kHistBins = 2048;

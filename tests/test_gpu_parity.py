@@ -47,8 +47,9 @@ def test_small_shapes(dt, K, N):
             check_against_oracle(layer, X[b], dt, 0.2, tau, bf, what=f"K={K} N={N} tau={tau}")
 
 
+@pytest.mark.parametrize("lanes", [64, 32])
 @pytest.mark.parametrize("waves,unroll", [(4, 4), (4, 8), (4, 16), (8, 4), (8, 8), (8, 16), (16, 4), (16, 8), (16, 16)])
-def test_every_launch_shape(waves, unroll):
+def test_every_launch_shape(waves, unroll, lanes):
     K, N = 3000, 1544
     W = wl.weights(K, N, 301, BF16)
     layer = Layer(W, BF16, B=1)
@@ -56,14 +57,32 @@ def test_every_launch_shape(waves, unroll):
     bf = np.random.default_rng(303).standard_normal(N).astype(np.float32)
     for rows in (64, 192, 512, 1024, 3008):
         for tau in (0.05, 0.6):
-            say(f"launch shape waves={waves} unroll={unroll} rows={rows} tau={tau}")
-            check_against_oracle(layer, x, BF16, 0.0, tau, bf, cfg=(waves, rows, unroll), what=f"{waves}/{rows}/{unroll}")
+            say(f"launch shape waves={waves} unroll={unroll} rows={rows} lanes={lanes} tau={tau}")
+            check_against_oracle(layer, x, BF16, 0.0, tau, bf, cfg=(waves, rows, unroll, lanes),
+                                 what=f"{waves}/{rows}/{unroll}/{lanes}")
+
+
+@pytest.mark.parametrize("dt", [F16, I8])
+@pytest.mark.parametrize("lanes", [32])
+def test_narrow_tiles_other_dtypes(dt, lanes):
+    K, N = 1100, 2064 if dt == I8 else 1032
+    if dt == I8:
+        q, scale = wl.quantize_i8(K, N, 311)
+        layer = Layer(q, I8, col_scale_bits=scale, B=1)
+    else:
+        layer = Layer(wl.weights(K, N, 311, dt), dt, B=1)
+    x = wl.swiglu(1, K, 312, F16 if dt == F16 else BF16)[0]
+    for rows in (128, 576):
+        for tau in (0.0, 0.4):
+            say(f"narrow tiles dt={dt} lanes={lanes} rows={rows} tau={tau}")
+            check_against_oracle(layer, x, F16 if dt == F16 else BF16, 0.0, tau, None, cfg=(8, rows, 8, lanes),
+                                 what=f"dt={dt} lanes={lanes}")
 
 
 def test_invalid_launch_shape_is_rejected():
     layer = Layer(wl.weights(256, 512, 1, BF16), BF16, B=1)
     x = to_dev(wl.swiglu(1, 256, 2, BF16)[0], BF16)
-    for cfg in [(3, 128, 8), (8, 100, 8), (8, 128, 5)]:
+    for cfg in [(3, 128, 8), (8, 100, 8), (8, 128, 5), (8, 128, 8, 48)]:
         with pytest.raises(scap.ScapError) as e:
             scap.sparse_fc(layer.W, x, 0.0, 0.1, None, workspace=layer.ws, cfg=cfg)
         assert e.value.status == -9
