@@ -31,11 +31,20 @@ int check_workspace(void* ws, size_t bytes, int64_t K, int64_t N, int64_t B) {
     return SCAP_OK;
 }
 
-void fill_workspace_ptrs(GemvArgs& a, void* ws) {
+size_t union_list_offset(int64_t N, int64_t B) { return kOffPartial + 4 * (size_t)B * partial_capacity(N); }
+
+void fill_workspace_ptrs(GemvArgs& a, void* ws, int64_t K, int64_t N, int64_t B) {
     char* base = static_cast<char*>(ws);
     a.counters = reinterpret_cast<int32_t*>(base + kOffCounters);
     a.seg_cnt = reinterpret_cast<int32_t*>(base + kOffSegCnt);
     a.partial = reinterpret_cast<float*>(base + kOffPartial);
+    a.u_idx = nullptr;
+    a.u_d = nullptr;
+    if (B >= kMfmaMinTokens) {
+        char* lists = base + union_list_offset(N, B);
+        a.u_d = reinterpret_cast<float*>(lists);
+        a.u_idx = reinterpret_cast<int32_t*>(lists + union_list_entries(K) * 64);
+    }
 }
 
 int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
@@ -76,7 +85,7 @@ int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t
     a.xdt = xdt;
     a.m = m;
     a.tau = tau;
-    fill_workspace_ptrs(a, workspace);
+    fill_workspace_ptrs(a, workspace, K, N, B);
     return launch_gemv(a, wdt, cfg, static_cast<hipStream_t>(stream));
 }
 
@@ -106,7 +115,7 @@ size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B) {
     if (K < 1 || N < 0 || B < 1) return 0;
     if (N == 0) return kOffSegCnt;  // calibration only uses the fixed header
     if (K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19) || B > SCAP_MAX_TOKENS) return 0;
-    return kOffPartial + 4 * (size_t)B * partial_capacity(N);
+    return union_list_offset(N, B) + (B >= kMfmaMinTokens ? union_list_entries(K) * 68 : 0);
 }
 
 int scap_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {

@@ -13,49 +13,9 @@
 //      -- a fixed order, so y is bit-reproducible -- plus the fused bias, and resets the counter.
 // The last arrival of tile 0 also closes the gaps between the per-split index lists that the splits
 // left in idx_out, and writes nnz_out.
-#include "scap_device.hpp"
-#include "scap_internal.hpp"
+#include "scap_gemv_parts.hpp"
 
 namespace scap {
-
-constexpr int kHdrBytes = 2048;  // LDS header: per-wave counts + flags
-
-// Data handed from one workgroup to another inside a launch (split-K partials, per-split index lists,
-// arrival counters) bypasses the non-coherent cache levels: device-scope relaxed atomics for single
-// words, buffer loads/stores with the device-coherent cache policy for the 16-byte partial sums.
-// Such stores write through to the device's coherence point and such loads read from it, so no
-// workgroup has to write back or invalidate its whole L2 -- on an 8-XCD part one device-scope fence
-// per workgroup costs several times the GEMV itself.  A compute unit pulls coherent data at only a few
-// tens of GB/s, so these accesses are kept few and wide.
-// Ordering: every thread waits until its own stores are acknowledged (s_waitcnt vmcnt(0)), the workgroup
-// barriers, then one thread takes the arrival ticket; the last arrival barriers again before anyone
-// reads.
-
-constexpr int kAuxDeviceCoherent = 1 << 4;  // "sc1" bit of the buffer cache policy
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_raw_buffer(void* base, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
-}
-__device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, float4 v) {
-    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    const u32x4_t t = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
-    __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)byte_off, 0, kAuxDeviceCoherent);
-}
-__device__ __forceinline__ float4 load_coherent16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
-    const auto t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kAuxDeviceCoherent);
-    return make_float4(__uint_as_float(t[0]), __uint_as_float(t[1]), __uint_as_float(t[2]), __uint_as_float(t[3]));
-}
-// all of this thread's earlier memory operations have completed
-__device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-template <typename T>
-__device__ __forceinline__ void store_dev(T* p, T v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T>
-__device__ __forceinline__ T load_dev(const T* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // 16 bytes of weight row `row` at this lane's columns.  `row` is wave-uniform, so the row base is
 // formed on the scalar unit and the load takes a scalar base plus a 32-bit lane offset.
@@ -81,139 +41,22 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
     constexpr int TILE = LPR * ELEMS;
     constexpr int RPI = kWave / LPR;  // rows per load instruction
     constexpr int NT = WAVES * kWave;
+    constexpr int GROUPS = TILE / 4;  // 4-column groups of a tile
 
     extern __shared__ uint4 smem_raw[];
-    char* smem = reinterpret_cast<char*>(smem_raw);
-    int* s_hdr = reinterpret_cast<int*>(smem);              // [(1+BT)][WAVES] wave counts, then flags
-    int* s_flag = s_hdr + (1 + BT) * WAVES;                 // [0] last-arrival flag
-    int* s_idx = reinterpret_cast<int*>(smem + kHdrBytes);  // [Kc]
-    float* s_d = reinterpret_cast<float*>(s_idx + a.Kc);    // [BT][Kc]
-    float* s_red = reinterpret_cast<float*>(smem + kHdrBytes);  // [WAVES*RPI][TILE], reuses the list space
+    const Lds L = carve_lds<WAVES, BT>(reinterpret_cast<char*>(smem_raw), a.Kc);
+    const int* s_idx = L.idx;
+    const float* s_d = L.d;
+    float* s_red = L.red;  // [WAVES*RPI][TILE]
 
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
     const int lane = tid & 63;
     const int tile = blockIdx.x % a.T;
     const int split = blockIdx.x / a.T;
-    const int k0 = split * a.Kc;
-    const int kend = min(k0 + a.Kc, a.K);
-    const bool per_token = BT > 1 && tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr);
-    const bool want_idx = tile == 0 && a.idx_out != nullptr;
 
     // ------------------------------------------------------------------ 1. centre, threshold, compact
-    const int nchunk = (kend - k0 + kWave - 1) / kWave;
-    const int cpw = (nchunk + WAVES - 1) / WAVES;
-    const int c_begin = min(w * cpw, nchunk);
-    const int c_end = min(c_begin + cpw, nchunk);
-
-    auto eval = [&](int b, int k, bool valid, float& d) -> bool {
-        d = 0.f;
-        if (b >= a.B || !valid) return false;
-        if (a.mode == kModeFold) {
-            d = a.m;
-            return true;
-        }
-        const float xf = act_to_f32(a.x, (int64_t)b * a.K + k, a.xdt);
-        if (a.mode == kModeDense) {
-            d = xf;
-            return true;
-        }
-        d = xf - a.m;               // one fp32 subtraction
-        return fabsf(d) > a.tau;    // strict; NaN compares false
-    };
-
-    {
-        int ucount = 0;
-        int tcount[BT];
-#pragma unroll
-        for (int b = 0; b < BT; ++b) tcount[b] = 0;
-        for (int c = c_begin; c < c_end; ++c) {
-            const int k = k0 + c * kWave + lane;
-            const bool valid = k < kend;
-            bool any = false;
-#pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                float d;
-                const bool keep = eval(b, k, valid, d);
-                any |= keep;
-                if (per_token) tcount[b] += __popcll(__ballot(keep));
-            }
-            ucount += __popcll(__ballot(any));
-        }
-        if (lane == 0) {
-            s_hdr[w] = ucount;
-            if (per_token) {
-#pragma unroll
-                for (int b = 0; b < BT; ++b) s_hdr[(1 + b) * WAVES + w] = tcount[b];
-            }
-        }
-    }
-    __syncthreads();
-    int ubase = 0, cnt = 0;
-#pragma unroll
-    for (int i = 0; i < WAVES; ++i) {
-        const int v = s_hdr[i];
-        if (i < w) ubase += v;
-        cnt += v;
-    }
-    cnt = uniform(cnt);
-    ubase = uniform(ubase);
-    {
-        int tbase[BT];
-        int ttotal[BT];
-#pragma unroll
-        for (int b = 0; b < BT; ++b) {
-            tbase[b] = 0;
-            ttotal[b] = 0;
-            if (per_token) {
-                for (int i = 0; i < WAVES; ++i) {
-                    const int v = s_hdr[(1 + b) * WAVES + i];
-                    if (i < w) tbase[b] += v;
-                    ttotal[b] += v;
-                }
-            }
-        }
-        for (int c = c_begin; c < c_end; ++c) {
-            const int k = k0 + c * kWave + lane;
-            const bool valid = k < kend;
-            bool any = false;
-            float d[BT];
-            bool keep[BT];
-#pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                keep[b] = eval(b, k, valid, d[b]);
-                any |= keep[b];
-            }
-            const uint64_t ub = __ballot(any);
-            if (any) {
-                const int pos = ubase + lanes_below(ub);
-                s_idx[pos] = k;
-#pragma unroll
-                for (int b = 0; b < BT; ++b) s_d[b * a.Kc + pos] = keep[b] ? d[b] : 0.f;
-                if (BT == 1 && want_idx) store_dev(&a.idx_out[k0 + pos], k);
-            }
-            ubase += __popcll(ub);
-            if (BT > 1 && per_token) {
-#pragma unroll
-                for (int b = 0; b < BT; ++b) {
-                    const uint64_t tb = __ballot(keep[b]);
-                    if (want_idx && keep[b]) store_dev(&a.idx_out[(int64_t)b * a.K + k0 + tbase[b] + lanes_below(tb)], k);
-                    tbase[b] += __popcll(tb);
-                }
-            }
-        }
-        if (tile == 0 && tid == 0) {
-            store_dev(&a.seg_cnt[a.B * a.S + split], cnt);  // union
-            if (BT == 1) {
-                store_dev(&a.seg_cnt[split], cnt);
-            } else if (per_token) {
-#pragma unroll
-                for (int b = 0; b < BT; ++b)
-                    if (b < a.B) store_dev(&a.seg_cnt[b * a.S + split], ttotal[b]);
-            }
-        }
-    }
-    __syncthreads();
+    const int cnt = compact_inputs<WAVES, BT>(a, tile, split, L);
 
     // ------------------------------------------------------------------ 2. stream the kept rows
     float acc[BT][ELEMS];
@@ -301,28 +144,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
     }
 
     // ------------------------------------------------------------------ 3. add the wavefronts' sums
-    constexpr int GROUPS = TILE / 4;  // 4-column groups of a tile
-    auto finish_columns = [&](int b, int g, float4 s) {  // scale, add the fused bias, store y
-        const int col = tile * TILE + 4 * g;
-        if (col >= a.N) return;  // N is a multiple of 8: a group is inside or outside as a whole
-        if (WDT == kI8) {
-            s.x *= f16_bits_to_f32(a.col_scale[col]);
-            s.y *= f16_bits_to_f32(a.col_scale[col + 1]);
-            s.z *= f16_bits_to_f32(a.col_scale[col + 2]);
-            s.w *= f16_bits_to_f32(a.col_scale[col + 3]);
-        }
-        if (a.bias) {
-            const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
-            s.x += bv.x;
-            s.y += bv.y;
-            s.z += bv.z;
-            s.w += bv.w;
-        }
-        *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
-    };
-
-    // split-K partials of this call: [B][S][T][TILE] floats, addressed by byte offset
-    const __amdgpu_buffer_rsrc_t pbuf = make_raw_buffer(a.partial, (uint32_t)a.B * a.S * a.T * TILE * 4u);
+    const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
     __syncthreads();  // the list is no longer needed; its LDS becomes the reduction buffer
 #pragma unroll
     for (int b = 0; b < BT; ++b) {
@@ -343,150 +165,56 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
                     s.z += v.z;
                     s.w += v.w;
                 }
-                if (a.S == 1)
-                    finish_columns(b, g, s);
-                else
-                    store_coherent16(pbuf, (uint32_t)((((b * a.S + split) * a.T + tile) * TILE + 4 * g) * 4), s);
+                emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, s);
             }
             __syncthreads();
         }
     }
 
     // ------------------------------------------------------------------ 4. last arrival finishes the tile
-    const bool wants_lists = tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr || a.union_nnz_out != nullptr);
-    if (a.S > 1) {
-        wait_memory_ops();  // my coherent stores have been acknowledged
-        __syncthreads();
-        if (tid == 0) {
-            const int old = __hip_atomic_fetch_add(&a.counters[tile * kCounterStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_flag[0] = (old == a.S - 1);
-        }
-        __syncthreads();
-        if (s_flag[0] == 0) return;
-        // The S partials of a 4-column group are shared out over Q threads (splits q, q+Q, ...), each adds
-        // its share in ascending split order, then the Q shares are added in ascending q: a fixed
-        // association, so y does not depend on which workgroup arrived last or when.
-        constexpr int Q = (NT / GROUPS) > 0 ? (NT / GROUPS) : 1;
-        constexpr int PASSES = (GROUPS + NT - 1) / NT;  // > 1 only when a workgroup has fewer threads than groups
-        const uint32_t pstride = (uint32_t)a.T * TILE * 4u;  // bytes between consecutive splits
-        for (int b = 0; b < a.B; ++b) {
-#pragma unroll
-            for (int pass = 0; pass < PASSES; ++pass) {
-                const int g = (tid % GROUPS) + pass * NT;
-                const int q = (PASSES > 1) ? 0 : tid / GROUPS;
-                if (g < GROUPS && q < Q) {
-                    const uint32_t pc = (uint32_t)(((b * a.S * a.T + tile) * TILE + 4 * g) * 4);
-                    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-                    for (int sp0 = q; sp0 < a.S; sp0 += 8 * Q) {  // 8 loads in flight
-                        float4 v[8];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            const int sp = sp0 + j * Q;
-                            v[j] = sp < a.S ? load_coherent16(pbuf, pc + sp * pstride) : make_float4(0.f, 0.f, 0.f, 0.f);
-                        }
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            s.x += v[j].x;
-                            s.y += v[j].y;
-                            s.z += v[j].z;
-                            s.w += v[j].w;
-                        }
-                    }
-                    *reinterpret_cast<float4*>(s_red + q * TILE + 4 * g) = s;
-                }
-            }
-            __syncthreads();
-            for (int g = tid; g < GROUPS; g += NT) {
-                float4 s = *reinterpret_cast<const float4*>(s_red + 4 * g);
-#pragma unroll
-                for (int q = 1; q < Q; ++q) {
-                    const float4 v = *reinterpret_cast<const float4*>(s_red + q * TILE + 4 * g);
-                    s.x += v.x;
-                    s.y += v.y;
-                    s.z += v.z;
-                    s.w += v.w;
-                }
-                finish_columns(b, g, s);
-            }
-            __syncthreads();
-        }
-        if (tid == 0) store_dev(&a.counters[tile * kCounterStride], 0);  // ready for the next call
-    }
-
-    // ------------------------------------------------------------------ index lists (tile 0 only)
-    if (!wants_lists) return;
-    // Each split left its ascending list in place at idx_out[b*K + split*Kc ...]; close the gaps.
-    // Every entry moves left or stays, so reading a block of source positions, synchronising, then
-    // writing it, block after block from the left, never overwrites an entry that is still to be read.
-    __syncthreads();
-    int* s_off = s_idx;               // [S] exclusive offsets
-    int* s_cnt = s_idx + kMaxSplits;  // [S] counts
-    const int nlist = a.B + 1;
-    for (int l = 0; l < nlist; ++l) {
-        const bool is_union = l == a.B;
-        if (is_union && a.union_nnz_out == nullptr) continue;
-        if (!is_union && a.nnz_out == nullptr) continue;
-        const int src_l = (BT == 1) ? 0 : l;  // with one token the union list is the token's list
-        __syncthreads();
-        if (w == 0) {
-            int run = 0;
-            for (int s0 = 0; s0 < a.S; s0 += kWave) {
-                const int sp = s0 + lane;
-                const int v = sp < a.S ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.S + sp]) : 0;
-                const int inc = wave_inclusive_scan(v);
-                if (sp < a.S) {
-                    s_off[sp] = run + inc - v;
-                    s_cnt[sp] = v;
-                }
-                run += __shfl(inc, kWave - 1, kWave);
-            }
-            if (lane == 0) {
-                if (is_union)
-                    a.union_nnz_out[0] = run;
-                else
-                    a.nnz_out[l] = run;
-            }
-        }
-        __syncthreads();
-        if (!is_union && a.idx_out != nullptr && a.S > 1) {
-            int32_t* base = a.idx_out + (int64_t)l * a.K;
-            constexpr int PER = 16;
-            for (int c0 = 0; c0 < a.K; c0 += NT * PER) {
-                int vals[PER], dsts[PER];
-#pragma unroll
-                for (int j = 0; j < PER; ++j) {
-                    const int p = c0 + j * NT + tid;
-                    dsts[j] = -1;
-                    vals[j] = 0;
-                    if (p < a.K) {
-                        const int seg = p / a.Kc;
-                        const int r = p - seg * a.Kc;
-                        if (r < s_cnt[seg]) {
-                            vals[j] = load_dev(&base[p]);
-                            dsts[j] = s_off[seg] + r;
-                        }
-                    }
-                }
-                __syncthreads();
-#pragma unroll
-                for (int j = 0; j < PER; ++j)
-                    if (dsts[j] >= 0) base[dsts[j]] = vals[j];
-                __syncthreads();
-            }
-        }
-    }
+    finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L);
 }
 
 // ---------------------------------------------------------------------------------------------- launch
+int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced) {
+    a.T = (int)((a.N + tile - 1) / tile);
+    if (a.T > kMaxTiles) return SCAP_ERR_SHAPE;
+    if (kc == 0) {
+        // about one workgroup per compute unit (256): more splits only lengthen the final reduction,
+        // fewer leave compute units -- each limited to ~100 GB/s of misses -- without work
+        const int want_groups = 256;
+        int s = (want_groups + a.T - 1) / a.T;
+        if (s < 1) s = 1;
+        kc = (int)align_up((size_t)((a.K + s - 1) / s), kWave);
+        if (kc < 128) kc = 128;
+    }
+    // bounds from the workspace: at most kMaxSplits splits and partial_capacity floats per token
+    const size_t tile_cols = (size_t)a.T * tile;
+    size_t s_cap = partial_capacity(a.N) / tile_cols;
+    if (s_cap > (size_t)kMaxSplits) s_cap = kMaxSplits;
+    if (s_cap < 1) s_cap = 1;
+    int s = (a.K + kc - 1) / kc;
+    if ((size_t)s > s_cap) {
+        kc = (int)align_up((size_t)((a.K + s_cap - 1) / s_cap), kWave);
+        s = (a.K + kc - 1) / kc;
+    }
+    // LDS budget: the list of one workgroup must fit
+    const int kc_lds = (int)((64 * 1024 - kHdrBytes) / (4 * (1 + floats_per_entry)) / kWave * kWave);
+    if (kc > kc_lds) {
+        if (kc_forced) return SCAP_ERR_CONFIG;
+        kc = kc_lds;
+        s = (a.K + kc - 1) / kc;
+        if ((size_t)s > s_cap) return SCAP_ERR_SHAPE;
+    }
+    a.Kc = kc;
+    a.S = s;
+    return SCAP_OK;
+}
+
 template <int WDT, int WAVES, int UNROLL, int BT, int LPR>
 static int launch_one(const GemvArgs& a, hipStream_t stream) {
     constexpr int ELEMS = Vec<WDT>::kElems;
-    const size_t list_bytes = (size_t)a.Kc * 4 * (1 + BT);
-    const size_t red_bytes = (size_t)WAVES * kWave * ELEMS * 4;
-    const size_t off_bytes = (size_t)kMaxSplits * 8;
-    size_t body = list_bytes > red_bytes ? list_bytes : red_bytes;
-    if (body < off_bytes) body = off_bytes;
-    const size_t lds = kHdrBytes + body;
+    const size_t lds = lds_bytes(a.Kc, BT, (size_t)WAVES * kWave * (ELEMS > 4 ? ELEMS : 4) * 4);
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
     const dim3 grid((unsigned)(a.S * a.T));
     const dim3 block(WAVES * kWave);
@@ -540,6 +268,11 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     while (bt < a.B) bt <<= 1;
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
+    // Several tokens over bf16 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
+    const bool explicit_valu = cfg && (cfg->waves_per_group || cfg->unroll || cfg->lanes_per_row);
+    if (a.B >= kMfmaMinTokens && wdt == kBF16 && a.mode != kModeFold && !explicit_valu)
+        return launch_gemm_mfma(a, cfg, stream);
+
     int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0, lpr = 64;
     if (cfg) {
         if (cfg->waves_per_group) waves = cfg->waves_per_group;
@@ -550,39 +283,8 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         if (lpr != 64 && lpr != 32) return SCAP_ERR_CONFIG;
     }
     const int elems = (wdt == kI8) ? 16 : 8;
-    const int tile = lpr * elems;
-    a.T = (int)((a.N + tile - 1) / tile);
-    if (a.T > kMaxTiles) return (cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : SCAP_ERR_SHAPE;
-
-    if (kc == 0) {
-        // about one workgroup per compute unit (256): more splits only lengthen the final reduction,
-        // fewer leave compute units -- each limited to ~100 GB/s of misses -- without work
-        const int want_groups = 256;
-        int s = (want_groups + a.T - 1) / a.T;
-        if (s < 1) s = 1;
-        kc = (int)align_up((size_t)((a.K + s - 1) / s), kWave);
-        if (kc < 128) kc = 128;
-    }
-    // bounds from the workspace: at most kMaxSplits splits and partial_capacity floats per token
-    const size_t tile_cols = (size_t)a.T * tile;
-    size_t s_cap = partial_capacity(a.N) / tile_cols;
-    if (s_cap > (size_t)kMaxSplits) s_cap = kMaxSplits;
-    if (s_cap < 1) s_cap = 1;
-    int s = (a.K + kc - 1) / kc;
-    if ((size_t)s > s_cap) {
-        kc = (int)align_up((size_t)((a.K + s_cap - 1) / s_cap), kWave);
-        s = (a.K + kc - 1) / kc;
-    }
-    // LDS budget: the list of one workgroup must fit
-    const int kc_lds = (int)((64 * 1024 - kHdrBytes) / (4 * (1 + bt)) / kWave * kWave);
-    if (kc > kc_lds) {
-        if (cfg && cfg->rows_per_group) return SCAP_ERR_CONFIG;
-        kc = kc_lds;
-        s = (a.K + kc - 1) / kc;
-        if ((size_t)s > s_cap) return SCAP_ERR_SHAPE;
-    }
-    a.Kc = kc;
-    a.S = s;
+    const int rc = plan_splits(a, lpr * elems, bt, kc, cfg && cfg->rows_per_group);
+    if (rc != SCAP_OK) return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
 
     switch (wdt) {
         case kF16: return launch_wdt<kF16>(a, bt, waves, unroll, lpr, stream);

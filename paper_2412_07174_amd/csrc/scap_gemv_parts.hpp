@@ -1,0 +1,396 @@
+// Pieces shared by the GEMV (vector ALU) and batched (MFMA) kernels of libscap: LDS carving, the
+// centre/threshold/compact prologue (SCAP Alg. 3 steps 1-2, Eq. 2), and the split-K epilogue.
+#pragma once
+
+#include "scap_device.hpp"
+#include "scap_internal.hpp"
+
+namespace scap {
+
+constexpr int kHdrBytes = 2048;  // LDS header: per-wave counts + flags
+
+// Data handed from one workgroup to another inside a launch (split-K partials, per-split index lists,
+// arrival counters) bypasses the non-coherent cache levels: device-scope relaxed atomics for single
+// words, buffer loads/stores with the device-coherent cache policy for the 16-byte partial sums.
+// Such stores write through to the device's coherence point and such loads read from it, so no
+// workgroup has to write back or invalidate its whole L2 -- on an 8-XCD part one device-scope fence
+// per workgroup costs several times the GEMV itself.  A compute unit pulls coherent data at only a few
+// tens of GB/s, so these accesses are kept few and wide.
+// Ordering: every thread waits until its own stores are acknowledged (s_waitcnt vmcnt(0)), the workgroup
+// barriers, then one thread takes the arrival ticket; the last arrival barriers again before anyone
+// reads.
+
+constexpr int kAuxDeviceCoherent = 1 << 4;  // "sc1" bit of the buffer cache policy
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_raw_buffer(void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ void store_coherent16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, float4 v) {
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t t = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)byte_off, 0, kAuxDeviceCoherent);
+}
+__device__ __forceinline__ float4 load_coherent16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+    const auto t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kAuxDeviceCoherent);
+    return make_float4(__uint_as_float(t[0]), __uint_as_float(t[1]), __uint_as_float(t[2]), __uint_as_float(t[3]));
+}
+// all of this thread's earlier memory operations have completed
+__device__ __forceinline__ void wait_memory_ops() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <typename T>
+__device__ __forceinline__ void store_dev(T* p, T v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T load_dev(const T* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+
+// ---------------------------------------------------------------------------------------------- LDS
+struct Lds {
+    int* hdr;    // [(1+BT)][WAVES] per-wave kept counts (union first, then per token)
+    int* flag;   // [0] last-arrival flag
+    int* idx;    // [Kc] kept channel indices, ascending (LDS, or global for the batched path)
+    float* d;    // centred values per token (0 where the token pruned the channel); see d_at()
+    float* red;  // reduction buffer; reuses the list space once the rows have been streamed
+};
+
+// Position of token b's value of list entry e in the list's value array.  DSTRIDE == 0: token-major
+// [BT][Kc] (a wavefront reads consecutive entries of one token).  DSTRIDE == kDPacked16: groups of 4
+// entries x 16 tokens x 4 values, so that the matrix-core kernel's lane (token, row group) finds its four
+// values in one 16-byte vector.
+constexpr int kDPacked16 = -16;
+template <int DSTRIDE>
+__device__ __forceinline__ int d_at(int b, int e, int Kc) {
+    return DSTRIDE == 0 ? b * Kc + e : (e >> 2) * 64 + b * 4 + (e & 3);
+}
+
+template <int WAVES, int BT>
+__device__ __forceinline__ Lds carve_lds(char* smem, int Kc) {
+    Lds L;
+    L.hdr = reinterpret_cast<int*>(smem);
+    L.flag = L.hdr + (1 + BT) * WAVES;
+    L.idx = reinterpret_cast<int*>(smem + kHdrBytes);
+    L.d = reinterpret_cast<float*>(L.idx + Kc);
+    L.red = reinterpret_cast<float*>(smem + kHdrBytes);
+    return L;
+}
+
+// ---------------------------------------------------------------------------------------------- prologue
+// Centre and threshold the workgroup's Kc inputs of every token, and compact the channels kept by any
+// token into an ascending list in LDS (wave64 ballot + prefix counts; cross-wave offsets through LDS).
+// Workgroups of column tile 0 also leave the per-token lists in idx_out and the counts in seg_cnt when
+// the caller asked for them.  Returns the list length (wave-uniform); ends with a barrier.
+template <int WAVES, int BT, int DSTRIDE = 0>
+__device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int split, const Lds& L) {
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    const int k0 = split * a.Kc;
+    const int kend = min(k0 + a.Kc, a.K);
+    const bool per_token = BT > 1 && tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr);
+    const bool want_idx = tile == 0 && a.idx_out != nullptr;
+
+    const int nchunk = (kend - k0 + kWave - 1) / kWave;
+    const int cpw = (nchunk + WAVES - 1) / WAVES;
+    const int c_begin = min(w * cpw, nchunk);
+    const int c_end = min(c_begin + cpw, nchunk);
+
+    auto eval = [&](int b, int k, bool valid, float& d) -> bool {
+        d = 0.f;
+        if (b >= a.B || !valid) return false;
+        if (a.mode == kModeFold) {
+            d = a.m;
+            return true;
+        }
+        const float xf = act_to_f32(a.x, (int64_t)b * a.K + k, a.xdt);
+        if (a.mode == kModeDense) {
+            d = xf;
+            return true;
+        }
+        d = xf - a.m;               // one fp32 subtraction
+        return fabsf(d) > a.tau;    // strict; NaN compares false
+    };
+
+    {
+        int ucount = 0;
+        int tcount[BT];
+#pragma unroll
+        for (int b = 0; b < BT; ++b) tcount[b] = 0;
+        for (int c = c_begin; c < c_end; ++c) {
+            const int k = k0 + c * kWave + lane;
+            const bool valid = k < kend;
+            bool any = false;
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                float d;
+                const bool keep = eval(b, k, valid, d);
+                any |= keep;
+                if (per_token) tcount[b] += __popcll(__ballot(keep));
+            }
+            ucount += __popcll(__ballot(any));
+        }
+        if (lane == 0) {
+            L.hdr[w] = ucount;
+            if (per_token) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) L.hdr[(1 + b) * WAVES + w] = tcount[b];
+            }
+        }
+    }
+    __syncthreads();
+    int ubase = 0, cnt = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+        const int v = L.hdr[i];
+        if (i < w) ubase += v;
+        cnt += v;
+    }
+    cnt = uniform(cnt);
+    ubase = uniform(ubase);
+    {
+        int tbase[BT];
+        int ttotal[BT];
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            tbase[b] = 0;
+            ttotal[b] = 0;
+            if (per_token) {
+                for (int i = 0; i < WAVES; ++i) {
+                    const int v = L.hdr[(1 + b) * WAVES + i];
+                    if (i < w) tbase[b] += v;
+                    ttotal[b] += v;
+                }
+            }
+        }
+        for (int c = c_begin; c < c_end; ++c) {
+            const int k = k0 + c * kWave + lane;
+            const bool valid = k < kend;
+            bool any = false;
+            float d[BT];
+            bool keep[BT];
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                keep[b] = eval(b, k, valid, d[b]);
+                any |= keep[b];
+            }
+            const uint64_t ub = __ballot(any);
+            if (any) {
+                const int pos = ubase + lanes_below(ub);
+                L.idx[pos] = k;
+#pragma unroll
+                for (int b = 0; b < BT; ++b) L.d[d_at<DSTRIDE>(b, pos, a.Kc)] = keep[b] ? d[b] : 0.f;
+                if (BT == 1 && want_idx) store_dev(&a.idx_out[k0 + pos], k);
+            }
+            ubase += __popcll(ub);
+            if (BT > 1 && per_token) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    const uint64_t tb = __ballot(keep[b]);
+                    if (want_idx && keep[b]) store_dev(&a.idx_out[(int64_t)b * a.K + k0 + tbase[b] + lanes_below(tb)], k);
+                    tbase[b] += __popcll(tb);
+                }
+            }
+        }
+        if (tile == 0 && tid == 0) {
+            store_dev(&a.seg_cnt[a.B * a.S + split], cnt);  // union
+            if (BT == 1) {
+                store_dev(&a.seg_cnt[split], cnt);
+            } else if (per_token) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b)
+                    if (b < a.B) store_dev(&a.seg_cnt[b * a.S + split], ttotal[b]);
+            }
+        }
+    }
+    __syncthreads();
+    return cnt;
+}
+
+// ---------------------------------------------------------------------------------------------- epilogue
+// scale (int8), add the fused bias, store 4 columns of y
+template <int WDT, int TILE>
+__device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int b, int g, float4 s) {
+    const int col = tile * TILE + 4 * g;
+    if (col >= a.N) return;  // N is a multiple of 8: a group is inside or outside as a whole
+    if (WDT == kI8) {
+        s.x *= f16_bits_to_f32(a.col_scale[col]);
+        s.y *= f16_bits_to_f32(a.col_scale[col + 1]);
+        s.z *= f16_bits_to_f32(a.col_scale[col + 2]);
+        s.w *= f16_bits_to_f32(a.col_scale[col + 3]);
+    }
+    if (a.bias) {
+        const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
+        s.x += bv.x;
+        s.y += bv.y;
+        s.z += bv.z;
+        s.w += bv.w;
+    }
+    *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
+}
+
+// split-K partials of one call: [B][S][T][TILE] floats, addressed by byte offset
+template <int TILE>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_buffer(const GemvArgs& a) {
+    return make_raw_buffer(a.partial, (uint32_t)a.B * a.S * a.T * TILE * 4u);
+}
+
+// the workgroup's sum of 4 columns for token b: final output if there is one split, else a partial
+template <int WDT, int TILE>
+__device__ __forceinline__ void emit_group(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, int split, int b,
+                                           int g, float4 s) {
+    if (a.S == 1)
+        finish_columns<WDT, TILE>(a, tile, b, g, s);
+    else
+        store_coherent16(pbuf, (uint32_t)((((b * a.S + split) * a.T + tile) * TILE + 4 * g) * 4), s);
+}
+
+// Arrival ticket; the last arrival of a tile adds the S partials (fixed association), writes y and clears
+// the counter; the last arrival of tile 0 also closes the gaps between the per-split index lists.
+// Every thread of the workgroup must call this after its last emit_group().
+template <int WDT, int WAVES, int TILE, int BT>
+__device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, const Lds& L) {
+    constexpr int NT = WAVES * kWave;
+    constexpr int GROUPS = TILE / 4;
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    float* s_red = L.red;
+    const bool wants_lists = tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr || a.union_nnz_out != nullptr);
+    if (a.S > 1) {
+        wait_memory_ops();  // my coherent stores have been acknowledged
+        __syncthreads();
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(&a.counters[tile * kCounterStride], 1, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+            L.flag[0] = (old == a.S - 1);
+        }
+        __syncthreads();
+        if (L.flag[0] == 0) return;
+        // Work items are (token, 4-column group) pairs.  The S partials of an item are shared out over
+        // Q threads (splits q, q+Q, ...), each adds its share in ascending split order, then the Q shares
+        // are added in ascending q: a fixed association, so y does not depend on which workgroup arrived
+        // last or when.  All items of a pass have their loads in flight together.
+        const int nitems = a.B * GROUPS;
+        const int per_pass = nitems < NT ? nitems : NT;
+        const int Q = NT / per_pass;
+        const uint32_t pstride = (uint32_t)a.T * TILE * 4u;  // bytes between consecutive splits
+        const int li = tid % per_pass, q = tid / per_pass;
+        for (int i0 = 0; i0 < nitems; i0 += per_pass) {
+            const int item = i0 + li;
+            const int b = item / GROUPS, g = item - b * GROUPS;
+            if (q < Q && item < nitems) {
+                const uint32_t pc = (uint32_t)(((b * a.S * a.T + tile) * TILE + 4 * g) * 4);
+                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int sp0 = q; sp0 < a.S; sp0 += 8 * Q) {  // 8 loads in flight
+                    float4 v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int sp = sp0 + j * Q;
+                        v[j] = sp < a.S ? load_coherent16(pbuf, pc + sp * pstride) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        s.x += v[j].x;
+                        s.y += v[j].y;
+                        s.z += v[j].z;
+                        s.w += v[j].w;
+                    }
+                }
+                *reinterpret_cast<float4*>(s_red + (q * per_pass + li) * 4) = s;
+            }
+            __syncthreads();
+            if (q == 0 && item < nitems) {
+                float4 s = *reinterpret_cast<const float4*>(s_red + li * 4);
+                for (int qq = 1; qq < Q; ++qq) {
+                    const float4 v = *reinterpret_cast<const float4*>(s_red + (qq * per_pass + li) * 4);
+                    s.x += v.x;
+                    s.y += v.y;
+                    s.z += v.z;
+                    s.w += v.w;
+                }
+                finish_columns<WDT, TILE>(a, tile, b, g, s);
+            }
+            __syncthreads();
+        }
+        if (tid == 0) store_dev(&a.counters[tile * kCounterStride], 0);  // ready for the next call
+    }
+
+    if (!wants_lists) return;
+    // Each split left its ascending list in place at idx_out[b*K + split*Kc ...]; close the gaps.
+    // Every entry moves left or stays, so reading a block of source positions, synchronising, then
+    // writing it, block after block from the left, never overwrites an entry that is still to be read.
+    __syncthreads();
+    int* s_off = L.idx;               // [S] exclusive offsets
+    int* s_cnt = L.idx + kMaxSplits;  // [S] counts
+    const int nlist = a.B + 1;
+    for (int l = 0; l < nlist; ++l) {
+        const bool is_union = l == a.B;
+        if (is_union && a.union_nnz_out == nullptr) continue;
+        if (!is_union && a.nnz_out == nullptr) continue;
+        const int src_l = (BT == 1) ? 0 : l;  // with one token the union list is the token's list
+        __syncthreads();
+        if (w == 0) {
+            int run = 0;
+            for (int s0 = 0; s0 < a.S; s0 += kWave) {
+                const int sp = s0 + lane;
+                const int v = sp < a.S ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.S + sp]) : 0;
+                const int inc = wave_inclusive_scan(v);
+                if (sp < a.S) {
+                    s_off[sp] = run + inc - v;
+                    s_cnt[sp] = v;
+                }
+                run += __shfl(inc, kWave - 1, kWave);
+            }
+            if (lane == 0) {
+                if (is_union)
+                    a.union_nnz_out[0] = run;
+                else
+                    a.nnz_out[l] = run;
+            }
+        }
+        __syncthreads();
+        if (!is_union && a.idx_out != nullptr && a.S > 1) {
+            int32_t* base = a.idx_out + (int64_t)l * a.K;
+            constexpr int PER = 16;
+            for (int c0 = 0; c0 < a.K; c0 += NT * PER) {
+                int vals[PER], dsts[PER];
+#pragma unroll
+                for (int j = 0; j < PER; ++j) {
+                    const int p = c0 + j * NT + tid;
+                    dsts[j] = -1;
+                    vals[j] = 0;
+                    if (p < a.K) {
+                        const int seg = p / a.Kc;
+                        const int r = p - seg * a.Kc;
+                        if (r < s_cnt[seg]) {
+                            vals[j] = load_dev(&base[p]);
+                            dsts[j] = s_off[seg] + r;
+                        }
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < PER; ++j)
+                    if (dsts[j] >= 0) base[dsts[j]] = vals[j];
+                __syncthreads();
+            }
+        }
+    }
+}
+
+// LDS bytes one workgroup needs: header + max(list, reduction buffers, offset tables)
+inline size_t lds_bytes(int Kc, int floats_per_entry, size_t red_bytes) {
+    const size_t list_bytes = (size_t)Kc * 4 * (1 + floats_per_entry);
+    const size_t off_bytes = (size_t)kMaxSplits * 8;
+    size_t body = list_bytes > red_bytes ? list_bytes : red_bytes;
+    if (body < off_bytes) body = off_bytes;
+    return kHdrBytes + body;
+}
+
+// Choose the K split of a launch: fills a.T, a.Kc, a.S.  `tile` = columns per workgroup, `kc` = requested
+// rows per workgroup (0 = about one workgroup per compute unit).  Returns a scap_status.
+int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced);
+
+}  // namespace scap

@@ -27,6 +27,7 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 //   [131072, +1 MiB)     int32 counter per column tile, one every 1 KiB so that the arrival tickets of
 //                        different tiles go to different memory channels; zero at rest
 //   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums
+//   [.., +68*(K+16384))  batched path (B >= 4): union list of every K split (index + 16 centred values per entry)
 // ---------------------------------------------------------------------------------------------
 constexpr size_t kOffHist = 4096;
 constexpr size_t kOffSums = 20480;
@@ -42,6 +43,9 @@ constexpr int kSumSlots = 1024;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // columns rounded up to whole 1024-column blocks (covers the 512- and 1024-column tiles)
+// entries of union-list storage for a K-channel layer: every split may round up to a multiple of 64
+inline size_t union_list_entries(int64_t K) { return (size_t)K + 64 * 256; }
+
 inline size_t padded_cols(int64_t N) { return align_up((size_t)N, 1024); }
 
 // floats of split-K partial storage per token
@@ -63,12 +67,18 @@ struct GemvArgs {
     int32_t* counters;
     int32_t* seg_cnt;
     float* partial;
+    int32_t* u_idx;  // batched path: union list of each K split, [S][Kc] channel indices
+    float* u_d;      // batched path: centred values of the union list, 16 tokens per entry
     int K, N, B, Kc, S, T, mode, xdt;
     float m, tau;
 };
 
 // Enqueue one GEMV (sparse / dense / fold mode).  Returns a scap_status.
 int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+
+// Batched tokens over bf16 weights on the matrix cores (B >= kMfmaMinTokens).
+constexpr int kMfmaMinTokens = 4;
+int launch_gemm_mfma(const GemvArgs& a, const scap_launch_cfg* cfg, hipStream_t stream);
 
 // Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).
 int launch_zero_words(int32_t* p, size_t n, hipStream_t stream);

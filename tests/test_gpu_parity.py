@@ -209,16 +209,48 @@ def test_headline_layer_three_sparsities_and_dense():
 
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
-@pytest.mark.parametrize("B", [2, 3, 4, 8, 16])
-def test_batched_tokens_moderate(B):
+@pytest.mark.parametrize("path", ["auto", "vector"])
+@pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 13, 16])
+def test_batched_tokens_moderate(B, path):
+    """auto: bf16 weights and B >= 4 run on the matrix cores; vector: the same batch forced onto the FMA kernel."""
     K, N = 2500, 1032
     W = wl.weights(K, N, 501, BF16)
     layer = Layer(W, BF16, B=16)
     X = wl.swiglu(B, K, 502 + B, BF16)
     bf = np.random.default_rng(503).standard_normal(N).astype(np.float32)
+    cfg = None if path == "auto" else (8, 0, 8 if B <= 4 else 4, 64)
     for tau in (0.0, 0.15, 0.8, 50.0):
-        say(f"batched B={B} tau={tau}")
-        check_against_oracle(layer, X, BF16, 0.0, tau, bf, what=f"B={B} tau={tau}")
+        say(f"batched B={B} path={path} tau={tau}")
+        check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"B={B} {path} tau={tau}")
+
+
+def test_batched_matrix_core_edge_cases():
+    """Ragged list lengths (not multiples of the 16-row MFMA block), infinities, one split and many splits."""
+    K, N = 1000, 264
+    W = wl.weights(K, N, 511, BF16)
+    layer = Layer(W, BF16, B=16)
+    X = wl.swiglu(6, K, 512, BF16)
+    Xf = wl.decode(X, BF16)
+    Xf[2, 17] = np.inf
+    Xf[4, 900] = -np.inf
+    Xf[1, 3] = np.nan
+    X = wl.encode(Xf, BF16)
+    for rows in (0, 64, 128, 832):
+        for tau in (0.0, 0.3, 1.5, 2.5):
+            say(f"matrix-core edge rows={rows} tau={tau}")
+            check_against_oracle(layer, X, BF16, 0.01, tau, None, cfg=None if rows == 0 else (0, rows, 0, 0),
+                                 what=f"mfma rows={rows} tau={tau}")
+
+
+@pytest.mark.parametrize("B", [4, 16])
+def test_batched_tokens_fp16_weights(B):
+    K, N = 1500, 1032
+    W = wl.weights(K, N, 521, F16)
+    layer = Layer(W, F16, B=16)
+    X = wl.laplace(B, K, 522, F16)
+    for tau in (0.0, 0.4):
+        say(f"batched fp16 B={B} tau={tau}")
+        check_against_oracle(layer, X, F16, 0.1, tau, None, what=f"fp16 B={B} tau={tau}")
 
 
 @pytest.mark.parametrize("which,B", [(0, 4), (1, 4), (1, 16)])
