@@ -66,7 +66,10 @@ typedef enum {
                              0.001 and 0.999 order statistics, 5-bin box smoothing, fullest bin */
 } scap_mode_est;
 
-/* Optional launch shape of the GEMV kernels (for tuning sweeps).  Zero fields mean "choose". */
+/* Optional launch shape of the GEMV kernels (for tuning sweeps).  Zero fields mean "choose".
+ * With 4 or more tokens over bf16 weights the matrix-core kernel runs unless lanes_per_row is given; there
+ * waves_per_group is 8 or 16, unroll (1, 2, 4) counts 16-row blocks in flight per wavefront, and
+ * rows_per_group is rounded up to whole 512-channel list segments. */
 typedef struct {
     int32_t waves_per_group; /* 4, 8 or 16 wavefronts per workgroup */
     int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */

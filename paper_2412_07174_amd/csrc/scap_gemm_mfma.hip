@@ -6,11 +6,13 @@
 //
 //     Y[16 tokens, 16 columns] += D[16 tokens, 16 rows] * W[16 rows, 16 columns]     v_mfma_f32_16x16x16_bf16
 //
-// Two launches.  `batch_compact_kernel` (one workgroup per K split) centres and thresholds the inputs of all
-// tokens once and leaves, in the workspace, the ascending union list of its split and the centred values
-// packed the way the matrix-core kernel reads them.  Doing this inside every (split, column tile) workgroup,
-// as the one-token kernel does, repeats 16 tokens' worth of work per tile and took longer than the GEMM.
-// `gemm_mfma_kernel` (split, tile of 128 columns) then only streams rows.
+// Two launches.  `batch_union_kernel` (one workgroup per K split) centres and thresholds the inputs of all
+// tokens once and leaves the ascending union list of its split in the workspace (plus the per-token lists
+// when the caller wants them).  Doing this inside every (split, column tile) workgroup, as the one-token
+// kernel does, repeats 16 tokens' worth of work per tile and took longer than the GEMM itself.
+// `gemm_mfma_kernel` (split, tile of 128 columns) then streams the listed rows; the centred values come
+// from the list, 16 tokens of an entry side by side, so that the 16 lanes of a row group read 64 contiguous
+// bytes (gathering them from x instead touches one cache line per token and row and throttles the kernel).
 //
 // Operand layout without any transposition.  For this instruction lane l holds
 //     A[m = l%16][k = 4*(l/16) + j],   B[k = 4*(l/16) + j][n = l%16],   C[m = 4*(l/16) + i][n = l%16],  i,j = 0..3.
@@ -20,8 +22,9 @@
 // those four vectors is exactly this lane's B operand of the MFMA that produces columns {8*n + e}.  Eight
 // MFMAs (e = 0..7) per block cover the wavefront's 128 columns; the C registers of lane l then hold tokens
 // 4*(l/16)+i and 8 consecutive columns.  The A operand (centred values of token l%16 at rows 4*(l/16)+j)
-// is one 16-byte vector of the packed list; it is split into a bf16 head and a bf16 tail (d = hi + lo) and
-// fed through two MFMAs, so the bf16 rounding of d costs about 2^-17 relative instead of 2^-9.
+// is read from the list; it is split into a bf16 head and a bf16
+// tail (d = hi + lo) and fed through two MFMAs, so the bf16 rounding of d costs about 2^-17 relative
+// instead of 2^-9.
 #include "scap_gemv_parts.hpp"
 
 namespace scap {
@@ -32,7 +35,7 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kMfmaTile = 128;    // columns per workgroup
 constexpr int kMfmaTokens = 16;   // M of the MFMA; tokens beyond B are zero rows
 constexpr int kMfmaBlock = 16;    // list rows per MFMA (K of the MFMA)
-constexpr int kCompactWaves = 16;
+constexpr int kCompactWaves = 8;
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float v) {
     const uint32_t u = __float_as_uint(v);
@@ -53,19 +56,100 @@ __device__ __forceinline__ void split_bf16x4(const float4& d, s16x4_t& hi, s16x4
 }
 
 // ---------------------------------------------------------------------------------------------- launch 1
-// Workgroup `split`: union list of channels [split*Kc, (split+1)*Kc) -> u_idx[split*Kc ...] (ascending),
-// centred values -> u_d (16 floats per entry, packed by d_at<kDPacked16>), list length -> seg_cnt[B*S+split];
-// per-token lists and counts for idx_out / nnz_out as in the one-token kernel.
-__global__ __launch_bounds__(kCompactWaves * kWave) void batch_compact_kernel(const GemvArgs a) {
-    __shared__ int s_hdr[kHdrBytes / 4];
-    const int split = blockIdx.x;
-    Lds L;
-    L.hdr = s_hdr;
-    L.flag = s_hdr + (1 + kMfmaTokens) * kCompactWaves;
-    L.idx = a.u_idx + (int64_t)split * a.Kc;
-    L.d = a.u_d + (int64_t)split * a.Kc * kMfmaTokens;
-    L.red = nullptr;
-    compact_inputs<kCompactWaves, kMfmaTokens, kDPacked16>(a, 0, split, L);
+// Workgroup `seg` owns channels [seg*Kl, (seg+1)*Kl): one channel per thread and pass; the x values of all
+// tokens are loaded together, the union of the keep tests is compacted with a ballot per wavefront and a
+// scan over the wavefronts.  Segments are short (512 channels unless K is huge) so that the whole input is
+// handled in one round of loads by many workgroups.
+//   u_idx[seg*Kl ...]        ascending channels kept by at least one token
+//   u_d[(seg*Kl + e)*16 + b] centred value of token b at list entry e (0 where token b pruned it)
+//   seg_cnt[B*Sl + seg]      their number;   seg_cnt[b*Sl + seg], idx_out: per-token lists on request
+__global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(const GemvArgs a) {
+    constexpr int BT = kMfmaTokens;
+    constexpr int NT = kCompactWaves * kWave;
+    __shared__ int s_cnt[1 + BT][kCompactWaves];
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    const int seg = blockIdx.x;
+    const int k0 = seg * a.Kl;
+    const int kend = min(k0 + a.Kl, a.K);
+    const bool per_token = a.nnz_out != nullptr || a.idx_out != nullptr;
+    const bool want_idx = a.idx_out != nullptr;
+    int32_t* __restrict__ out = a.u_idx + (int64_t)seg * a.Kl;
+    float* __restrict__ out_d = a.u_d + (int64_t)seg * a.Kl * BT;
+
+    int run_u = 0;
+    int run_t[BT];
+#pragma unroll
+    for (int b = 0; b < BT; ++b) run_t[b] = 0;
+
+    for (int p0 = k0; p0 < kend; p0 += NT) {
+        const int k = p0 + tid;
+        const bool valid = k < kend;
+        uint32_t xb[BT];
+#pragma unroll
+        for (int b = 0; b < BT; ++b) xb[b] = (valid && b < a.B) ? (uint32_t)a.x[(int64_t)b * a.K + k] : 0u;
+        uint32_t keepmask = 0;
+        float dm[BT];  // centred value where the token keeps the channel, else 0
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            const float xf = a.xdt == kBF16 ? bf16_bits_to_f32(xb[b]) : f16_bits_to_f32(xb[b]);
+            const float d = (a.mode == kModeDense) ? xf : xf - a.m;  // one fp32 subtraction
+            const bool keep = valid && b < a.B && (a.mode == kModeDense || fabsf(d) > a.tau);
+            keepmask |= keep ? (1u << b) : 0u;
+            dm[b] = keep ? d : 0.f;
+        }
+        const bool any = keepmask != 0;
+        const uint64_t ub = __ballot(any);
+        if (lane == 0) s_cnt[0][w] = __popcll(ub);
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                const uint64_t tb = __ballot((keepmask >> b) & 1u);
+                if (lane == 0) s_cnt[1 + b][w] = __popcll(tb);
+            }
+        }
+        __syncthreads();
+        int below = 0, total = 0;
+#pragma unroll
+        for (int i = 0; i < kCompactWaves; ++i) {
+            const int v = s_cnt[0][i];
+            if (i < w) below += v;
+            total += v;
+        }
+        if (any) {
+            const int pos = run_u + below + lanes_below(ub);
+            out[pos] = k;
+            float4* dst = reinterpret_cast<float4*>(out_d + (int64_t)pos * BT);
+#pragma unroll
+            for (int q = 0; q < BT / 4; ++q) dst[q] = make_float4(dm[4 * q], dm[4 * q + 1], dm[4 * q + 2], dm[4 * q + 3]);
+        }
+        run_u += total;
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                int tbelow = 0, ttotal = 0;
+                for (int i = 0; i < kCompactWaves; ++i) {
+                    const int v = s_cnt[1 + b][i];
+                    if (i < w) tbelow += v;
+                    ttotal += v;
+                }
+                const uint64_t tb = __ballot((keepmask >> b) & 1u);
+                if (want_idx && ((keepmask >> b) & 1u))
+                    a.idx_out[(int64_t)b * a.K + k0 + run_t[b] + tbelow + lanes_below(tb)] = k;
+                run_t[b] += ttotal;
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        a.seg_cnt[a.B * a.Sl + seg] = run_u;
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+                if (b < a.B) a.seg_cnt[b * a.Sl + seg] = run_t[b];
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------- launch 2
@@ -86,13 +170,31 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     const int tile = blockIdx.x % a.T;
     const int split = blockIdx.x / a.T;
 
-    const int cnt = uniform(a.seg_cnt[a.B * a.S + split]);  // written by the previous launch
-    const int4* __restrict__ lidx = reinterpret_cast<const int4*>(a.u_idx + (int64_t)split * a.Kc);
-    const float4* __restrict__ ld4 = reinterpret_cast<const float4*>(a.u_d + (int64_t)split * a.Kc * BT);
+    // The split covers list segments [seg0, seg1) written by the previous launch.  Their 16-row blocks are
+    // numbered through: s_pre[i] = blocks before segment seg0+i.
+    constexpr int kMaxSeg = 64;
+    __shared__ int s_segcnt[kMaxSeg];
+    __shared__ int s_pre[kMaxSeg + 1];
+    const int per_split = a.Kc / a.Kl;
+    const int seg0 = split * per_split;
+    const int nseg = min(per_split, a.Sl - seg0);
+    if (tid < nseg) s_segcnt[tid] = a.seg_cnt[a.B * a.Sl + seg0 + tid];
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int i = 0; i < nseg; ++i) {
+            s_pre[i] = run;
+            run += (s_segcnt[i] + kMfmaBlock - 1) / kMfmaBlock;
+        }
+        s_pre[nseg] = run;
+    }
+    __syncthreads();
+    const int n_blocks = uniform(s_pre[nseg]);
+
+    const int tok = lane & 15;  // token whose centred values this lane supplies (A index m)
 
     const int cg = lane & 15;   // column group: columns 8*cg .. 8*cg+7 of the tile (B/C index n)
     const int kg = lane >> 4;   // row group: list rows 4*kg .. 4*kg+3 of a block (k of A and B); token group of C
-    const int tok = lane & 15;  // token whose centred values this lane supplies (A index m)
     const int col0 = tile * TILE + cg * 8;
     const uint32_t lane_off = (col0 < a.N) ? (uint32_t)col0 * 2u : 0u;
     const uint32_t row_bytes = (uint32_t)a.N * 2u;
@@ -102,49 +204,65 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // Entry group (blk, kg) = list entries blk*16 + 4*kg .. +3: one int4 of indices, and for token `tok` one
-    // float4 of centred values at float4 index (blk*4 + kg)*16 + tok.  Groups at or past the end of the list
-    // are not loaded; inside the last group, entries >= cnt are masked.
-    auto load_idx = [&](int blk) -> int4 {
-        const int g4 = blk * 4 + kg;
-        return (g4 * 4 < cnt) ? lidx[g4] : make_int4(0, 0, 0, 0);
+    // Block blk (wave-uniform) -> its four list entries for this lane's row group: the int4 of channel
+    // indices and how many of them are valid (0..4).  Blocks past the end give 0 valid entries.
+    auto fetch = [&](int blk, int4& rows, const float*& dptr) -> int {
+        rows = make_int4(0, 0, 0, 0);
+        dptr = a.u_d;
+        if (blk >= n_blocks) return 0;
+        int i = 0;
+        while (i + 1 < nseg && s_pre[i + 1] <= blk) ++i;  // nseg is small
+        i = uniform(i);
+        const int local = blk - s_pre[i];
+        const int left = s_segcnt[i] - local * kMfmaBlock - 4 * kg;  // entries from this lane's first one on
+        if (left <= 0) return 0;
+        const int64_t e = (int64_t)(seg0 + i) * a.Kl + local * kMfmaBlock + 4 * kg;  // this lane's first entry
+        rows = *reinterpret_cast<const int4*>(a.u_idx + e);
+        dptr = a.u_d + e * BT + tok;
+        return left < 4 ? left : 4;
     };
 
-    const int n_blocks = (cnt + kMfmaBlock - 1) / kMfmaBlock;
-    int4 ix[UB];
-#pragma unroll
-    for (int u = 0; u < UB; ++u) ix[u] = load_idx(w + u * WAVES);
-
-    for (int blk0 = w; blk0 < n_blocks; blk0 += WAVES * UB) {
+    // Software pipeline, three deep: while the MFMAs of iteration `it` run, the row loads of `it+1` are in
+    // flight and the list indices of `it+2` are being fetched.  An iteration is UB blocks per wavefront.
+    struct IdxSet {
+        int4 ix[UB];
+        int nv[UB];
+        const float* dp[UB];
+    };
+    struct Stage {
         uint4 r[UB][4];
         float4 dv[UB];
+    };
+    auto fetch_set = [&](int it, IdxSet& I) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) I.nv[u] = fetch(w + (it * UB + u) * WAVES, I.ix[u], I.dp[u]);
+    };
+    auto issue = [&](const IdxSet& I, Stage& st) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
-            const int blk = blk0 + u * WAVES;
-            const int e0 = blk * kMfmaBlock + 4 * kg;
-            const int rows[4] = {ix[u].x, ix[u].y, ix[u].z, ix[u].w};
-            dv[u] = (e0 < cnt) ? ld4[(blk * 4 + kg) * 16 + tok] : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int rows[4] = {I.ix[u].x, I.ix[u].y, I.ix[u].z, I.ix[u].w};
+            float dj[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                r[u][j] = make_uint4(0u, 0u, 0u, 0u);
-                if (e0 + j < cnt)
-                    r[u][j] = *reinterpret_cast<const uint4*>(wbase + (uint64_t)(uint32_t)rows[j] * row_bytes + lane_off);
+                st.r[u][j] = make_uint4(0u, 0u, 0u, 0u);
+                dj[j] = 0.f;
+                if (j < I.nv[u]) {
+                    st.r[u][j] = *reinterpret_cast<const uint4*>(wbase + (uint64_t)(uint32_t)rows[j] * row_bytes + lane_off);
+                    dj[j] = I.dp[u][j * BT];  // 16 lanes read 64 contiguous bytes of one list entry
+                }
             }
-            if (e0 + 1 >= cnt) dv[u].y = 0.f;
-            if (e0 + 2 >= cnt) dv[u].z = 0.f;
-            if (e0 + 3 >= cnt) dv[u].w = 0.f;
+            st.dv[u] = make_float4(dj[0], dj[1], dj[2], dj[3]);
         }
-        int4 ixn[UB];  // indices of the next iteration, fetched while this one computes
-#pragma unroll
-        for (int u = 0; u < UB; ++u) ixn[u] = load_idx(blk0 + (UB + u) * WAVES);
+    };
+    auto compute = [&](const Stage& st) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             s16x4_t a_hi, a_lo;
-            split_bf16x4(dv[u], a_hi, a_lo);
-            const uint32_t q0[4] = {r[u][0].x, r[u][0].y, r[u][0].z, r[u][0].w};
-            const uint32_t q1[4] = {r[u][1].x, r[u][1].y, r[u][1].z, r[u][1].w};
-            const uint32_t q2[4] = {r[u][2].x, r[u][2].y, r[u][2].z, r[u][2].w};
-            const uint32_t q3[4] = {r[u][3].x, r[u][3].y, r[u][3].z, r[u][3].w};
+            split_bf16x4(st.dv[u], a_hi, a_lo);
+            const uint32_t q0[4] = {st.r[u][0].x, st.r[u][0].y, st.r[u][0].z, st.r[u][0].w};
+            const uint32_t q1[4] = {st.r[u][1].x, st.r[u][1].y, st.r[u][1].z, st.r[u][1].w};
+            const uint32_t q2[4] = {st.r[u][2].x, st.r[u][2].y, st.r[u][2].z, st.r[u][2].w};
+            const uint32_t q3[4] = {st.r[u][3].x, st.r[u][3].y, st.r[u][3].z, st.r[u][3].w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int q = e >> 1;
@@ -163,8 +281,23 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
                 acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop.v, acc[e], 0, 0, 0);
             }
         }
-#pragma unroll
-        for (int u = 0; u < UB; ++u) ix[u] = ixn[u];
+    };
+
+    const int niter = (n_blocks > w) ? (n_blocks - w + WAVES * UB - 1) / (WAVES * UB) : 0;
+    IdxSet I0, I1;
+    Stage A, Bs;
+    fetch_set(0, I0);
+    fetch_set(1, I1);
+    issue(I0, A);
+    for (int it = 0; it < niter;) {
+        fetch_set(it + 2, I0);
+        issue(I1, Bs);
+        compute(A);
+        if (++it >= niter) break;
+        fetch_set(it + 2, I1);
+        issue(I0, A);
+        compute(Bs);
+        ++it;
     }
 
     // ------------------------------------------------------------------ add the wavefronts' sums
@@ -198,28 +331,44 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
 
 int launch_gemm_mfma(const GemvArgs& a_in, const scap_launch_cfg* cfg, hipStream_t stream) {
     GemvArgs a = a_in;
-    constexpr int WAVES = 16;
     if (!a.u_idx || !a.u_d) return SCAP_ERR_WORKSPACE;
-    int kc = 0;
-    if (cfg && cfg->rows_per_group) {
-        kc = cfg->rows_per_group;
+    int kc = 0, waves = 8, ub = 2;
+    if (cfg) {
+        if (cfg->rows_per_group) kc = cfg->rows_per_group;
         if (kc < 0 || (kc % kWave) != 0) return SCAP_ERR_CONFIG;
+        if (cfg->waves_per_group) waves = cfg->waves_per_group;
+        if (cfg->unroll) ub = cfg->unroll;  // 16-row blocks in flight per wavefront
     }
-    // no list in LDS: the split is bounded only by the workspace
+    // list segments: 512 channels each, longer only if K is so large that there would be more than 256
+    a.Kl = 512;
+    while (((int64_t)a.K + a.Kl - 1) / a.Kl > kMaxSplits) a.Kl *= 2;
+    a.Sl = (a.K + a.Kl - 1) / a.Kl;
+    if ((size_t)a.Sl * a.Kl > union_list_entries(a.K)) return SCAP_ERR_SHAPE;
+    // K split of the GEMM: whole segments, at most 64 per workgroup; no list in LDS
+    kc = (int)align_up((size_t)kc, (size_t)a.Kl);  // a requested split is rounded up to whole segments
     const int rc = plan_splits(a, kMfmaTile, 0, kc, kc != 0);
     if (rc != SCAP_OK) return rc;
-    if ((size_t)a.S * a.Kc > union_list_entries(a.K)) return SCAP_ERR_CONFIG;
+    a.Kc = (int)align_up((size_t)a.Kc, (size_t)a.Kl);
+    if (a.Kc / a.Kl > 64) a.Kc = 64 * a.Kl;
+    a.S = (a.K + a.Kc - 1) / a.Kc;
+    if ((size_t)a.S * a.T * kMfmaTile > partial_capacity(a.N)) return SCAP_ERR_SHAPE;
 
-    hipLaunchKernelGGL(batch_compact_kernel, dim3((unsigned)a.S), dim3(kCompactWaves * kWave), 0, stream, a);
+    hipLaunchKernelGGL(batch_union_kernel, dim3((unsigned)a.Sl), dim3(kCompactWaves * kWave), 0, stream, a);
     if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
 
-    // reduction buffers: WAVES x 4 token groups x 128 columns (the final reduction needs less)
-    const size_t red = (size_t)WAVES * 4 * kMfmaTile * 4;
-    const size_t lds = lds_bytes(0, 0, red);
+    // reduction buffers: waves x 4 token groups x 128 columns (the final reduction needs less)
+    const size_t lds = lds_bytes(0, 0, (size_t)waves * 4 * kMfmaTile * 4);
     const dim3 grid((unsigned)(a.S * a.T));
-    const dim3 block(WAVES * kWave);
-    hipLaunchKernelGGL((gemm_mfma_kernel<WAVES, 2>), grid, block, lds, stream, a);
-    return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
+    const dim3 block(waves * kWave);
+#define SCAP_MFMA_CASE(WV, UBV)                                                                     \
+    if (waves == WV && ub == UBV) {                                                                  \
+        hipLaunchKernelGGL((gemm_mfma_kernel<WV, UBV>), grid, block, lds, stream, a);                \
+        return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;                             \
+    }
+    SCAP_MFMA_CASE(16, 1) SCAP_MFMA_CASE(16, 2) SCAP_MFMA_CASE(16, 4)
+    SCAP_MFMA_CASE(8, 1) SCAP_MFMA_CASE(8, 2) SCAP_MFMA_CASE(8, 4)
+#undef SCAP_MFMA_CASE
+    return SCAP_ERR_CONFIG;
 }
 
 }  // namespace scap

@@ -269,7 +269,7 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
     // Several tokens over bf16 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
-    const bool explicit_valu = cfg && (cfg->waves_per_group || cfg->unroll || cfg->lanes_per_row);
+    const bool explicit_valu = cfg && cfg->lanes_per_row;  // naming a lane layout selects the vector kernel
     if (a.B >= kMfmaMinTokens && wdt == kBF16 && a.mode != kModeFold && !explicit_valu)
         return launch_gemm_mfma(a, cfg, stream);
 
@@ -285,6 +285,8 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     const int elems = (wdt == kI8) ? 16 : 8;
     const int rc = plan_splits(a, lpr * elems, bt, kc, cfg && cfg->rows_per_group);
     if (rc != SCAP_OK) return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
+    a.Kl = a.Kc;
+    a.Sl = a.S;
 
     switch (wdt) {
         case kF16: return launch_wdt<kF16>(a, bt, waves, unroll, lpr, stream);

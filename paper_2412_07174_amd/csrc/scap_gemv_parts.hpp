@@ -56,14 +56,11 @@ struct Lds {
     float* red;  // reduction buffer; reuses the list space once the rows have been streamed
 };
 
-// Position of token b's value of list entry e in the list's value array.  DSTRIDE == 0: token-major
-// [BT][Kc] (a wavefront reads consecutive entries of one token).  DSTRIDE == kDPacked16: groups of 4
-// entries x 16 tokens x 4 values, so that the matrix-core kernel's lane (token, row group) finds its four
-// values in one 16-byte vector.
-constexpr int kDPacked16 = -16;
+// Position of token b's value of list entry e in Lds::d: token-major [BT][Kc] (a wavefront reads
+// consecutive entries of one token).
 template <int DSTRIDE>
 __device__ __forceinline__ int d_at(int b, int e, int Kc) {
-    return DSTRIDE == 0 ? b * Kc + e : (e >> 2) * 64 + b * 4 + (e & 3);
+    return b * Kc + e;
 }
 
 template <int WAVES, int BT>
@@ -194,13 +191,13 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
             }
         }
         if (tile == 0 && tid == 0) {
-            store_dev(&a.seg_cnt[a.B * a.S + split], cnt);  // union
+            store_dev(&a.seg_cnt[a.B * a.Sl + split], cnt);  // union
             if (BT == 1) {
                 store_dev(&a.seg_cnt[split], cnt);
             } else if (per_token) {
 #pragma unroll
                 for (int b = 0; b < BT; ++b)
-                    if (b < a.B) store_dev(&a.seg_cnt[b * a.S + split], ttotal[b]);
+                    if (b < a.B) store_dev(&a.seg_cnt[b * a.Sl + split], ttotal[b]);
             }
         }
     }
@@ -318,12 +315,12 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
     }
 
     if (!wants_lists) return;
-    // Each split left its ascending list in place at idx_out[b*K + split*Kc ...]; close the gaps.
+    // Each split left its ascending list in place at idx_out[b*K + segment*Kl ...]; close the gaps.
     // Every entry moves left or stays, so reading a block of source positions, synchronising, then
     // writing it, block after block from the left, never overwrites an entry that is still to be read.
     __syncthreads();
-    int* s_off = L.idx;               // [S] exclusive offsets
-    int* s_cnt = L.idx + kMaxSplits;  // [S] counts
+    int* s_off = L.idx;               // [Sl] exclusive offsets
+    int* s_cnt = L.idx + kMaxSplits;  // [Sl] counts
     const int nlist = a.B + 1;
     for (int l = 0; l < nlist; ++l) {
         const bool is_union = l == a.B;
@@ -333,11 +330,11 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
         __syncthreads();
         if (w == 0) {
             int run = 0;
-            for (int s0 = 0; s0 < a.S; s0 += kWave) {
+            for (int s0 = 0; s0 < a.Sl; s0 += kWave) {
                 const int sp = s0 + lane;
-                const int v = sp < a.S ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.S + sp]) : 0;
+                const int v = sp < a.Sl ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.Sl + sp]) : 0;
                 const int inc = wave_inclusive_scan(v);
-                if (sp < a.S) {
+                if (sp < a.Sl) {
                     s_off[sp] = run + inc - v;
                     s_cnt[sp] = v;
                 }
@@ -351,7 +348,7 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
             }
         }
         __syncthreads();
-        if (!is_union && a.idx_out != nullptr && a.S > 1) {
+        if (!is_union && a.idx_out != nullptr && a.Sl > 1) {
             int32_t* base = a.idx_out + (int64_t)l * a.K;
             constexpr int PER = 16;
             for (int c0 = 0; c0 < a.K; c0 += NT * PER) {
@@ -362,8 +359,8 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
                     dsts[j] = -1;
                     vals[j] = 0;
                     if (p < a.K) {
-                        const int seg = p / a.Kc;
-                        const int r = p - seg * a.Kc;
+                        const int seg = p / a.Kl;
+                        const int r = p - seg * a.Kl;
                         if (r < s_cnt[seg]) {
                             vals[j] = load_dev(&base[p]);
                             dsts[j] = s_off[seg] + r;

@@ -27,7 +27,8 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 //   [131072, +1 MiB)     int32 counter per column tile, one every 1 KiB so that the arrival tickets of
 //                        different tiles go to different memory channels; zero at rest
 //   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums
-//   [.., +68*(K+16384))  batched path (B >= 4): union list of every K split (index + 16 centred values per entry)
+//   [.., +68*(K+16384))  batched path (B >= 4): union list of every list segment (16 centred values and
+//                        the channel index per entry)
 // ---------------------------------------------------------------------------------------------
 constexpr size_t kOffHist = 4096;
 constexpr size_t kOffSums = 20480;
@@ -67,9 +68,10 @@ struct GemvArgs {
     int32_t* counters;
     int32_t* seg_cnt;
     float* partial;
-    int32_t* u_idx;  // batched path: union list of each K split, [S][Kc] channel indices
-    float* u_d;      // batched path: centred values of the union list, 16 tokens per entry
+    int32_t* u_idx;  // batched path: union list of each segment, [Sl][Kl] channel indices
+    float* u_d;      // batched path: centred values of the union list, [Sl][Kl][16 tokens]
     int K, N, B, Kc, S, T, mode, xdt;
+    int Kl, Sl;  // segmentation of the kept-channel lists: Sl segments of Kl channels (= S, Kc unless batched)
     float m, tau;
 };
 
