@@ -269,9 +269,11 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
     // Several tokens over bf16 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
-    const bool explicit_valu = cfg && cfg->lanes_per_row;  // naming a lane layout selects the vector kernel
-    if (a.B >= kMfmaMinTokens && wdt == kBF16 && a.mode != kModeFold && !explicit_valu)
-        return launch_gemm_mfma(a, cfg, stream);
+    // lanes_per_row = 16 asks for that kernel (its lane layout), 64 or 32 for the vector kernel.
+    const int lanes = cfg ? cfg->lanes_per_row : 0;
+    const bool mfma_ok = a.B >= kMfmaMinTokens && wdt == kBF16 && a.mode != kModeFold;
+    if (lanes == 16 && !mfma_ok) return SCAP_ERR_CONFIG;
+    if (mfma_ok && (lanes == 16 || (lanes == 0 && a.B >= kMfmaAutoTokens))) return launch_gemm_mfma(a, cfg, stream);
 
     int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0, lpr = 64;
     if (cfg) {

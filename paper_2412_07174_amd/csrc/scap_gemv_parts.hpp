@@ -94,20 +94,29 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
     const int c_begin = min(w * cpw, nchunk);
     const int c_end = min(c_begin + cpw, nchunk);
 
-    auto eval = [&](int b, int k, bool valid, float& d) -> bool {
-        d = 0.f;
-        if (b >= a.B || !valid) return false;
-        if (a.mode == kModeFold) {
-            d = a.m;
-            return true;
+    // Centred value and keep test of every token at channel k.  The loads of all tokens are issued
+    // together (no control flow between them) so that one memory latency covers the whole batch.
+    auto eval_all = [&](int k, bool valid, float (&d)[BT], bool (&keep)[BT]) {
+        uint32_t xb[BT];
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+            xb[b] = (valid && b < a.B && a.mode != kModeFold) ? (uint32_t)a.x[(int64_t)b * a.K + k] : 0u;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            const float xf = a.xdt == kBF16 ? bf16_bits_to_f32(xb[b]) : f16_bits_to_f32(xb[b]);
+            const bool live = valid && b < a.B;
+            float dv = xf - a.m;  // one fp32 subtraction
+            bool kp = fabsf(dv) > a.tau;  // strict; NaN compares false
+            if (a.mode == kModeDense) {
+                dv = xf;
+                kp = true;
+            } else if (a.mode == kModeFold) {
+                dv = a.m;
+                kp = true;
+            }
+            keep[b] = live && kp;
+            d[b] = keep[b] ? dv : 0.f;
         }
-        const float xf = act_to_f32(a.x, (int64_t)b * a.K + k, a.xdt);
-        if (a.mode == kModeDense) {
-            d = xf;
-            return true;
-        }
-        d = xf - a.m;               // one fp32 subtraction
-        return fabsf(d) > a.tau;    // strict; NaN compares false
     };
 
     {
@@ -119,12 +128,13 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
             const int k = k0 + c * kWave + lane;
             const bool valid = k < kend;
             bool any = false;
+            float d[BT];
+            bool keep[BT];
+            eval_all(k, valid, d, keep);
 #pragma unroll
             for (int b = 0; b < BT; ++b) {
-                float d;
-                const bool keep = eval(b, k, valid, d);
-                any |= keep;
-                if (per_token) tcount[b] += __popcll(__ballot(keep));
+                any |= keep[b];
+                if (per_token) tcount[b] += __popcll(__ballot(keep[b]));
             }
             ucount += __popcll(__ballot(any));
         }
@@ -167,17 +177,15 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
             bool any = false;
             float d[BT];
             bool keep[BT];
+            eval_all(k, valid, d, keep);
 #pragma unroll
-            for (int b = 0; b < BT; ++b) {
-                keep[b] = eval(b, k, valid, d[b]);
-                any |= keep[b];
-            }
+            for (int b = 0; b < BT; ++b) any |= keep[b];
             const uint64_t ub = __ballot(any);
             if (any) {
                 const int pos = ubase + lanes_below(ub);
                 L.idx[pos] = k;
 #pragma unroll
-                for (int b = 0; b < BT; ++b) L.d[d_at<DSTRIDE>(b, pos, a.Kc)] = keep[b] ? d[b] : 0.f;
+                for (int b = 0; b < BT; ++b) L.d[d_at<DSTRIDE>(b, pos, a.Kc)] = d[b];
                 if (BT == 1 && want_idx) store_dev(&a.idx_out[k0 + pos], k);
             }
             ubase += __popcll(ub);

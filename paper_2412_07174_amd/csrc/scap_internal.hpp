@@ -27,7 +27,7 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 //   [131072, +1 MiB)     int32 counter per column tile, one every 1 KiB so that the arrival tickets of
 //                        different tiles go to different memory channels; zero at rest
 //   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums
-//   [.., +68*(K+16384))  batched path (B >= 4): union list of every list segment (16 centred values and
+//   [.., +68*(K+16384))  batched path (B >= 2): union list of every list segment (16 centred values and
 //                        the channel index per entry)
 // ---------------------------------------------------------------------------------------------
 constexpr size_t kOffHist = 4096;
@@ -78,8 +78,11 @@ struct GemvArgs {
 // Enqueue one GEMV (sparse / dense / fold mode).  Returns a scap_status.
 int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
 
-// Batched tokens over bf16 weights on the matrix cores (B >= kMfmaMinTokens).
-constexpr int kMfmaMinTokens = 4;
+// Batched tokens over bf16 weights on the matrix cores: possible from kMfmaMinTokens tokens on (the
+// workspace then carries the union lists), chosen by default from kMfmaAutoTokens on -- at 4 tokens the
+// single-launch vector kernel is still faster (measured 31 vs 41 us on 14336 x 4096).
+constexpr int kMfmaMinTokens = 2;
+constexpr int kMfmaAutoTokens = 5;
 int launch_gemm_mfma(const GemvArgs& a, const scap_launch_cfg* cfg, hipStream_t stream);
 
 // Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).

@@ -209,16 +209,16 @@ def test_headline_layer_three_sparsities_and_dense():
 
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
-@pytest.mark.parametrize("path", ["auto", "vector"])
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix"])
 @pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 13, 16])
 def test_batched_tokens_moderate(B, path):
-    """auto: bf16 weights and B >= 4 run on the matrix cores; vector: the same batch forced onto the FMA kernel."""
+    """auto: bf16 weights and B >= 5 run on the matrix cores; vector / matrix: the batch forced onto one kernel."""
     K, N = 2500, 1032
     W = wl.weights(K, N, 501, BF16)
     layer = Layer(W, BF16, B=16)
     X = wl.swiglu(B, K, 502 + B, BF16)
     bf = np.random.default_rng(503).standard_normal(N).astype(np.float32)
-    cfg = None if path == "auto" else (8, 0, 8 if B <= 4 else 4, 64)
+    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16)}[path]
     for tau in (0.0, 0.15, 0.8, 50.0):
         say(f"batched B={B} path={path} tau={tau}")
         check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"B={B} {path} tau={tau}")
@@ -238,7 +238,7 @@ def test_batched_matrix_core_edge_cases():
     for rows in (0, 64, 128, 832):
         for tau in (0.0, 0.3, 1.5, 2.5):
             say(f"matrix-core edge rows={rows} tau={tau}")
-            check_against_oracle(layer, X, BF16, 0.01, tau, None, cfg=None if rows == 0 else (0, rows, 0, 0),
+            check_against_oracle(layer, X, BF16, 0.01, tau, None, cfg=(0, rows, 0, 16),
                                  what=f"mfma rows={rows} tau={tau}")
 
 
