@@ -43,6 +43,96 @@ def algorithmic_bytes(nnz_rows: float, K: int, N: int, B: int, wbytes: int) -> f
     return nnz_rows * N * wbytes + B * K * 2 + N * 4 + B * N * 4
 
 
+def run_suite(args, torch, scap, wl, dev):
+    """Every benchmark configuration, one line per (layer, batch, target sparsity): us per launch and GB/s
+    on the bytes actually needed.  Weights are random on the device (values do not matter for timing),
+    inputs come from the seeded generators, thresholds from scap_calibrate.  Prints ONE JSON line."""
+    steps = max(100, args.steps // 10)
+
+    def dev16(bits, dt):
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+        return t.view(torch.float16 if dt == wl.F16 else torch.bfloat16).to(dev)
+
+    def timed(fn):
+        for i in range(10):
+            fn(i)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(steps):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e3  # us
+
+    rows = []
+
+    def run_site(cfg_no, site, batches, targets, est):
+        K, N = site.K, site.N
+        wbytes = 1 if site.wdt == wl.I8 else 2
+        if site.wdt == wl.I8:
+            W0 = torch.randint(-127, 128, (K, N), dtype=torch.int8, device=dev)
+            scale = (torch.rand(N, device=dev) * 1e-3 + 1e-4).to(torch.float16)
+        else:
+            W0 = (torch.randn(K, N, device=dev) * 0.02).to(torch.float16 if site.wdt == wl.F16 else torch.bfloat16)
+            scale = None
+        R = max(2, -(-(1 << 30) // (K * N * wbytes)))
+        Ws = [W0] + [W0.clone() for _ in range(R - 1)]
+        X = dev16(site.draw(64, site.seed_test), site.xdt)
+        calib = dev16(site.draw(128, site.seed_calib), site.xdt)
+        ws = scap.Workspace(K, N, max(batches))
+        unz = torch.zeros(1, dtype=torch.int32, device=dev)
+        taus = {s: scap.calibrate(calib, s, est, workspace=ws) for s in targets}
+        for B in batches:
+            y = torch.empty((B, N), dtype=torch.float32, device=dev)
+
+            def xs(i):
+                o = (i * B) % (64 - B + 1)
+                return X[o] if B == 1 else X[o:o + B]
+
+            t_dense = timed(lambda i: scap.dense_fc(Ws[i % R], xs(i), None, col_scale=scale, y=y, workspace=ws))
+            rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
+                         "target": None, "density": 1.0, "us": round(t_dense, 2),
+                         "GBps": round(algorithmic_bytes(K, K, N, B, wbytes) / t_dense / 1e3, 1)})
+            for s in targets:
+                m, tau = taus[s]
+                dens = 0.0
+                for i in range(8):
+                    scap.sparse_fc(Ws[0], xs(i), m, tau, None, col_scale=scale, y=y, union_nnz_out=unz, workspace=ws)
+                    dens += unz.item() / K / 8
+                t = timed(lambda i: scap.sparse_fc(Ws[i % R], xs(i), m, tau, None, col_scale=scale, y=y, workspace=ws))
+                rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
+                             "target": s, "density": round(dens, 4), "us": round(t, 2),
+                             "GBps": round(algorithmic_bytes(dens * K, K, N, B, wbytes) / t / 1e3, 1),
+                             "vs_dense": round(t_dense / t, 3)})
+        del Ws, W0
+        torch.cuda.empty_cache()
+
+    run_site(1, wl.sites(1)[0], (1,), (0.5,), scap.MODE_MEDIAN)
+    for st in wl.sites(2):
+        run_site(2, st, (1,), (0.5, 0.7, 0.9), scap.MODE_MEDIAN)
+    for st in wl.sites(3):
+        run_site(3, st, (1,), (0.5,), scap.MODE_MEDIAN)
+    for st in wl.sites(4):
+        run_site(4, st, (1, 4, 16), (0.5, 0.7, 0.9), scap.MODE_ZERO)
+    c5 = wl.sites(5)
+    run_site(5, c5[0], (1,), (0.4,), scap.MODE_MEDIAN)
+    run_site(5, c5[1], (1, 8), (0.7,), scap.MODE_MEDIAN)
+
+    layer3 = [r for r in rows if r["cfg"] == 3]
+    summary = {"mistral_layer_fc_set_dense_us": round(sum(r["us"] for r in layer3 if r["target"] is None), 2),
+               "mistral_layer_fc_set_s50_us": round(sum(r["us"] for r in layer3 if r["target"] == 0.5), 2)}
+    print(json.dumps({"suite": rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
+                      "note": "GB/s = (rows read x N x sizeof(w) + x + bias + y) / time; density = union of the "
+                              "batch's masks / K"}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +142,9 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sweep", action="store_true", help="only the headline point")
     ap.add_argument("--cfg", type=str, default="", help="launch shape waves,rows,unroll (tuning)")
+    ap.add_argument("--suite", action="store_true",
+                    help="time every benchmark configuration (layers of configs 1-5, batches, sparsities) instead "
+                         "of the headline run")
     ap.add_argument("--counter-pass", action="store_true",
                     help="for rocprofv3 --pmc runs: a few eager launches of a copy of known size, the headline "
                          "sparse FC and the dense FC, then exit (no timing, no JSON)")
@@ -72,6 +165,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     cfg = tuple(int(v) for v in args.cfg.split(",")) if args.cfg else None
+    if args.suite:
+        return run_suite(args, torch, scap, wl, dev)
 
     site = wl.sites(4)[1]  # mistral_down: 14336 -> 4096, bf16, SiLU(g)*u inputs
     K, N = site.K, site.N
