@@ -18,6 +18,7 @@ _SRC = os.path.join(_HERE, "scap_oracle.c")
 _LIB = os.path.join(_HERE, "libscap_oracle.so")
 
 F16, BF16, I8 = 0, 1, 2
+F32 = 3  # activations only: fp32 values (the gated product inside a SwiGLU block)
 MODE_ZERO, MODE_MEAN, MODE_MEDIAN, MODE_HIST = 0, 1, 2, 3
 EST = {"zero": MODE_ZERO, "mean": MODE_MEAN, "median": MODE_MEDIAN, "hist": MODE_HIST}
 
@@ -52,6 +53,9 @@ def _load():
     lib.oracle_fold_bias.argtypes = [vp, vp, i64, i64, i32, vp, f32, vp]
     lib.oracle_calibrate.restype = i32
     lib.oracle_calibrate.argtypes = [vp, i64, i64, i32, f32, i32, vp, vp]
+    lib.oracle_swiglu_block.restype = i32
+    lib.oracle_swiglu_block.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, i32, f32, f32, vp, vp,
+                                        f32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32]
     lib.oracle_ffn_sparsity.restype = ctypes.c_double
     lib.oracle_ffn_sparsity.argtypes = [ctypes.c_double, ctypes.c_double]
     _lib = lib
@@ -91,7 +95,7 @@ def sparse_fc(W: np.ndarray, x: np.ndarray, eta: float, tau: float, b_fused: Opt
     lib = _load()
     W = _w_array(W, wdt)
     K, N = W.shape
-    x = np.ascontiguousarray(x, dtype=np.uint16).reshape(-1, K)
+    x = np.ascontiguousarray(x, dtype=np.float32 if xdt == F32 else np.uint16).reshape(-1, K)
     B = x.shape[0]
     if b_fused is not None:
         b_fused = np.ascontiguousarray(b_fused, dtype=np.float32)
@@ -109,6 +113,43 @@ def sparse_fc(W: np.ndarray, x: np.ndarray, eta: float, tau: float, b_fused: Opt
         raise ValueError(f"oracle_sparse_fc failed: {rc}")
     return {"y": y, "idx": [idx[b, :nnz[b]].copy() for b in range(B)], "nnz": nnz,
             "union_idx": uidx[:unnz[0]].copy(), "union_nnz": int(unnz[0])}
+
+
+def swiglu_block(W_gate: np.ndarray, W_up: np.ndarray, W_down: np.ndarray, x: np.ndarray, eta_x: float,
+                 tau_x: float, eta_z: float, tau_z: float, wdt: int, xdt: int, b_gate=None, b_up=None, b_down=None,
+                 gate_scale=None, up_scale=None, down_scale=None, nthreads: int = 1) -> dict:
+    """SwiGLU block of one token (Appendix B Alg. 2 with the centred FC of Alg. 3).
+    Returns dict(g, u, z [F] f32, y [N] f32, idx_x, idx_z int32 arrays)."""
+    lib = _load()
+    W_gate, W_up, W_down = _w_array(W_gate, wdt), _w_array(W_up, wdt), _w_array(W_down, wdt)
+    K, F = W_gate.shape
+    assert W_up.shape == (K, F) and W_down.shape[0] == F
+    N = W_down.shape[1]
+    x = np.ascontiguousarray(x, dtype=np.uint16).reshape(K)
+
+    def f32(a, n):
+        if a is None:
+            return None
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        assert a.shape == (n,)
+        return a
+
+    def u16(a):
+        return None if a is None else np.ascontiguousarray(a, dtype=np.uint16)
+
+    b_gate, b_up, b_down = f32(b_gate, F), f32(b_up, F), f32(b_down, N)
+    gate_scale, up_scale, down_scale = u16(gate_scale), u16(up_scale), u16(down_scale)
+    g, u, z = (np.empty(F, dtype=np.float32) for _ in range(3))
+    y = np.empty(N, dtype=np.float32)
+    idx_x, idx_z = np.full(K, -1, dtype=np.int32), np.full(F, -1, dtype=np.int32)
+    nnz_x, nnz_z = np.zeros(1, dtype=np.int32), np.zeros(1, dtype=np.int32)
+    rc = lib.oracle_swiglu_block(_ptr(W_gate), _ptr(gate_scale), _ptr(W_up), _ptr(up_scale), _ptr(W_down),
+                                 _ptr(down_scale), K, F, N, wdt, _ptr(x), xdt, eta_x, tau_x, _ptr(b_gate), _ptr(b_up),
+                                 eta_z, tau_z, _ptr(b_down), _ptr(g), _ptr(u), _ptr(z), _ptr(y), _ptr(idx_x),
+                                 _ptr(nnz_x), _ptr(idx_z), _ptr(nnz_z), nthreads)
+    if rc != 0:
+        raise ValueError(f"oracle_swiglu_block failed: {rc}")
+    return {"g": g, "u": u, "z": z, "y": y, "idx_x": idx_x[:nnz_x[0]].copy(), "idx_z": idx_z[:nnz_z[0]].copy()}
 
 
 def dense_fc(W: np.ndarray, x: np.ndarray, bias: Optional[np.ndarray], wdt: int, xdt: int,

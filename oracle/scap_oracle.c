@@ -19,6 +19,8 @@
  *                       y = (x_eta * Mask) W + b_fused                (Appendix B, Alg. 3)
  *   mode estimate       mean or median of the calibration sample      (Section 3, "Determination
  *                                                                      of mode value")
+ *   SwiGLU block        z = scap_fc(x; W_up) * silu(scap_fc(x; W_gate));
+ *                       y = scap_fc(z; W_down)                        (Appendix B, Alg. 2)
  *   FFN sparsity        2/3 s_x + 1/3 s_gated                         (Appendix B)
  *
  * Readings of points the paper leaves open (also listed in the design notes):
@@ -34,6 +36,8 @@
  *   - with several tokens each token has its own mask (Eq. 2 is elementwise); the union of
  *     the masks is reported because it is the set of weight rows a kernel has to read
  *     (Appendix C);
+ *   - inside a SwiGLU block the gated product is an fp32 vector (it is never stored in 16 bits) and
+ *     the last call of Alg. 2 takes it, not x, as its input;
  *   - int8 weights are symmetric with one fp16 scale per output channel: w = scale[o]*q[i,o].
  *
  * Parity unpinned: the histogram mode estimator (ORACLE_MODE_HIST).  The paper names kernel
@@ -49,6 +53,7 @@
 #define ORACLE_F16 0
 #define ORACLE_BF16 1
 #define ORACLE_I8 2
+#define ORACLE_F32 3 /* activations only: plain fp32 values (the gated product inside a SwiGLU block) */
 
 #define ORACLE_MODE_ZERO 0
 #define ORACLE_MODE_MEAN 1
@@ -101,13 +106,23 @@ static double weight_at(const void *W, int wdt, int64_t pos)
 }
 
 /* ---------------------------------------------------------------- Alg. 3, steps 1-2 */
+/* activation i of a vector stored as 16-bit codes, or as fp32 when xdt == ORACLE_F32 */
+static float act_at(const void *x, int xdt, int64_t i)
+{
+    if (xdt == ORACLE_F32)
+        return ((const float *)x)[i];
+    return oracle_to_f32(((const uint16_t *)x)[i], xdt);
+}
+
+static size_t act_bytes(int xdt) { return xdt == ORACLE_F32 ? 4 : 2; }
+
 /* d[i] = x[i] - eta (fp32), keep[i] = |d[i]| > tau (strict, Eq. 2).  Returns the count kept. */
-int64_t oracle_centre_threshold(const uint16_t *x, int xdt, int64_t K, float eta, float tau,
+int64_t oracle_centre_threshold(const void *x, int xdt, int64_t K, float eta, float tau,
                                 float *d, uint8_t *keep)
 {
     int64_t cnt = 0;
     for (int64_t i = 0; i < K; ++i) {
-        volatile float xf = oracle_to_f32(x[i], xdt);
+        volatile float xf = act_at(x, xdt, i);
         volatile float di = xf - eta; /* one IEEE fp32 subtraction */
         int k = fabsf(di) > tau;      /* NaN compares false */
         d[i] = di;
@@ -146,12 +161,12 @@ static void fc_columns(const void *W, const uint16_t *col_scale, int64_t N, int 
 
 /*
  * Centred, thresholded FC for B tokens (Alg. 3 per token; Eq. 2 is elementwise over X_ij).
- *   W [K,N] K-major; x [B,K]; y [B,N] fp32; idx [B,K] (ascending kept channels, first nnz[b]
+ *   W [K,N] K-major; x [B,K] (16-bit codes, or fp32 values for ORACLE_F32); y [B,N] fp32; idx [B,K] (ascending kept channels, first nnz[b]
  *   valid per token) or NULL; nnz [B] or NULL; union_idx [K] / union_nnz [1] or NULL.
  * nthreads > 1 splits the output columns over that many threads; the loop nest is unchanged.
  */
 int oracle_sparse_fc(const void *W, const uint16_t *col_scale, int64_t K, int64_t N, int wdt,
-                     const uint16_t *x, int xdt, int64_t B, float eta, float tau,
+                     const void *x, int xdt, int64_t B, float eta, float tau,
                      const float *b_fused, float *y, int32_t *idx, int32_t *nnz,
                      int32_t *union_idx, int32_t *union_nnz, int nthreads)
 {
@@ -164,7 +179,7 @@ int oracle_sparse_fc(const void *W, const uint16_t *col_scale, int64_t K, int64_
     uint8_t *any = (uint8_t *)calloc((size_t)K, 1);
     int32_t *list = (int32_t *)malloc((size_t)K * sizeof(int32_t));
     for (int64_t b = 0; b < B; ++b) {
-        oracle_centre_threshold(x + b * K, xdt, K, eta, tau, d, keep);
+        oracle_centre_threshold((const char *)x + (size_t)(b * K) * act_bytes(xdt), xdt, K, eta, tau, d, keep);
         int64_t cnt = 0;
         for (int64_t i = 0; i < K; ++i)
             if (keep[i]) {
@@ -368,6 +383,45 @@ int oracle_calibrate(const uint16_t *X, int64_t n, int64_t K, int xdt, float s, 
     *eta_out = eta;
     free(v);
     return 0;
+}
+
+/*
+ * SwiGLU feed-forward block of one token, Appendix B Alg. 2, each of its three scap_fc calls being the
+ * centred form of Alg. 3 (the paper notes the two can be merged; eta = 0 and a NULL bias give Alg. 2 as
+ * printed):
+ *     g = scap_fc(tau_x, x, W_gate)     u = scap_fc(tau_x, x, W_up)        one mask for both
+ *     z = u * silu(g)                   silu(t) = t / (1 + exp(-t))
+ *     y = scap_fc(tau_z, z, W_down)     (the printed listing passes x here; the gated product is meant)
+ * g and u are the fp32 outputs of the first two calls; the product is formed in fp64 and rounded once
+ * to fp32; z stays fp32 (it is never stored in 16 bits), so the second pruner compares
+ * |fp32(z) - eta_z| with tau_z in fp32 exactly as the first compares the input.
+ * Outputs: g, u, z [F], y [N]; idx_x/nnz_x and idx_z/nnz_z as in oracle_sparse_fc (may be NULL).
+ */
+int oracle_swiglu_block(const void *W_gate, const uint16_t *gate_scale, const void *W_up,
+                        const uint16_t *up_scale, const void *W_down, const uint16_t *down_scale,
+                        int64_t K, int64_t F, int64_t N, int wdt, const void *x, int xdt,
+                        float eta_x, float tau_x, const float *b_gate, const float *b_up,
+                        float eta_z, float tau_z, const float *b_down,
+                        float *g, float *u, float *z, float *y,
+                        int32_t *idx_x, int32_t *nnz_x, int32_t *idx_z, int32_t *nnz_z, int nthreads)
+{
+    if (!g || !u || !z || !y)
+        return -1;
+    int rc = oracle_sparse_fc(W_gate, gate_scale, K, F, wdt, x, xdt, 1, eta_x, tau_x, b_gate, g,
+                              idx_x, nnz_x, NULL, NULL, nthreads);
+    if (rc)
+        return rc;
+    rc = oracle_sparse_fc(W_up, up_scale, K, F, wdt, x, xdt, 1, eta_x, tau_x, b_up, u,
+                          NULL, NULL, NULL, NULL, nthreads);
+    if (rc)
+        return rc;
+    for (int64_t i = 0; i < F; ++i) {
+        double t = (double)g[i];
+        double silu = t / (1.0 + exp(-t));
+        z[i] = (float)((double)u[i] * silu);
+    }
+    return oracle_sparse_fc(W_down, down_scale, F, N, wdt, z, ORACLE_F32, 1, eta_z, tau_z, b_down, y,
+                            idx_z, nnz_z, NULL, NULL, nthreads);
 }
 
 /* Appendix B: three equal-sized FCs, Up and Gate share the input sparsity s_x. */
