@@ -124,10 +124,77 @@ def run_suite(args, torch, scap, wl, dev):
     run_site(5, c5[0], (1,), (0.4,), scap.MODE_MEDIAN)
     run_site(5, c5[1], (1, 8), (0.7,), scap.MODE_MEDIAN)
 
+    # Feed-forward blocks (Alg. 2): the fused two-launch block against the same work as separate calls
+    # (sparse_fc on [gate | up], torch silu * up and cast to 16 bits, sparse_fc on down) and the dense block.
+    blocks = []
+
+    def run_block(name, K, F, N, targets):
+        dt = torch.bfloat16
+        Wg = (torch.randn(K, F, device=dev) * 0.02).to(dt)
+        Wu = (torch.randn(K, F, device=dev) * 0.02).to(dt)
+        Wd0 = (torch.randn(F, N, device=dev) * 0.02).to(dt)
+        R = max(2, -(-(1 << 30) // (3 * K * F * 2)))
+        Wcat = [torch.cat([Wg, Wu], dim=1).contiguous() for _ in range(R)]
+        Wgu = [scap.pack_gate_up(Wg, Wu) for _ in range(R)]
+        Wd = [Wd0.clone() for _ in range(R)]
+        del Wg, Wu
+        site = wl.Site(name, K, 2 * F, wl.BF16, wl.BF16, "prenorm", 128, 4001, 4002, 4003)
+        X = dev16(site.draw(64, site.seed_test), wl.BF16)
+        calib = dev16(site.draw(128, site.seed_calib), wl.BF16)
+        ws = scap.Workspace(K, N, 1, F=F)
+        ycat = torch.empty((1, 2 * F), dtype=torch.float32, device=dev)
+        y = torch.empty((1, N), dtype=torch.float32, device=dev)
+        nz = torch.zeros(1, dtype=torch.int32, device=dev)
+        nx = torch.zeros(1, dtype=torch.int32, device=dev)
+
+        def dense_block(i):
+            scap.dense_fc(Wcat[i % R], X[i % 64], None, y=ycat, workspace=ws)
+            z = (torch.nn.functional.silu(ycat[:, :F]) * ycat[:, F:]).to(dt)
+            scap.dense_fc(Wd[i % R], z, None, y=y, workspace=ws)
+
+        t_dense = timed(dense_block)
+        blocks.append({"block": name, "K": K, "F": F, "N": N, "variant": "dense, 2 calls + torch silu*up", "target": None,
+                       "us": round(t_dense, 2)})
+        for s in targets:
+            m_x, tau_x = scap.calibrate(calib, s, scap.MODE_MEDIAN, workspace=ws)
+            bgu = scap.fold_bias(Wgu[0], m_x, None, workspace=ws)
+            bcat = scap.fold_bias(Wcat[0], m_x, None, workspace=ws)
+            zc = torch.empty((32, F), dtype=dt, device=dev)
+            for j in range(32):
+                scap.sparse_fc(Wcat[0], calib[j], m_x, tau_x, bcat, y=ycat, workspace=ws)
+                zc[j] = (torch.nn.functional.silu(ycat[0, :F]) * ycat[0, F:]).to(dt)
+            _, tau_z = scap.calibrate(zc, s, scap.MODE_ZERO, workspace=ws)
+
+            def unfused(i):
+                scap.sparse_fc(Wcat[i % R], X[i % 64], m_x, tau_x, bcat, y=ycat, workspace=ws)
+                z = (torch.nn.functional.silu(ycat[:, :F]) * ycat[:, F:]).to(dt)
+                scap.sparse_fc(Wd[i % R], z, 0.0, tau_z, None, y=y, workspace=ws)
+
+            def fused(i):
+                scap.swiglu_block(Wgu[i % R], Wd[i % R], X[i % 64], m_x, tau_x, bgu, 0.0, tau_z, None, y=y, workspace=ws)
+
+            dx = dz = 0.0
+            for i in range(8):
+                scap.sparse_fc(Wcat[0], X[i], m_x, tau_x, bcat, y=ycat, nnz_out=nx, workspace=ws)
+                scap.swiglu_block(Wgu[0], Wd[0], X[i], m_x, tau_x, bgu, 0.0, tau_z, None, y=y, nnz_z_out=nz, workspace=ws)
+                dx += nx.item() / K / 8
+                dz += nz.item() / F / 8
+            t_u, t_f = timed(unfused), timed(fused)
+            nbytes = dx * K * 2 * F * 2 + dz * F * N * 2 + K * 2 + 2 * F * 4 + N * 4
+            for variant, t in (("sparse, 2 calls + torch silu*up", t_u), ("sparse, fused block", t_f)):
+                blocks.append({"block": name, "K": K, "F": F, "N": N, "variant": variant, "target": s,
+                               "density_x": round(dx, 4), "density_z": round(dz, 4), "us": round(t, 2),
+                               "GBps": round(nbytes / t / 1e3, 1), "vs_dense": round(t_dense / t, 3)})
+        del Wcat, Wgu, Wd
+        torch.cuda.empty_cache()
+
+    run_block("mistral7b_ffn", 4096, 14336, 4096, (0.5, 0.7, 0.9))
+    run_block("llama2_7b_ffn", 4096, 11008, 4096, (0.5,))
+
     layer3 = [r for r in rows if r["cfg"] == 3]
     summary = {"mistral_layer_fc_set_dense_us": round(sum(r["us"] for r in layer3 if r["target"] is None), 2),
                "mistral_layer_fc_set_s50_us": round(sum(r["us"] for r in layer3 if r["target"] == 0.5), 2)}
-    print(json.dumps({"suite": rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
+    print(json.dumps({"suite": rows, "blocks": blocks, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
                       "note": "GB/s = (rows read x N x sizeof(w) + x + bias + y) / time; density = union of the "
                               "batch's masks / K"}))
     return 0

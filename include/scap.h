@@ -167,6 +167,47 @@ int scap_dense_fc(const void* W, const void* col_scale, int64_t K, int64_t N, in
                   const scap_launch_cfg* cfg);
 
 /*
+ * ASYNC, offline.  Column layout of the fused block's first matrix: interleaves two row-major [rows, F]
+ * arrays in groups of 4 columns, out[r, 8j + 0..3] = gate[r, 4j + 0..3], out[r, 8j + 4..7] = up[r, 4j + 0..3].
+ * Serves the weights (rows = K; elem_bytes 2, or 1 for int8), their column scales (rows = 1, elem_bytes 2)
+ * and biases (rows = 1, elem_bytes 4).  Gate and up share one input mask (Section 4, "Implementation"), so
+ * the pair is one layer with 2F columns; this order puts matching gate and up columns in one 16-byte load.
+ *   gate, up, out  DEVICE, 16-byte aligned; F a multiple of 4; out must not overlap the inputs.
+ */
+int scap_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F, int elem_bytes, void* out,
+                      void* stream);
+
+/* Bytes of workspace scap_swiglu_block needs (hidden size K, intermediate size F, output size N, B tokens);
+ * such a workspace also serves every other call on layers no larger than the block's two.  0 = out of range. */
+size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B);
+
+/*
+ * ASYNC.  SwiGLU feed-forward block of one token (Appendix B, Alg. 2; each scap_fc in the centred form of
+ * Alg. 3):   z = scap_fc(x; W_up) * silu(scap_fc(x; W_gate)),   y = scap_fc(z; W_down)
+ * in two launches.  The first reads the kept rows of the interleaved gate|up matrix; the workgroup that
+ * completes a column tile forms z in fp32 (silu(t) = t / (1 + exp(-t))), subtracts m_z, applies the strict
+ * threshold tau_z and leaves the kept channels compacted in the workspace.  The second takes those lists as
+ * its input.  z is never rounded to 16 bits.
+ *   W_gu, gu_scale   DEVICE  [K, 2F] from scap_pack_gate_up (and its packed fp16 scales for int8, else NULL).
+ *   W_down, down_scale DEVICE [F, N] K-major (scales for int8, else NULL); same dtype wdt as W_gu.
+ *   x                DEVICE  [K], dtype xdt.   B must be 1 (larger batches: SCAP_ERR_UNIMPL).
+ *   m_x, tau_x       constants of the block input;  b_gu_fused  DEVICE fp32 [2F] packed fused bias or NULL
+ *                    (scap_fold_bias on W_gu with the packed bias gives it).
+ *   m_z, tau_z       constants of the gated product;  b_down_fused  DEVICE fp32 [N] or NULL.
+ *   y                DEVICE  fp32 [N], fully overwritten.
+ *   z_out            DEVICE  fp32 [F] or NULL: the gated product before centring.
+ *   idx_z_out        DEVICE  int32 [F] or NULL: kept channels of z, ascending, first nnz_z_out[0] valid.
+ *   nnz_z_out        DEVICE  int32 [1] or NULL (required with idx_z_out).
+ *   workspace        scap_swiglu_workspace_bytes(K, F, N, 1) bytes, initialised.
+ * F must be a multiple of 4 (8 for int8) and at most 262144.
+ */
+int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale, int64_t K,
+                      int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x, float tau_x,
+                      const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,
+                      float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/*
  * ASYNC.  Streaming-read probe used to measure the HBM read ceiling of the box: reads `bytes` bytes at
  * `src` (DEVICE, 16-byte aligned, bytes a multiple of 16) with 2048 workgroups and stores one uint32
  * checksum per workgroup to out (DEVICE, uint32 [SCAP_PROBE_SLOTS]).

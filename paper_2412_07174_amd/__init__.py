@@ -7,6 +7,6 @@ library has not been built, loading fails loudly.
 """
 from .binding import (  # noqa: F401
     BF16, F16, I8, MODE_HIST, MODE_MEAN, MODE_MEDIAN, MODE_ZERO, LaunchCfg, ScapError, Workspace,
-    calibrate, dense_fc, fold_bias, lib_path, load_library, read_probe, sparse_fc, status_string,
-    version, workspace_bytes,
+    calibrate, dense_fc, fold_bias, lib_path, load_library, pack_gate_up, read_probe, sparse_fc, status_string,
+    swiglu_block, swiglu_workspace_bytes, version, workspace_bytes,
 )

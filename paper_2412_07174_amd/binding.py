@@ -19,6 +19,7 @@ _TORCH_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8}
 EXPORTS = (
     "scap_status_string", "scap_version", "scap_workspace_bytes", "scap_workspace_init", "scap_calibrate",
     "scap_fold_bias", "scap_sparse_fc", "scap_sparse_fc_ex", "scap_dense_fc", "scap_read_probe",
+    "scap_pack_gate_up", "scap_swiglu_workspace_bytes", "scap_swiglu_block",
 )
 
 
@@ -70,6 +71,13 @@ def load_library() -> ctypes.CDLL:
     lib.scap_sparse_fc_ex.argtypes = fc + [ctypes.POINTER(LaunchCfg)]
     lib.scap_dense_fc.restype = i32
     lib.scap_dense_fc.argtypes = [vp, vp, i64, i64, i32, vp, i32, i64, vp, vp, vp, sz, vp, ctypes.POINTER(LaunchCfg)]
+    lib.scap_pack_gate_up.restype = i32
+    lib.scap_pack_gate_up.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+    lib.scap_swiglu_workspace_bytes.restype = sz
+    lib.scap_swiglu_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    lib.scap_swiglu_block.restype = i32
+    lib.scap_swiglu_block.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i32, i64, f32, f32, vp, f32, f32, vp, vp,
+                                      vp, vp, vp, vp, sz, vp]
     lib.scap_read_probe.restype = i32
     lib.scap_read_probe.argtypes = [vp, sz, vp, vp]
     _lib = lib
@@ -86,6 +94,10 @@ def version() -> int:
 
 def workspace_bytes(K: int, N: int, B: int = 1) -> int:
     return int(load_library().scap_workspace_bytes(K, N, B))
+
+
+def swiglu_workspace_bytes(K: int, F: int, N: int, B: int = 1) -> int:
+    return int(load_library().scap_swiglu_workspace_bytes(K, F, N, B))
 
 
 def _check(rc: int, where: str) -> None:
@@ -122,8 +134,9 @@ def _cfg(cfg):
 class Workspace:
     """Caller-owned scratch for one stream: a torch byte buffer passed once to scap_workspace_init."""
 
-    def __init__(self, K: int, N: int, B: int = 1, device="cuda", stream=None):
-        nbytes = workspace_bytes(K, N, B)
+    def __init__(self, K: int, N: int, B: int = 1, device="cuda", stream=None, F: int = 0):
+        """K x N layer and B tokens; with F > 0 a SwiGLU block K -> F -> N (scap_swiglu_workspace_bytes)."""
+        nbytes = swiglu_workspace_bytes(K, F, N, B) if F else workspace_bytes(K, N, B)
         if nbytes == 0:
             raise ScapError(-2, "scap_workspace_bytes")
         self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -189,6 +202,40 @@ def dense_fc(W: torch.Tensor, x: torch.Tensor, bias: Optional[torch.Tensor] = No
     rc = lib.scap_dense_fc(_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(x), _code(x, "x"), B, _ptr(bias),
                            _ptr(y), _ptr(workspace.buf), workspace.nbytes, _stream(stream), _cfg(cfg))
     _check(rc, "scap_dense_fc")
+    return y
+
+
+def pack_gate_up(gate: torch.Tensor, up: torch.Tensor, stream=None) -> torch.Tensor:
+    """[rows, 2F] (or [2F]) interleaving of two [rows, F] (or [F]) tensors in groups of 4 columns."""
+    assert gate.shape == up.shape and gate.dtype == up.dtype and gate.is_contiguous() and up.is_contiguous()
+    rows = 1 if gate.dim() == 1 else gate.shape[0]
+    F = gate.shape[-1]
+    out = torch.empty(gate.shape[:-1] + (2 * F,), dtype=gate.dtype, device=gate.device)
+    rc = load_library().scap_pack_gate_up(_ptr(gate), _ptr(up), rows, F, gate.element_size(), _ptr(out), _stream(stream))
+    _check(rc, "scap_pack_gate_up")
+    return out
+
+
+def swiglu_block(W_gu: torch.Tensor, W_down: torch.Tensor, x: torch.Tensor, m_x: float, tau_x: float,
+                 b_gu_fused: Optional[torch.Tensor], m_z: float, tau_z: float, b_down_fused: Optional[torch.Tensor], *,
+                 gu_scale=None, down_scale=None, y: Optional[torch.Tensor] = None, z_out=None, idx_z_out=None,
+                 nnz_z_out=None, workspace: Workspace, stream=None) -> torch.Tensor:
+    """y[N] of the SwiGLU block: W_gu is the packed [K, 2F] gate|up matrix, W_down is [F, N]."""
+    lib = load_library()
+    K, F2 = W_gu.shape
+    F, N = W_down.shape
+    if F2 != 2 * F:
+        raise ValueError(f"W_gu has {F2} columns, W_down has {F} rows")
+    B = 1 if x.dim() == 1 else x.shape[0]
+    if y is None:
+        y = torch.empty((B, N), dtype=torch.float32, device=W_gu.device)
+    if _code(W_gu, "W_gu") != _code(W_down, "W_down"):
+        raise TypeError("W_gu and W_down must have one dtype")
+    rc = lib.scap_swiglu_block(_ptr(W_gu), _ptr(gu_scale), _ptr(W_down), _ptr(down_scale), K, F, N, _code(W_gu, "W_gu"),
+                               _ptr(x), _code(x, "x"), B, float(m_x), float(tau_x), _ptr(b_gu_fused), float(m_z),
+                               float(tau_z), _ptr(b_down_fused), _ptr(y), _ptr(z_out), _ptr(idx_z_out),
+                               _ptr(nnz_z_out), _ptr(workspace.buf), workspace.nbytes, _stream(stream))
+    _check(rc, "scap_swiglu_block")
     return y
 
 

@@ -89,6 +89,13 @@ int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t
     return launch_gemv(a, wdt, cfg, static_cast<hipStream_t>(stream));
 }
 
+constexpr int64_t kMaxGated = 262144;  // channels of the gated product: 4096 segments of 64
+
+size_t block_list_offset(int64_t F, int64_t N, int64_t B) {
+    const size_t c1 = partial_capacity(2 * F), c2 = partial_capacity(N);
+    return kOffPartial + 4 * (size_t)B * (c1 > c2 ? c1 : c2);
+}
+
 }  // namespace
 
 extern "C" {
@@ -165,6 +172,96 @@ int scap_dense_fc(const void* W, const void* col_scale, int64_t K, int64_t N, in
                   const scap_launch_cfg* cfg) {
     return fc_common(kModeDense, W, col_scale, K, N, wdt, x, xdt, B, 0.f, 0.f, bias, y, nullptr, nullptr, nullptr,
                      workspace, workspace_bytes, stream, cfg);
+}
+
+int scap_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F, int elem_bytes, void* out,
+                      void* stream) {
+    if (!gate || !up || !out) return SCAP_ERR_NULL;
+    if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4) return SCAP_ERR_DTYPE;
+    if (rows < 1 || F < 4 || F % 4 != 0 || F > ((int64_t)1 << 24) || rows > ((int64_t)1 << 24)) return SCAP_ERR_SHAPE;
+    if (!aligned16(gate) || !aligned16(up) || !aligned16(out)) return SCAP_ERR_ALIGN;
+    return launch_pack_gate_up(gate, up, rows, F, elem_bytes, out, static_cast<hipStream_t>(stream));
+}
+
+size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B) {
+    if (K < 1 || F < 1 || N < 1 || B < 1 || B > SCAP_MAX_TOKENS) return 0;
+    if (K > ((int64_t)1 << 24) || F > kMaxGated || N > ((int64_t)1 << 19)) return 0;
+    const size_t segs = (size_t)((F + 63) / 64);
+    size_t bytes = block_list_offset(F, N, B) + segs * 64 * 8 + align_up(segs * 4, 256);
+    const size_t a = scap_workspace_bytes(K, 2 * F, B), b = scap_workspace_bytes(F, N, B);
+    if (bytes < a) bytes = a;
+    if (bytes < b) bytes = b;
+    return bytes;
+}
+
+int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale, int64_t K,
+                      int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x, float tau_x,
+                      const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,
+                      float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    if (F < 1 || F > kMaxGated) return SCAP_ERR_SHAPE;
+    int rc = check_layer(W_gu, gu_scale, K, 2 * F, wdt);
+    if (rc != SCAP_OK) return rc;
+    rc = check_layer(W_down, down_scale, F, N, wdt);
+    if (rc != SCAP_OK) return rc;
+    if (F % 4 != 0) return SCAP_ERR_SHAPE;
+    if (!x || !y) return SCAP_ERR_NULL;
+    if (!act_dtype_ok(xdt)) return SCAP_ERR_DTYPE;
+    if (B < 1 || B > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
+    if (B != 1) return SCAP_ERR_UNIMPL;
+    if (!aligned16(x) || !aligned16(y) || (b_gu_fused && !aligned16(b_gu_fused)) ||
+        (b_down_fused && !aligned16(b_down_fused)) || (z_out && !aligned16(z_out)))
+        return SCAP_ERR_ALIGN;
+    if (idx_z_out && !nnz_z_out) return SCAP_ERR_NULL;
+    if (!(tau_x >= 0.f) || !isfinite(tau_x) || !isfinite(m_x)) return SCAP_ERR_VALUE;
+    if (!(tau_z >= 0.f) || !isfinite(tau_z) || !isfinite(m_z)) return SCAP_ERR_VALUE;
+    if (!workspace) return SCAP_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return SCAP_ERR_ALIGN;
+    const size_t need = scap_swiglu_workspace_bytes(K, F, N, B);
+    if (need == 0 || workspace_bytes < need) return SCAP_ERR_WORKSPACE;
+
+    char* base = static_cast<char*>(workspace);
+    const size_t segs = (size_t)((F + 63) / 64);
+    char* lists = base + block_list_offset(F, N, B);
+
+    GemvArgs up{};
+    up.W = W_gu;
+    up.col_scale = static_cast<const uint16_t*>(gu_scale);
+    up.x = static_cast<const uint16_t*>(x);
+    up.bias = b_gu_fused;
+    up.K = (int)K;
+    up.N = (int)(2 * F);
+    up.B = 1;
+    up.mode = kModeSparse;
+    up.xdt = xdt;
+    up.m = m_x;
+    up.tau = tau_x;
+    up.counters = reinterpret_cast<int32_t*>(base + kOffCounters);
+    up.seg_cnt = reinterpret_cast<int32_t*>(base + kOffSegCnt);
+    up.partial = reinterpret_cast<float*>(base + kOffPartial);
+    up.m2 = m_z;
+    up.tau2 = tau_z;
+    up.z_out = z_out;
+    up.zl_d = reinterpret_cast<float*>(lists);
+    up.zl_idx = reinterpret_cast<int32_t*>(lists + segs * 256);
+    up.zl_cnt = reinterpret_cast<int32_t*>(lists + segs * 512);
+    up.F = (int)F;
+
+    GemvArgs dn = up;
+    dn.W = W_down;
+    dn.col_scale = static_cast<const uint16_t*>(down_scale);
+    dn.x = nullptr;
+    dn.bias = b_down_fused;
+    dn.y = y;
+    dn.K = (int)F;
+    dn.N = (int)N;
+    dn.m = m_z;
+    dn.tau = tau_z;
+    dn.idx_out = idx_z_out;
+    dn.nnz_out = nnz_z_out;
+    dn.seg_cnt = up.zl_cnt;  // the counts the list-closing step reads
+    dn.z_out = nullptr;
+    return launch_swiglu_block(up, dn, wdt, static_cast<hipStream_t>(stream));
 }
 
 int scap_read_probe(const void* src, size_t bytes, uint32_t* out, void* stream) {

@@ -9,6 +9,12 @@ namespace scap {
 
 constexpr int kHdrBytes = 2048;  // LDS header: per-wave counts + flags
 
+// What surrounds the gathered GEMV of a launch:
+constexpr int kFusePlain = 0;   // inputs from x, outputs to y
+constexpr int kFuseSwiglu = 1;  // columns are gate|up interleaved in groups of 4; the tile's last arrival forms
+                                // z = silu(gate) * up, centres and thresholds it and leaves compacted lists
+constexpr int kFuseList = 2;    // inputs are those lists instead of x
+
 // Data handed from one workgroup to another inside a launch (split-K partials, per-split index lists,
 // arrival counters) bypasses the non-coherent cache levels: device-scope relaxed atomics for single
 // words, buffer loads/stores with the device-coherent cache policy for the 16-byte partial sums.
@@ -54,6 +60,7 @@ struct Lds {
     int* idx;    // [Kc] kept channel indices, ascending (LDS, or global for the batched path)
     float* d;    // centred values per token (0 where the token pruned the channel); see d_at()
     float* red;  // reduction buffer; reuses the list space once the rows have been streamed
+    float* fin;  // kFuseSwiglu: the tile's finished columns (after scale and bias), [TILE]
 };
 
 // Position of token b's value of list entry e in Lds::d: token-major [BT][Kc] (a wavefront reads
@@ -71,6 +78,7 @@ __device__ __forceinline__ Lds carve_lds(char* smem, int Kc) {
     L.idx = reinterpret_cast<int*>(smem + kHdrBytes);
     L.d = reinterpret_cast<float*>(L.idx + Kc);
     L.red = reinterpret_cast<float*>(smem + kHdrBytes);
+    L.fin = nullptr;
     return L;
 }
 
@@ -213,10 +221,94 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
     return cnt;
 }
 
+// ---------------------------------------------------------------------------------------------- list input
+// kFuseList prologue: the workgroup's Kc channels are Kc/64 segments of the previous launch's lists.  The
+// segment counts and every entry slot are loaded together (one memory latency); entry r of a segment goes
+// to position (entries of the earlier segments) + r.  Requires Kc/64 <= 64.  Ends with a barrier.
+template <int WAVES>
+__device__ __forceinline__ int gather_lists(const GemvArgs& a, int split, const Lds& L) {
+    constexpr int PER_WAVE = kWave / WAVES;  // segments a wavefront may have to move
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    const int spw = a.Kc >> 6;
+    const int seg0 = split * spw;
+    const int nseg = min(spw, a.Sl - seg0);
+    int cv = lane < nseg ? a.zl_cnt[seg0 + lane] : 0;
+    cv = min(max(cv, 0), kWave);  // a segment never holds more; keeps LDS writes in range whatever the memory holds
+    int vi[PER_WAVE];
+    float vd[PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int sl = w + j * WAVES;
+        vi[j] = 0;
+        vd[j] = 0.f;
+        if (sl < nseg) {
+            const int64_t p = (int64_t)(seg0 + sl) * kWave + lane;
+            vi[j] = a.zl_idx[p];
+            vd[j] = a.zl_d[p];
+        }
+    }
+    const int inc = wave_inclusive_scan(cv);
+    const int total = __shfl(inc, kWave - 1, kWave);
+    const int excl = inc - cv;
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int sl = w + j * WAVES;
+        if (sl < nseg) {
+            const int c = __shfl(cv, sl, kWave);
+            const int off = __shfl(excl, sl, kWave);
+            if (lane < c) {
+                L.idx[off + lane] = vi[j];
+                L.d[off + lane] = vd[j];
+            }
+        }
+    }
+    __syncthreads();
+    return uniform(total);
+}
+
+// kFuseSwiglu: the finished columns of a tile hold, per 8 columns, 4 gate then the 4 matching up
+// pre-activations.  Form z = silu(gate) * up (Alg. 2), centre and threshold it like any other layer input
+// (Alg. 3 steps 1-2, strict compare of Eq. 2) and leave each 64-channel segment's kept channels, compacted,
+// for the down launch.  Called by every thread of the tile's last arrival.
+template <int WAVES, int TILE>
+__device__ __forceinline__ void gate_and_compact(const GemvArgs& a, int tile, const float* s_fin) {
+    constexpr int HALF = TILE / 2;  // gated outputs per tile; a multiple of 64
+    constexpr int NT = WAVES * kWave;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int nsegs = (a.F + kWave - 1) / kWave;
+    for (int t0 = 0; t0 < HALF; t0 += NT) {
+        const int t = t0 + tid;
+        const int c = tile * HALF + t;
+        float dv = 0.f;
+        bool keep = false;
+        if (t < HALF && c < a.F) {
+            const int p = (t >> 2) * 8 + (t & 3);
+            const float g = s_fin[p], u = s_fin[p + 4];
+            const float z = g / (1.f + expf(-g)) * u;
+            if (a.z_out) a.z_out[c] = z;
+            dv = z - a.m2;
+            keep = fabsf(dv) > a.tau2;
+        }
+        const uint64_t bal = __ballot(keep);
+        const int seg = uniform((tile * HALF + t0 + (tid & ~63)) >> 6);
+        if (t0 + (tid & ~63) < HALF && seg < nsegs) {
+            if (keep) {
+                const int64_t p = (int64_t)seg * kWave + lanes_below(bal);
+                a.zl_idx[p] = c;
+                a.zl_d[p] = dv;
+            }
+            if (lane == 0) a.zl_cnt[seg] = __popcll(bal);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------- epilogue
 // scale (int8), add the fused bias, store 4 columns of y
-template <int WDT, int TILE>
-__device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int b, int g, float4 s) {
+template <int WDT, int TILE, int FUSE = kFusePlain>
+__device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int b, int g, float4 s, float* s_fin) {
     const int col = tile * TILE + 4 * g;
     if (col >= a.N) return;  // N is a multiple of 8: a group is inside or outside as a whole
     if (WDT == kI8) {
@@ -232,7 +324,10 @@ __device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int 
         s.z += bv.z;
         s.w += bv.w;
     }
-    *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
+    if constexpr (FUSE == kFuseSwiglu)
+        *reinterpret_cast<float4*>(s_fin + 4 * g) = s;
+    else
+        *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
 }
 
 // split-K partials of one call: [B][S][T][TILE] floats, addressed by byte offset
@@ -242,11 +337,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_buffer(const GemvArgs&
 }
 
 // the workgroup's sum of 4 columns for token b: final output if there is one split, else a partial
-template <int WDT, int TILE>
+template <int WDT, int TILE, int FUSE = kFusePlain>
 __device__ __forceinline__ void emit_group(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, int split, int b,
-                                           int g, float4 s) {
+                                           int g, float4 s, float* s_fin = nullptr) {
     if (a.S == 1)
-        finish_columns<WDT, TILE>(a, tile, b, g, s);
+        finish_columns<WDT, TILE, FUSE>(a, tile, b, g, s, s_fin);
     else
         store_coherent16(pbuf, (uint32_t)((((b * a.S + split) * a.T + tile) * TILE + 4 * g) * 4), s);
 }
@@ -254,7 +349,7 @@ __device__ __forceinline__ void emit_group(const GemvArgs& a, __amdgpu_buffer_rs
 // Arrival ticket; the last arrival of a tile adds the S partials (fixed association), writes y and clears
 // the counter; the last arrival of tile 0 also closes the gaps between the per-split index lists.
 // Every thread of the workgroup must call this after its last emit_group().
-template <int WDT, int WAVES, int TILE, int BT>
+template <int WDT, int WAVES, int TILE, int BT, int FUSE = kFusePlain>
 __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, const Lds& L) {
     constexpr int NT = WAVES * kWave;
     constexpr int GROUPS = TILE / 4;
@@ -315,11 +410,15 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
                     s.z += v.z;
                     s.w += v.w;
                 }
-                finish_columns<WDT, TILE>(a, tile, b, g, s);
+                finish_columns<WDT, TILE, FUSE>(a, tile, b, g, s, L.fin);
             }
             __syncthreads();
         }
         if (tid == 0) store_dev(&a.counters[tile * kCounterStride], 0);  // ready for the next call
+    }
+    if constexpr (FUSE == kFuseSwiglu) {
+        __syncthreads();  // the tile's columns are complete in L.fin
+        gate_and_compact<WAVES, TILE>(a, tile, L.fin);
     }
 
     if (!wants_lists) return;
@@ -327,8 +426,8 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
     // Every entry moves left or stays, so reading a block of source positions, synchronising, then
     // writing it, block after block from the left, never overwrites an entry that is still to be read.
     __syncthreads();
-    int* s_off = L.idx;               // [Sl] exclusive offsets
-    int* s_cnt = L.idx + kMaxSplits;  // [Sl] counts
+    int* s_off = L.idx;          // [Sl] exclusive offsets
+    int* s_cnt = L.idx + a.Sl;   // [Sl] counts
     const int nlist = a.B + 1;
     for (int l = 0; l < nlist; ++l) {
         const bool is_union = l == a.B;
@@ -340,7 +439,8 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
             int run = 0;
             for (int s0 = 0; s0 < a.Sl; s0 += kWave) {
                 const int sp = s0 + lane;
-                const int v = sp < a.Sl ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.Sl + sp]) : 0;
+                const int row = (FUSE == kFuseList) ? 0 : (is_union ? a.B : src_l);
+                const int v = sp < a.Sl ? load_dev(&a.seg_cnt[row * a.Sl + sp]) : 0;
                 const int inc = wave_inclusive_scan(v);
                 if (sp < a.Sl) {
                     s_off[sp] = run + inc - v;
@@ -356,8 +456,12 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
             }
         }
         __syncthreads();
-        if (!is_union && a.idx_out != nullptr && a.Sl > 1) {
+        // list input: the source is the previous launch's segment lists, other workgroups may still be
+        // reading them, so the closed-up copy goes to idx_out and the source stays as it is
+        const bool in_place = FUSE != kFuseList;
+        if (!is_union && a.idx_out != nullptr && (a.Sl > 1 || !in_place)) {
             int32_t* base = a.idx_out + (int64_t)l * a.K;
+            const int32_t* src = in_place ? base : a.zl_idx;
             constexpr int PER = 16;
             for (int c0 = 0; c0 < a.K; c0 += NT * PER) {
                 int vals[PER], dsts[PER];
@@ -370,7 +474,7 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
                         const int seg = p / a.Kl;
                         const int r = p - seg * a.Kl;
                         if (r < s_cnt[seg]) {
-                            vals[j] = load_dev(&base[p]);
+                            vals[j] = load_dev(&src[p]);
                             dsts[j] = s_off[seg] + r;
                         }
                     }

@@ -73,10 +73,26 @@ struct GemvArgs {
     int K, N, B, Kc, S, T, mode, xdt;
     int Kl, Sl;  // segmentation of the kept-channel lists: Sl segments of Kl channels (= S, Kc unless batched)
     float m, tau;
+    // Fused SwiGLU block (Alg. 2).  The gate|up launch leaves the gated product z, centred and thresholded,
+    // as one compacted list per 64 channels; the down launch takes those lists as its input.
+    float m2, tau2;   // mode estimate and threshold of the gated product
+    float* z_out;     // optional fp32 [F]: the gated product itself
+    int32_t* zl_idx;  // [ceil(F/64)][64] kept channels of each 64-channel segment, ascending from the segment start
+    float* zl_d;      // [ceil(F/64)][64] their centred values
+    int32_t* zl_cnt;  // [ceil(F/64)] entries per segment
+    int F;            // channels of the gated product (half the columns of the gate|up launch)
 };
 
 // Enqueue one GEMV (sparse / dense / fold mode).  Returns a scap_status.
 int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+
+// Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
+// `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.
+int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
+
+// Interleave two [rows, F] arrays of `elem_bytes`-byte elements in groups of 4 columns: out[rows, 2F].
+int launch_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F, int elem_bytes, void* out,
+                        hipStream_t stream);
 
 // Batched tokens over bf16 weights on the matrix cores: possible from kMfmaMinTokens tokens on (the
 // workspace then carries the union lists), chosen by default from kMfmaAutoTokens on -- at 4 tokens the

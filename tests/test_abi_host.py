@@ -100,6 +100,49 @@ def test_other_entry_points_validate(lib):
     assert lib.scap_read_probe(FAKE, 1000, FAKE, None) == -2
 
 
+def _blk(lib, **kw):
+    a = dict(Wgu=FAKE, sgu=None, Wd=FAKE, sd=None, K=4096, F=14336, N=4096, wdt=1, x=FAKE, xdt=1, B=1, mx=0.0, tx=0.5,
+             bgu=None, mz=0.0, tz=0.1, bd=None, y=FAKE, z=None, idx=None, nnz=None, ws=FAKE, wsb=1 << 30, stream=None)
+    a.update(kw)
+    return lib.scap_swiglu_block(a["Wgu"], a["sgu"], a["Wd"], a["sd"], a["K"], a["F"], a["N"], a["wdt"], a["x"], a["xdt"],
+                                 a["B"], a["mx"], a["tx"], a["bgu"], a["mz"], a["tz"], a["bd"], a["y"], a["z"], a["idx"],
+                                 a["nnz"], a["ws"], a["wsb"], a["stream"])
+
+
+def test_swiglu_block_entry_points_validate(lib):
+    assert scap.swiglu_workspace_bytes(4096, 14336, 4096, 1) >= max(scap.workspace_bytes(4096, 28672, 1),
+                                                                    scap.workspace_bytes(14336, 4096, 1))
+    assert scap.swiglu_workspace_bytes(4096, 0, 4096, 1) == 0
+    assert scap.swiglu_workspace_bytes(4096, 1 << 19, 4096, 1) == 0
+    assert _blk(lib, Wgu=None) == -1
+    assert _blk(lib, Wd=None) == -1
+    assert _blk(lib, x=None) == -1
+    assert _blk(lib, y=None) == -1
+    assert _blk(lib, idx=FAKE) == -1                 # list without a count
+    assert _blk(lib, F=14338) == -2                  # not a multiple of 4
+    assert _blk(lib, F=0) == -2
+    assert _blk(lib, N=4100) == -2
+    assert _blk(lib, wdt=2) == -1                    # int8 without scales
+    assert _blk(lib, wdt=2, sgu=FAKE, sd=FAKE, F=14340) == -2   # int8: 2F must be a multiple of 16
+    assert _blk(lib, wdt=7) == -3
+    assert _blk(lib, xdt=2) == -3
+    assert _blk(lib, B=0) == -2
+    assert _blk(lib, B=17) == -2
+    assert _blk(lib, B=2) == -8
+    assert _blk(lib, x=ODD) == -4
+    assert _blk(lib, z=ODD) == -4
+    assert _blk(lib, tx=-0.5) == -5
+    assert _blk(lib, tz=float("inf")) == -5
+    assert _blk(lib, mz=float("nan")) == -5
+    assert _blk(lib, ws=None) == -6
+    assert _blk(lib, wsb=1 << 20) == -6
+    assert lib.scap_pack_gate_up(None, FAKE, 4, 8, 2, FAKE, None) == -1
+    assert lib.scap_pack_gate_up(FAKE, FAKE, 4, 8, 3, FAKE, None) == -3
+    assert lib.scap_pack_gate_up(FAKE, FAKE, 4, 6, 2, FAKE, None) == -2
+    assert lib.scap_pack_gate_up(FAKE, FAKE, 0, 8, 2, FAKE, None) == -2
+    assert lib.scap_pack_gate_up(FAKE, ODD, 4, 8, 2, FAKE, None) == -4
+
+
 def test_product_package_does_not_touch_the_oracle():
     """The product path must not import, link or call the CPU oracle."""
     pkg = os.path.join(ROOT, "paper_2412_07174_amd")

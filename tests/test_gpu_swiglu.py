@@ -1,0 +1,258 @@
+"""GPU parity of the fused SwiGLU block (Appendix B Alg. 2): scap_pack_gate_up and scap_swiglu_block through the
+C ABI against the CPU oracle on the same seeded inputs.
+
+The second pruner decides on a floating-point value (the gated product z) that the two sides sum in different
+orders, so a channel whose |z - m_z| lies within a rounding-sized band of tau_z may legitimately fall either way.
+The tests require: every channel outside the band decided exactly as the oracle decides it; the kept list
+ascending, duplicate-free and consistent with its count; z within rounding of the oracle's; and y within the
+usual bar of the oracle's y for the decisions actually taken (the oracle's y plus/minus the band channels'
+rows, evaluated here in fp64 from the oracle's own z)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_07174_amd as scap
+import workloads as wl
+from workloads import BF16, F16, I8
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from gpu_util import assert_y_close, f32_dev, to_dev
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def pack_host(g, u):
+    """The interleaving in groups of 4 columns, written with array reshapes."""
+    g2, u2 = np.atleast_2d(g), np.atleast_2d(u)
+    r, F = g2.shape
+    out = np.stack([g2.reshape(r, F // 4, 4), u2.reshape(r, F // 4, 4)], axis=2).reshape(r, 2 * F)
+    return out if np.ndim(g) == 2 else out[0]
+
+
+def weights_of(dt, K, N, seed, std):
+    if dt == I8:
+        return wl.quantize_i8(K, N, seed, std=std)
+    return wl.weights(K, N, seed, dt, std=std), None
+
+
+class Block:
+    def __init__(self, K, F, N, dt, seed, std=0.05):
+        self.K, self.F, self.N, self.dt = K, F, N, dt
+        (self.Wg, self.sg), (self.Wu, self.su) = weights_of(dt, K, F, seed, std), weights_of(dt, K, F, seed + 1, std)
+        self.Wd, self.sd = weights_of(dt, F, N, seed + 2, std)
+        self.W_gu = scap.pack_gate_up(to_dev(self.Wg, dt), to_dev(self.Wu, dt))
+        self.gu_scale = None if dt != I8 else scap.pack_gate_up(to_dev(self.sg, F16), to_dev(self.su, F16))
+        self.W_down = to_dev(self.Wd, dt)
+        self.down_scale = None if dt != I8 else to_dev(self.sd, F16)
+        self.ws = scap.Workspace(K, N, 1, F=F)
+        torch.cuda.synchronize()
+        assert np.array_equal(self.W_gu.cpu().view(torch.int8 if dt == I8 else torch.int16).numpy()
+                              .view(np.int8 if dt == I8 else np.uint16), pack_host(self.Wg, self.Wu))
+
+    def down_rows(self, rows):
+        w = self.Wd[rows].astype(np.float64) if self.dt == I8 else wl.decode(self.Wd[rows], self.dt).astype(np.float64)
+        if self.dt == I8:
+            w = w * wl.decode(self.sd, F16).astype(np.float64)[None, :]
+        return w
+
+    def run(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, want_lists=True, want_z=True):
+        b_gu = None if bg is None else scap.pack_gate_up(f32_dev(bg), f32_dev(bu))
+        z = torch.full((self.F,), float("nan"), dtype=torch.float32, device="cuda") if want_z else None
+        idx = torch.full((self.F,), -7, dtype=torch.int32, device="cuda") if want_lists else None
+        nnz = torch.full((1,), -7, dtype=torch.int32, device="cuda") if want_lists else None
+        y = torch.full((1, self.N), float("nan"), dtype=torch.float32, device="cuda")
+        scap.swiglu_block(self.W_gu, self.W_down, to_dev(x_bits, xdt), m_x, tau_x, b_gu, m_z, tau_z, f32_dev(bd),
+                          gu_scale=self.gu_scale, down_scale=self.down_scale, y=y, z_out=z, idx_z_out=idx,
+                          nnz_z_out=nnz, workspace=self.ws)
+        torch.cuda.synchronize()
+        out = {"y": y.cpu().numpy()[0]}
+        if want_z:
+            out["z"] = z.cpu().numpy()
+        if want_lists:
+            n = int(nnz.item())
+            assert 0 <= n <= self.F
+            out["idx_z"] = idx.cpu().numpy()[:n].copy()
+        return out
+
+    def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what):
+        want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, x_bits, m_x, tau_x, m_z, tau_z, self.dt, xdt,
+                                   b_gate=bg, b_up=bu, b_down=bd, gate_scale=self.sg, up_scale=self.su,
+                                   down_scale=self.sd, nthreads=8)
+        got = self.run(x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd)
+        zo = want["z"].astype(np.float64)
+        fin = np.isfinite(zo)
+        tol = 2e-5 + 2e-5 * np.abs(zo[fin])
+        assert np.all(np.abs(got["z"][fin] - zo[fin]) <= tol), f"{what}: z off by {np.abs(got['z'][fin] - zo[fin]).max()}"
+        # decisions: exact outside the band
+        d = (want["z"] - np.float32(m_z)).astype(np.float32)
+        margin = np.abs(np.abs(d.astype(np.float64)) - float(np.float32(tau_z)))
+        band = margin <= 1e-4 * np.maximum(1.0, np.abs(zo))
+        gi = got["idx_z"]
+        assert np.all(np.diff(gi) > 0), f"{what}: kept list not strictly ascending"
+        assert gi.size == 0 or (gi[0] >= 0 and gi[-1] < self.F)
+        g_mask = np.zeros(self.F, dtype=bool)
+        g_mask[gi] = True
+        o_mask = np.zeros(self.F, dtype=bool)
+        o_mask[want["idx_z"]] = True
+        diff = g_mask != o_mask
+        assert not np.any(diff & ~band), f"{what}: {np.count_nonzero(diff & ~band)} decisions differ outside the band"
+        # y for the decisions taken
+        y_want = want["y"].astype(np.float64)
+        extra, missing = np.nonzero(diff & g_mask)[0], np.nonzero(diff & o_mask)[0]
+        if extra.size:
+            y_want = y_want + d[extra].astype(np.float64) @ self.down_rows(extra)
+        if missing.size:
+            y_want = y_want - d[missing].astype(np.float64) @ self.down_rows(missing)
+        assert_y_close(got["y"], y_want, what)
+        return got, want, int(np.count_nonzero(diff))
+
+
+# ------------------------------------------------------------------ packing
+@pytest.mark.parametrize("rows,F,dtype", [(1, 8, np.float32), (1, 4096, np.uint16), (3, 12, np.int8), (257, 1500, np.uint16),
+                                          (64, 520, np.int8), (5, 36, np.float32)])
+def test_pack_gate_up_layout(rows, F, dtype):
+    rng = np.random.default_rng(rows * 1000 + F)
+    if dtype == np.float32:
+        g, u = rng.standard_normal((rows, F)).astype(dtype), rng.standard_normal((rows, F)).astype(dtype)
+    else:
+        info = np.iinfo(dtype)
+        g = rng.integers(info.min, info.max, size=(rows, F), endpoint=True).astype(dtype)
+        u = rng.integers(info.min, info.max, size=(rows, F), endpoint=True).astype(dtype)
+    tdt = {np.float32: torch.float32, np.uint16: torch.int16, np.int8: torch.int8}[dtype]
+    gd = torch.from_numpy(g.view(np.int16) if dtype == np.uint16 else g).cuda()
+    ud = torch.from_numpy(u.view(np.int16) if dtype == np.uint16 else u).cuda()
+    assert gd.dtype == tdt
+    out = scap.pack_gate_up(gd, ud).cpu().numpy()
+    want = pack_host(g, u)
+    assert np.array_equal(out.view(dtype), want)
+    # column p of the packed array: group p // 8, gate for p % 8 < 4
+    for p in (0, 3, 4, 7, 8, 2 * F - 1):
+        src = g if p % 8 < 4 else u
+        assert np.array_equal(want[:, p], src[:, (p // 8) * 4 + p % 4])
+
+
+# ------------------------------------------------------------------ small blocks: tiles, splits, ragged tails
+SMALL = [
+    # K, F, N
+    (8, 8, 8), (64, 64, 16), (200, 328, 136), (130, 1032, 520), (1000, 1500, 264), (512, 4100, 1032), (3000, 776, 4104),
+]
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("K,F,N", SMALL)
+def test_small_blocks(dt, K, F, N):
+    blk = Block(K, F, N, dt, seed=500 + K)
+    X = wl.laplace(3, K, 600 + K, dt, loc=0.1, scale=0.8)
+    rng = np.random.default_rng(K + F)
+    bg, bu, bd = (rng.standard_normal(n).astype(np.float32) * 0.05 for n in (F, F, N))
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.1, 0.5, 0.0, 0.0, dt, dt, b_gate=bg, b_up=bu)["z"])
+    flips = 0
+    for tau_x, tau_z in ((0.0, 0.0), (0.5, float(np.median(zs))), (1.1, float(np.quantile(zs, 0.8))), (0.5, 1e9)):
+        for b in range(X.shape[0]):
+            say(f"block K={K} F={F} N={N} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g} vec={b}")
+            flips += blk.check(X[b], dt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"K={K} F={F} N={N} tau_z={tau_z}")[2]
+    assert flips <= 6   # band decisions are rare
+
+
+@pytest.mark.parametrize("K,F,N", [(64, 64, 16), (520, 1032, 2064), (1000, 2056, 528)])
+def test_small_blocks_int8(K, F, N):
+    blk = Block(K, F, N, I8, seed=700 + K)
+    X = wl.laplace(2, K, 800 + K, BF16, loc=0.0, scale=0.8)
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.0, 0.4, 0.0, 0.0, I8, BF16, gate_scale=blk.sg,
+                                    up_scale=blk.su, down_scale=blk.sd)["z"])
+    for tau_x, tau_z in ((0.0, 0.0), (0.4, float(np.quantile(zs, 0.7)))):
+        for b in range(X.shape[0]):
+            say(f"block int8 K={K} F={F} N={N} tau_x={tau_x} tau_z={tau_z:.4g} vec={b}")
+            blk.check(X[b], BF16, 0.0, tau_x, None, None, 0.0, tau_z, None, f"int8 K={K} F={F} N={N}")
+
+
+# ------------------------------------------------------------------ degenerate cases
+def test_nothing_kept_and_everything_kept():
+    K, F, N = 300, 520, 264
+    blk = Block(K, F, N, BF16, seed=900)
+    x = wl.laplace(1, K, 901, BF16, loc=0.0, scale=1.0)[0]
+    bd = np.random.default_rng(902).standard_normal(N).astype(np.float32)
+    # second pruner drops everything: y is the fused bias exactly, the list is empty
+    got = blk.run(x, BF16, 0.0, 0.3, None, None, 0.0, 1e30, bd)
+    assert got["idx_z"].size == 0 and np.array_equal(got["y"], bd)
+    # first pruner drops everything: gate = up = fused bias = 0, z = 0, nothing passes a strict compare with 0
+    got = blk.run(x, BF16, 0.0, 1e30, None, None, 0.0, 0.0, bd)
+    assert got["idx_z"].size == 0 and np.array_equal(got["y"], bd) and not got["z"].any()
+    # a centred second pruner with an all-zero z keeps every channel at d = -m_z
+    got, want, _ = blk.check(x, BF16, 0.0, 1e30, None, None, 0.25, 0.1, bd, "all-zero z, centred")
+    assert got["idx_z"].size == F
+    # outputs not asked for
+    got = blk.run(x, BF16, 0.0, 0.3, None, None, 0.0, 0.01, bd, want_lists=False, want_z=False)
+    ref = blk.run(x, BF16, 0.0, 0.3, None, None, 0.0, 0.01, bd)
+    assert np.array_equal(got["y"], ref["y"])
+
+
+def test_block_is_bit_reproducible_and_workspace_is_reusable():
+    K, F, N = 1000, 2056, 1032
+    blk = Block(K, F, N, BF16, seed=910)
+    X = wl.laplace(2, K, 911, BF16, loc=0.0, scale=1.0)
+    a0 = blk.run(X[0], BF16, 0.0, 0.4, None, None, 0.0, 0.02, None)
+    b0 = blk.run(X[1], BF16, 0.0, 0.9, None, None, 0.0, 0.05, None)
+    a1 = blk.run(X[0], BF16, 0.0, 0.4, None, None, 0.0, 0.02, None)
+    b1 = blk.run(X[1], BF16, 0.0, 0.9, None, None, 0.0, 0.05, None)
+    for p, q in ((a0, a1), (b0, b1)):
+        assert np.array_equal(p["y"], q["y"]) and np.array_equal(p["z"], q["z"]) and np.array_equal(p["idx_z"], q["idx_z"])
+    # the workspace of a block also serves plain calls on its layers
+    y = scap.dense_fc(blk.W_down, to_dev(wl.laplace(1, F, 912, BF16)[0], BF16), None, workspace=blk.ws)
+    torch.cuda.synchronize()
+    assert np.isfinite(y.cpu().numpy()).all()
+
+
+def test_block_argument_errors():
+    K, F, N = 64, 64, 16
+    blk = Block(K, F, N, BF16, seed=920)
+    x = to_dev(wl.laplace(2, K, 921, BF16), BF16)
+    y = torch.empty((2, N), dtype=torch.float32, device="cuda")
+    with pytest.raises(scap.ScapError) as e:
+        scap.swiglu_block(blk.W_gu, blk.W_down, x, 0.0, 0.1, None, 0.0, 0.1, None, y=y, workspace=blk.ws)
+    assert e.value.status == -8      # two tokens: not implemented
+    with pytest.raises(scap.ScapError) as e:
+        scap.swiglu_block(blk.W_gu, blk.W_down, x[0], 0.0, -1.0, None, 0.0, 0.1, None, workspace=blk.ws)
+    assert e.value.status == -5
+    with pytest.raises(scap.ScapError) as e:
+        scap.swiglu_block(blk.W_gu, blk.W_down, x[0], 0.0, 0.1, None, 0.0, float("nan"), None, workspace=blk.ws)
+    assert e.value.status == -5
+    small = scap.Workspace(K, N, 1)
+    small.nbytes = 4096
+    with pytest.raises(scap.ScapError) as e:
+        scap.swiglu_block(blk.W_gu, blk.W_down, x[0], 0.0, 0.1, None, 0.0, 0.1, None, workspace=small)
+    assert e.value.status == -6
+    idx = torch.empty(F, dtype=torch.int32, device="cuda")
+    with pytest.raises(scap.ScapError) as e:
+        scap.swiglu_block(blk.W_gu, blk.W_down, x[0], 0.0, 0.1, None, 0.0, 0.1, None, idx_z_out=idx, workspace=blk.ws)
+    assert e.value.status == -1
+
+
+# ------------------------------------------------------------------ full size: the Mistral-7B feed-forward block
+@pytest.mark.parametrize("s_x,s_z", [(0.5, 0.5), (0.3, 0.7)])
+def test_mistral_ffn_block_full_size(s_x, s_z):
+    K, F, N = 4096, 14336, 4096
+    site = wl.sites(3)[2]     # gate|up input of the Mistral layer
+    assert site.K == K
+    blk = Block(K, F, N, BF16, seed=3003, std=0.02)
+    m_x, tau_x = oracle.calibrate(site.calib(), site.xdt, s_x, oracle.MODE_MEDIAN)
+    X = site.test_vectors(3)
+    # threshold of the gated product from the oracle's own z on calibration vectors
+    zc = np.concatenate([oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, v, m_x, tau_x, 0.0, 0.0, BF16, BF16, nthreads=8)["z"]
+                         for v in site.draw(2, 77)])
+    tau_z = float(np.sort(np.abs(zc))[int(np.ceil(s_z * zc.size)) - 1])
+    bgf, buf = oracle.fold_bias(blk.Wg, m_x, None, BF16), oracle.fold_bias(blk.Wu, m_x, None, BF16)
+    for b in range(X.shape[0]):
+        say(f"mistral ffn block s_x={s_x} s_z={s_z} vec={b}")
+        got, want, flips = blk.check(X[b], BF16, m_x, tau_x, bgf, buf, 0.0, tau_z, None, f"mistral block vec {b}")
+        dens = got["idx_z"].size / F
+        assert abs(dens - (1 - s_z)) < 0.05
+        assert flips <= 3
