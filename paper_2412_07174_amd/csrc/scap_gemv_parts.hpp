@@ -127,6 +127,61 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
         }
     };
 
+    // One token and few chunks per wavefront (the usual launch shapes): the centred values and keep
+    // ballots of the counting pass stay in registers, so the inputs are loaded once.
+    constexpr int kRegChunks = 4;
+    if (BT == 1 && cpw <= kRegChunks) {
+        float dreg[kRegChunks];
+        uint64_t breg[kRegChunks];
+        int ucount = 0;
+#pragma unroll
+        for (int j = 0; j < kRegChunks; ++j) {
+            const int c = c_begin + j;
+            dreg[j] = 0.f;
+            breg[j] = 0;
+            if (c < c_end) {
+                const int k = k0 + c * kWave + lane;
+                float d[BT];
+                bool keep[BT];
+                eval_all(k, k < kend, d, keep);
+                dreg[j] = d[0];
+                breg[j] = __ballot(keep[0]);
+                ucount += __popcll(breg[j]);
+            }
+        }
+        if (lane == 0) L.hdr[w] = ucount;
+        __syncthreads();
+        int ubase = 0, cnt = 0;
+#pragma unroll
+        for (int i = 0; i < WAVES; ++i) {
+            const int v = L.hdr[i];
+            if (i < w) ubase += v;
+            cnt += v;
+        }
+        cnt = uniform(cnt);
+        ubase = uniform(ubase);
+#pragma unroll
+        for (int j = 0; j < kRegChunks; ++j) {
+            const int c = c_begin + j;
+            if (c < c_end) {
+                if ((breg[j] >> lane) & 1) {
+                    const int k = k0 + c * kWave + lane;
+                    const int pos = ubase + lanes_below(breg[j]);
+                    L.idx[pos] = k;
+                    L.d[d_at<DSTRIDE>(0, pos, a.Kc)] = dreg[j];
+                    if (want_idx) store_dev(&a.idx_out[k0 + pos], k);
+                }
+                ubase += __popcll(breg[j]);
+            }
+        }
+        if (tile == 0 && tid == 0) {
+            store_dev(&a.seg_cnt[a.B * a.Sl + split], cnt);  // union
+            store_dev(&a.seg_cnt[split], cnt);
+        }
+        __syncthreads();
+        return cnt;
+    }
+
     {
         int ucount = 0;
         int tcount[BT];
