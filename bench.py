@@ -99,6 +99,11 @@ def run_suite(args, torch, scap, wl, dev):
             rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
                          "target": None, "density": 1.0, "us": round(t_dense, 2),
                          "GBps": round(algorithmic_bytes(K, K, N, B, wbytes) / t_dense / 1e3, 1)})
+            if site.wdt != wl.I8 and cfg_no == 4:
+                # the vendor library's dense GEMM on the same operands, for the crossover against a dense batch
+                yl = torch.empty((B, N), dtype=W0.dtype, device=dev)
+                t_lib = timed(lambda i: torch.matmul(xs(i).reshape(B, K), Ws[i % R], out=yl))
+                rows[-1]["library_dense_gemm_us"] = round(t_lib, 2)
             for s in targets:
                 m, tau = taus[s]
                 dens = 0.0

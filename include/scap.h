@@ -67,17 +67,17 @@ typedef enum {
 } scap_mode_est;
 
 /* Optional launch shape of the GEMV kernels (for tuning sweeps).  Zero fields mean "choose".
- * With 5 or more tokens over bf16 weights the matrix-core kernel runs unless lanes_per_row says otherwise
- * (64 / 32: vector kernel; 16: matrix-core kernel, allowed from 2 tokens on); there waves_per_group is 8 or
- * 16, unroll (1, 2, 4) counts 16-row blocks in flight per wavefront, and rows_per_group is rounded up to
- * whole 512-channel list segments. */
+ * With 5 or more tokens over bf16 or int8 weights the matrix-core kernel runs unless lanes_per_row says
+ * otherwise (64 / 32: vector kernel; 16: matrix-core kernel, allowed from 2 tokens on); there waves_per_group
+ * is 8 or 16 (int8: 8), unroll (1, 2, 4; int8: 1, 2) counts 16-row blocks in flight per wavefront, and
+ * rows_per_group is rounded up to whole 512-channel list segments. */
 typedef struct {
     int32_t waves_per_group; /* 4, 8 or 16 wavefronts per workgroup */
     int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */
     int32_t unroll;          /* weight rows in flight per wavefront: 4, 8 or 16 */
     int32_t lanes_per_row;   /* lanes sharing one weight row per load: 64 or 32 (column tile =
                                 lanes_per_row x 8 columns, x 16 for int8; batch > 1: 64 only), or 16 =
-                                the matrix-core kernel (2..16 tokens, bf16 weights) */
+                                the matrix-core kernel (2..16 tokens, bf16 or int8 weights) */
 } scap_launch_cfg;
 
 /* Static, NUL-terminated description of a status code.  Never freed. */

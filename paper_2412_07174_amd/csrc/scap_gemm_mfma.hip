@@ -1,4 +1,4 @@
-// Batched sparse FC on the matrix cores (gfx950 MFMA), bf16 weights, 4..16 tokens.
+// Batched sparse FC on the matrix cores (gfx950 MFMA), bf16 or int8 weights, 2..16 tokens.
 //
 // With several tokens each token keeps its own mask (SCAP Eq. 2 is elementwise); the rows that have to be
 // read are the union of the masks (Appendix C), and what multiplies them is a [tokens x kept-rows] matrix of
@@ -25,6 +25,10 @@
 // is read from the list; it is split into a bf16 head and a bf16
 // tail (d = hi + lo) and fed through two MFMAs, so the bf16 rounding of d costs about 2^-17 relative
 // instead of 2^-9.
+//
+// int8 weights (one fp16 scale per column) go through the same instruction: every int8 value is exactly a
+// bf16 number, so the 16 bytes a lane loads are widened in registers to the bf16 B operands of 16 MFMAs
+// (tile = 256 columns) and the column scale is applied to the finished sums, as in the vector kernel.
 #include "scap_gemv_parts.hpp"
 
 namespace scap {
@@ -32,7 +36,7 @@ namespace scap {
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kMfmaTile = 128;    // columns per workgroup
+constexpr int kMfmaTile = 128;    // columns per workgroup with bf16 weights (16 lanes x 8); int8: 256
 constexpr int kMfmaTokens = 16;   // M of the MFMA; tokens beyond B are zero rows
 constexpr int kMfmaBlock = 16;    // list rows per MFMA (K of the MFMA)
 constexpr int kCompactWaves = 8;
@@ -153,10 +157,11 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
 }
 
 // ---------------------------------------------------------------------------------------------- launch 2
-template <int WAVES, int UB>
+template <int WDT, int WAVES, int UB>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs a) {
     constexpr int BT = kMfmaTokens;
-    constexpr int TILE = kMfmaTile;
+    constexpr int ELEMS = Vec<WDT>::kElems;  // columns in a lane's 16-byte load = MFMAs per block
+    constexpr int TILE = 16 * ELEMS;
     constexpr int NT = WAVES * kWave;
     constexpr int GROUPS = TILE / 4;
 
@@ -193,16 +198,16 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
 
     const int tok = lane & 15;  // token whose centred values this lane supplies (A index m)
 
-    const int cg = lane & 15;   // column group: columns 8*cg .. 8*cg+7 of the tile (B/C index n)
+    const int cg = lane & 15;   // column group: columns ELEMS*cg .. +ELEMS-1 of the tile (B/C index n)
     const int kg = lane >> 4;   // row group: list rows 4*kg .. 4*kg+3 of a block (k of A and B); token group of C
-    const int col0 = tile * TILE + cg * 8;
-    const uint32_t lane_off = (col0 < a.N) ? (uint32_t)col0 * 2u : 0u;
-    const uint32_t row_bytes = (uint32_t)a.N * 2u;
+    const int col0 = tile * TILE + cg * ELEMS;
+    const uint32_t lane_off = (col0 < a.N) ? (uint32_t)col0 * Vec<WDT>::kBytes : 0u;
+    const uint32_t row_bytes = (uint32_t)a.N * Vec<WDT>::kBytes;
     const char* wbase = reinterpret_cast<const char*>(a.W);
 
-    f32x4_t acc[8];
+    f32x4_t acc[ELEMS];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < ELEMS; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // Block blk (wave-uniform) -> its four list entries for this lane's row group: the int4 of channel
     // indices and how many of them are valid (0..4).  Blocks past the end give 0 valid entries.
@@ -264,15 +269,26 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
             const uint32_t q2[4] = {st.r[u][2].x, st.r[u][2].y, st.r[u][2].z, st.r[u][2].w};
             const uint32_t q3[4] = {st.r[u][3].x, st.r[u][3].y, st.r[u][3].z, st.r[u][3].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = e >> 1;
+            for (int e = 0; e < ELEMS; ++e) {
                 uint32_t lo01, lo23;  // rows (0,1) and (2,3) of column element e, packed as two bf16
-                if ((e & 1) == 0) {
-                    lo01 = (q0[q] & 0xFFFFu) | (q1[q] << 16);
-                    lo23 = (q2[q] & 0xFFFFu) | (q3[q] << 16);
+                if constexpr (WDT == kBF16) {
+                    const int q = e >> 1;
+                    if ((e & 1) == 0) {
+                        lo01 = (q0[q] & 0xFFFFu) | (q1[q] << 16);
+                        lo23 = (q2[q] & 0xFFFFu) | (q3[q] << 16);
+                    } else {
+                        lo01 = (q0[q] >> 16) | (q1[q] & 0xFFFF0000u);
+                        lo23 = (q2[q] >> 16) | (q3[q] & 0xFFFF0000u);
+                    }
                 } else {
-                    lo01 = (q0[q] >> 16) | (q1[q] & 0xFFFF0000u);
-                    lo23 = (q2[q] >> 16) | (q3[q] & 0xFFFF0000u);
+                    // byte e of each row, sign-extended, as a float: its low 16 bits are zero (|v| <= 128)
+                    const int q = e >> 2, sh = 24 - 8 * (e & 3);
+                    const uint32_t f0 = __float_as_uint((float)(((int)(q0[q] << sh)) >> 24));
+                    const uint32_t f1 = __float_as_uint((float)(((int)(q1[q] << sh)) >> 24));
+                    const uint32_t f2 = __float_as_uint((float)(((int)(q2[q] << sh)) >> 24));
+                    const uint32_t f3 = __float_as_uint((float)(((int)(q3[q] << sh)) >> 24));
+                    lo01 = (f0 >> 16) | f1;
+                    lo23 = (f2 >> 16) | f3;
                 }
                 union { uint32_t u32[2]; s16x4_t v; } bop;
                 bop.u32[0] = lo01;
@@ -301,13 +317,14 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     }
 
     // ------------------------------------------------------------------ add the wavefronts' sums
-    // acc[e][i] = token 4*kg + i, column col0 + e.  One pass per i: 4 tokens x 128 columns per wavefront.
+    // acc[e][i] = token 4*kg + i, column col0 + e.  One pass per i: 4 tokens x TILE columns per wavefront.
     const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        float4* dst = reinterpret_cast<float4*>(s_red + (w * 4 + kg) * TILE + cg * 8);
-        dst[0] = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
-        dst[1] = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
+        float4* dst = reinterpret_cast<float4*>(s_red + (w * 4 + kg) * TILE + cg * ELEMS);
+#pragma unroll
+        for (int v = 0; v < ELEMS / 4; ++v)
+            dst[v] = make_float4(acc[4 * v][i], acc[4 * v + 1][i], acc[4 * v + 2][i], acc[4 * v + 3][i]);
         __syncthreads();
         for (int t = tid; t < 4 * GROUPS; t += NT) {
             const int mg = t / GROUPS, g = t % GROUPS;
@@ -321,16 +338,18 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
                 s.w += v.w;
             }
             const int b = 4 * mg + i;
-            if (b < a.B) emit_group<kBF16, TILE>(a, pbuf, tile, split, b, g, s);
+            if (b < a.B) emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, s);
         }
         __syncthreads();
     }
 
-    finish_tile<kBF16, WAVES, TILE, BT>(a, pbuf, tile, L);
+    finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L);
 }
 
-int launch_gemm_mfma(const GemvArgs& a_in, const scap_launch_cfg* cfg, hipStream_t stream) {
+int launch_gemm_mfma(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipStream_t stream) {
     GemvArgs a = a_in;
+    if (wdt != kBF16 && wdt != kI8) return SCAP_ERR_CONFIG;
+    const int tile_cols = wdt == kI8 ? 2 * kMfmaTile : kMfmaTile;
     if (!a.u_idx || !a.u_d) return SCAP_ERR_WORKSPACE;
     int kc = 0, waves = 8, ub = 2;
     if (cfg) {
@@ -346,27 +365,46 @@ int launch_gemm_mfma(const GemvArgs& a_in, const scap_launch_cfg* cfg, hipStream
     if ((size_t)a.Sl * a.Kl > union_list_entries(a.K)) return SCAP_ERR_SHAPE;
     // K split of the GEMM: whole segments, at most 64 per workgroup; no list in LDS
     kc = (int)align_up((size_t)kc, (size_t)a.Kl);  // a requested split is rounded up to whole segments
-    const int rc = plan_splits(a, kMfmaTile, 0, kc, kc != 0);
+    if (kc == 0) {
+        // Segments per workgroup g: every workgroup gets the same number (an uneven last split leaves compute
+        // units idle at the end), and the busiest compute unit -- ceil(workgroups / 256) workgroups of g
+        // segments -- should have as little as possible; ties go to the larger g (fewer partial sums).
+        const int tiles = (a.N + tile_cols - 1) / tile_cols;
+        long best_cost = -1;
+        int best_g = 1;
+        for (int g = 1; g <= a.Sl && g <= 64; ++g) {
+            const int splits = (a.Sl + g - 1) / g;
+            const long cost = (((long)splits * tiles + 255) / 256) * g;
+            if (best_cost < 0 || cost <= best_cost) {
+                best_cost = cost;
+                best_g = g;
+            }
+        }
+        kc = best_g * a.Kl;
+    }
+    const int rc = plan_splits(a, tile_cols, 0, kc, cfg && cfg->rows_per_group);
     if (rc != SCAP_OK) return rc;
     a.Kc = (int)align_up((size_t)a.Kc, (size_t)a.Kl);
     if (a.Kc / a.Kl > 64) a.Kc = 64 * a.Kl;
     a.S = (a.K + a.Kc - 1) / a.Kc;
-    if ((size_t)a.S * a.T * kMfmaTile > partial_capacity(a.N)) return SCAP_ERR_SHAPE;
+    if ((size_t)a.S * a.T * tile_cols > partial_capacity(a.N)) return SCAP_ERR_SHAPE;
 
     hipLaunchKernelGGL(batch_union_kernel, dim3((unsigned)a.Sl), dim3(kCompactWaves * kWave), 0, stream, a);
     if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
 
     // reduction buffers: waves x 4 token groups x 128 columns (the final reduction needs less)
-    const size_t lds = lds_bytes(0, 0, (size_t)waves * 4 * kMfmaTile * 4);
+    const size_t lds = lds_bytes(0, 0, (size_t)waves * 4 * tile_cols * 4);
+    if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
     const dim3 grid((unsigned)(a.S * a.T));
     const dim3 block(waves * kWave);
-#define SCAP_MFMA_CASE(WV, UBV)                                                                     \
-    if (waves == WV && ub == UBV) {                                                                  \
-        hipLaunchKernelGGL((gemm_mfma_kernel<WV, UBV>), grid, block, lds, stream, a);                \
+#define SCAP_MFMA_CASE(WD, WV, UBV)                                                                 \
+    if (wdt == WD && waves == WV && ub == UBV) {                                                     \
+        hipLaunchKernelGGL((gemm_mfma_kernel<WD, WV, UBV>), grid, block, lds, stream, a);            \
         return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;                             \
     }
-    SCAP_MFMA_CASE(16, 1) SCAP_MFMA_CASE(16, 2) SCAP_MFMA_CASE(16, 4)
-    SCAP_MFMA_CASE(8, 1) SCAP_MFMA_CASE(8, 2) SCAP_MFMA_CASE(8, 4)
+    SCAP_MFMA_CASE(kBF16, 16, 1) SCAP_MFMA_CASE(kBF16, 16, 2) SCAP_MFMA_CASE(kBF16, 16, 4)
+    SCAP_MFMA_CASE(kBF16, 8, 1) SCAP_MFMA_CASE(kBF16, 8, 2) SCAP_MFMA_CASE(kBF16, 8, 4)
+    SCAP_MFMA_CASE(kI8, 8, 1) SCAP_MFMA_CASE(kI8, 8, 2)
 #undef SCAP_MFMA_CASE
     return SCAP_ERR_CONFIG;
 }

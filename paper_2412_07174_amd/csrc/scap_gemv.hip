@@ -115,12 +115,12 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     while (bt < a.B) bt <<= 1;
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
-    // Several tokens over bf16 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
+    // Several tokens over bf16 or int8 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
     // lanes_per_row = 16 asks for that kernel (its lane layout), 64 or 32 for the vector kernel.
     const int lanes = cfg ? cfg->lanes_per_row : 0;
-    const bool mfma_ok = a.B >= kMfmaMinTokens && wdt == kBF16 && a.mode != kModeFold;
+    const bool mfma_ok = a.B >= kMfmaMinTokens && (wdt == kBF16 || wdt == kI8) && a.mode != kModeFold;
     if (lanes == 16 && !mfma_ok) return SCAP_ERR_CONFIG;
-    if (mfma_ok && (lanes == 16 || (lanes == 0 && a.B >= kMfmaAutoTokens))) return launch_gemm_mfma(a, cfg, stream);
+    if (mfma_ok && (lanes == 16 || (lanes == 0 && a.B >= kMfmaAutoTokens))) return launch_gemm_mfma(a, wdt, cfg, stream);
 
     int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0, lpr = 64;
     if (cfg) {

@@ -94,12 +94,12 @@ int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipSt
 int launch_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F, int elem_bytes, void* out,
                         hipStream_t stream);
 
-// Batched tokens over bf16 weights on the matrix cores: possible from kMfmaMinTokens tokens on (the
+// Batched tokens over bf16 or int8 weights on the matrix cores: possible from kMfmaMinTokens tokens on (the
 // workspace then carries the union lists), chosen by default from kMfmaAutoTokens on -- at 4 tokens the
 // single-launch vector kernel is still faster (measured 31 vs 41 us on 14336 x 4096).
 constexpr int kMfmaMinTokens = 2;
 constexpr int kMfmaAutoTokens = 5;
-int launch_gemm_mfma(const GemvArgs& a, const scap_launch_cfg* cfg, hipStream_t stream);
+int launch_gemm_mfma(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
 
 // Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).
 int launch_zero_words(int32_t* p, size_t n, hipStream_t stream);

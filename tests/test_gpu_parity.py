@@ -283,6 +283,25 @@ def test_int8_weights(K, N, B):
     assert np.allclose(bf.cpu().numpy(), bf_want, rtol=1e-5, atol=1e-5)
 
 
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix"])
+@pytest.mark.parametrize("B", [2, 5, 8, 13, 16])
+def test_int8_batched_tokens(B, path):
+    """int8 weights with several tokens: the matrix-core kernel widens int8 to bf16 exactly (auto from 5 tokens)."""
+    K, N = 2500, 1040          # 5 ragged 256-column tiles on the matrix cores, 2 tiles of 1024 on the vector kernel
+    q, scale = wl.quantize_i8(K, N, 611)
+    layer = Layer(q, I8, col_scale_bits=scale, B=16)
+    X = wl.swiglu(B, K, 612 + B, BF16)
+    bf = np.random.default_rng(613).standard_normal(N).astype(np.float32)
+    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16)}[path]
+    for tau in (0.0, 0.15, 0.8, 50.0):
+        say(f"int8 batched B={B} path={path} tau={tau}")
+        check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"int8 B={B} {path} tau={tau}")
+    # extreme codes: every weight -128 or 127
+    q2 = np.where(np.random.default_rng(614).random((K, N)) < 0.5, -128, 127).astype(np.int8)
+    layer2 = Layer(q2, I8, col_scale_bits=scale, B=16)
+    check_against_oracle(layer2, X, BF16, 0.0, 0.3, None, cfg=cfg, what=f"int8 extremes B={B} {path}")
+
+
 def test_config5_expert_down_projection():
     site = wl.sites(5)[1]          # expert 0, down 14336 -> 4096, int8
     q, scale = wl.quantize_i8(site.K, site.N, site.seed_w)
