@@ -196,10 +196,30 @@ def run_suite(args, torch, scap, wl, dev):
     run_block("mistral7b_ffn", 4096, 14336, 4096, (0.5, 0.7, 0.9))
     run_block("llama2_7b_ffn", 4096, 11008, 4096, (0.5,))
 
+    # Offline calibration at the paper's sample size (64 slices x 256 tokens per layer): wall time of the
+    # synchronous call, median estimator + threshold.
+    calib_rows = []
+    for K in (4096, 14336):
+        n = 16384
+        Xc = torch.randn(n, K, device=dev).to(torch.bfloat16)
+        wsc = scap.Workspace(K, 0, n)
+        scap.calibrate(Xc, 0.5, scap.MODE_MEDIAN, workspace=wsc)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 5
+        for _ in range(reps):
+            scap.calibrate(Xc, 0.5, scap.MODE_MEDIAN, workspace=wsc)
+        dt_ms = (time.perf_counter() - t0) / reps * 1e3
+        calib_rows.append({"n_tokens": n, "K": K, "estimator": "median", "ms": round(dt_ms, 3),
+                           "sample_GB": round(n * K * 2 / 1e9, 3),
+                           "GBps_over_all_passes": round(12 * n * K * 2 / dt_ms / 1e6, 1)})
+        del Xc
+        torch.cuda.empty_cache()
+
     layer3 = [r for r in rows if r["cfg"] == 3]
     summary = {"mistral_layer_fc_set_dense_us": round(sum(r["us"] for r in layer3 if r["target"] is None), 2),
                "mistral_layer_fc_set_s50_us": round(sum(r["us"] for r in layer3 if r["target"] == 0.5), 2)}
-    print(json.dumps({"suite": rows, "blocks": blocks, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
+    print(json.dumps({"suite": rows, "blocks": blocks, "calibration": calib_rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
                       "note": "GB/s = (rows read x N x sizeof(w) + x + bias + y) / time; density = union of the "
                               "batch's masks / K"}))
     return 0

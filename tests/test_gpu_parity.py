@@ -368,3 +368,22 @@ def test_calibrate_odd_count_and_small_sample():
         for s in (0.001, 0.25, 0.999):
             say(f"calibrate odd est={est} s={s}")
             assert scap.calibrate(Xd, s, oracle.EST[est], workspace=ws) == oracle.calibrate(X, F16, s, oracle.EST[est])
+
+
+def test_calibrate_paper_sized_sample():
+    """The paper calibrates on 64 slices of 256 tokens = 16384 tokens per layer (Section 4): 67 million pooled
+    values for a 4096-wide input.  Median and threshold must still equal the oracle's sort bit for bit."""
+    n, K = 16384, 4096
+    X = wl.prenorm(n, K, 951, BF16, 952)
+    Xd = to_dev(X, BF16)
+    ws = scap.Workspace(K, 0, n)
+    say("calibrate 16384 x 4096 median s=0.5")
+    got = scap.calibrate(Xd, 0.5, scap.MODE_MEDIAN, workspace=ws)
+    want = oracle.calibrate(X, BF16, 0.5, oracle.MODE_MEDIAN)
+    assert got == want, f"{got} vs {want}"
+    # a second target on the same sample, uncentred, checked against numpy's order statistic
+    say("calibrate 16384 x 4096 zero s=0.9")
+    _, tau = scap.calibrate(Xd, 0.9, scap.MODE_ZERO, workspace=ws)
+    v = np.abs(wl.decode(X, BF16).astype(np.float32)).ravel()
+    k = int(np.ceil(np.float64(np.float32(0.9)) * v.size))
+    assert tau == float(np.partition(v, k - 1)[k - 1])
