@@ -120,7 +120,7 @@ int scap_version(void) { return 100; }
 
 size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B) {
     if (K < 1 || N < 0 || B < 1) return 0;
-    if (N == 0) return kOffSegCnt;  // calibration only uses the fixed header
+    if (N == 0) return kCalibBytes;  // calibration only: fixed header + the code histogram
     if (K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19) || B > SCAP_MAX_TOKENS) return 0;
     return union_list_offset(N, B) + (B >= kMfmaMinTokens ? union_list_entries(K) * 68 : 0);
 }
@@ -140,7 +140,7 @@ int scap_calibrate(const void* X_calib, int64_t n, int64_t K, int xdt, float tar
     if (n < 1 || K < 1 || K > ((int64_t)1 << 24) || n > ((int64_t)1 << 34) / K) return SCAP_ERR_SHAPE;
     if (!(target_sparsity >= 0.f && target_sparsity < 1.f)) return SCAP_ERR_VALUE;
     if (!aligned16(X_calib)) return SCAP_ERR_ALIGN;
-    if (!workspace || workspace_bytes < kOffSegCnt) return SCAP_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < kCalibBytes) return SCAP_ERR_WORKSPACE;
     if (!aligned16(workspace)) return SCAP_ERR_ALIGN;
     return run_calibrate(static_cast<const uint16_t*>(X_calib), n * K, xdt, target_sparsity, est, m_out, tau_out,
                          workspace, static_cast<hipStream_t>(stream));

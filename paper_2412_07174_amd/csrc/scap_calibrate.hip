@@ -1,8 +1,17 @@
-// Offline calibration on the GPU (SCAP Eq. 2: tau = Quantile(|X_calib|, s); Section 3: mode estimate
-// first, threshold on the centred sample).  Order statistics are exact: an 8-bit-digit radix select over
-// the fp32 bit patterns (four histogram passes per rank), so tau and the median carry no float error.
+// Offline calibration (SCAP Eq. 2: tau = Quantile(|X_calib|, s); Section 3: mode estimate first, threshold
+// on the centred sample).
+//
+// The calibration activations are 16-bit codes, so a pooled sample of any size has at most 65 536 distinct
+// values.  ONE streaming pass over the sample counts how often each code occurs; every statistic the
+// estimators need is then a function of those 65 536 counts and is evaluated on the host with the same
+// IEEE operations the pruner uses on the device (widening is exact, d = fp32(x) - m is one fp32
+// subtraction): order statistics by walking the counts in value order -- exact, no float error -- the mean
+// as an fp64 sum of count x value, the histogram mode from fp64 bin arithmetic.
 #include <math.h>
+#include <string.h>
 
+#include <algorithm>
+#include <utility>
 #include <vector>
 
 #include "scap_device.hpp"
@@ -10,128 +19,167 @@
 
 namespace scap {
 
-// ascending numeric order == ascending unsigned key; every NaN ranks last
-__device__ __forceinline__ uint32_t order_key(float v) {
-    if (v != v) return 0xFFFFFFFFu;
-    const uint32_t u = __float_as_uint(v);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
+constexpr int kCodes = 65536;
+constexpr int kQuarter = 16384;     // codes counted by one workgroup (64 KB of LDS counters)
+constexpr int kHistThreads = 1024;
+constexpr int kHistChunks = 64;     // workgroups per quarter
 
-static float key_to_float(uint32_t key) {
-    const uint32_t u = (key & 0x80000000u) ? (key ^ 0x80000000u) : ~key;
-    union { uint32_t u; float f; } cv;
-    cv.u = u;
-    return cv.f;
-}
-
-// value whose order statistics are wanted: the raw activation, or its importance |fp32(x) - m|
-__device__ __forceinline__ float calib_value(const uint16_t* __restrict__ X, int64_t j, int xdt, int centred, float m) {
-    const float xf = act_to_f32(X, j, xdt);
-    if (!centred) return xf;
-    const float d = xf - m;  // formed exactly as the pruner forms it
-    return fabsf(d);
-}
-
-__global__ __launch_bounds__(256) void radix_hist_kernel(const uint16_t* __restrict__ X, int64_t M, int xdt, int centred,
-                                                         float m, uint32_t prefix, uint32_t prefix_mask, int shift,
-                                                         unsigned long long* __restrict__ hist) {
-    __shared__ uint32_t sh[256];
-    sh[threadIdx.x] = 0;
+// Workgroup (chunk, quarter) reads its share of the sample 16 bytes per lane and counts the codes whose top
+// two bits equal `quarter` in LDS, then adds its non-zero counters to the global histogram.
+__global__ __launch_bounds__(kHistThreads) void code_hist_kernel(const uint16_t* __restrict__ X, int64_t M,
+                                                                unsigned long long* __restrict__ hist) {
+    __shared__ uint32_t sh[kQuarter];
+    const int tid = threadIdx.x;
+    const uint32_t quarter = blockIdx.x & 3u;
+    const int chunk = blockIdx.x >> 2;
+    const int nchunk = gridDim.x >> 2;
+    for (int i = tid; i < kQuarter; i += kHistThreads) sh[i] = 0;
     __syncthreads();
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < M; j += stride) {
-        const uint32_t key = order_key(calib_value(X, j, xdt, centred, m));
-        if ((key & prefix_mask) == prefix) atomicAdd(&sh[(key >> shift) & 0xFFu], 1u);
+    auto count = [&](uint32_t code) {
+        if ((code >> 14) == quarter) atomicAdd(&sh[code & (kQuarter - 1)], 1u);
+    };
+    const int64_t nvec = M / 8;
+    const uint4* __restrict__ X8 = reinterpret_cast<const uint4*>(X);
+    for (int64_t i = (int64_t)chunk * kHistThreads + tid; i < nvec; i += (int64_t)nchunk * kHistThreads) {
+        const uint4 v = X8[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            count(w[q] & 0xFFFFu);
+            count(w[q] >> 16);
+        }
+    }
+    if (chunk == 0) {
+        const int64_t j = nvec * 8 + tid;  // the last M % 8 codes
+        if (j < M) count(X[j]);
     }
     __syncthreads();
-    const uint32_t v = sh[threadIdx.x];
-    if (v) atomicAdd(&hist[threadIdx.x], (unsigned long long)v);
-}
-
-__global__ __launch_bounds__(256) void block_sum_kernel(const uint16_t* __restrict__ X, int64_t M, int xdt,
-                                                        double* __restrict__ sums) {
-    __shared__ double sh[256];
-    double acc = 0.0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < M; j += stride)
-        acc += (double)act_to_f32(X, j, xdt);
-    sh[threadIdx.x] = acc;
-    __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) sh[threadIdx.x] += sh[threadIdx.x + off];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) sums[blockIdx.x] = sh[0];
-}
-
-// equal-width histogram between lo and hi (inclusive), bin = floor((v - lo) / w) in fp64
-__global__ __launch_bounds__(256) void mode_hist_kernel(const uint16_t* __restrict__ X, int64_t M, int xdt, float lo,
-                                                        float hi, double w, unsigned long long* __restrict__ hist) {
-    __shared__ uint32_t sh[kHistBins];
-    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) sh[i] = 0;
-    __syncthreads();
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < M; j += stride) {
-        const float v = act_to_f32(X, j, xdt);
-        if (!(v >= lo && v <= hi)) continue;
-        long long b = (long long)floor(((double)v - (double)lo) / w);
-        if (b > kHistBins - 1) b = kHistBins - 1;
-        if (b < 0) b = 0;
-        atomicAdd(&sh[b], 1u);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) {
+    for (int i = tid; i < kQuarter; i += kHistThreads) {
         const uint32_t v = sh[i];
-        if (v) atomicAdd(&hist[i], (unsigned long long)v);
+        if (v) atomicAdd(&hist[quarter * kQuarter + i], (unsigned long long)v);
     }
 }
 
 namespace {
 
-struct Ctx {
-    const uint16_t* X;
-    int64_t M;
-    int xdt;
-    unsigned long long* d_hist;
-    double* d_sums;
-    hipStream_t stream;
-    int blocks;
-};
-
 bool ok(hipError_t e) { return e == hipSuccess; }
 
-int fetch(const Ctx& c, void* host, const void* dev, size_t bytes) {
-    if (!ok(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, c.stream))) return SCAP_ERR_HIP;
-    if (!ok(hipStreamSynchronize(c.stream))) return SCAP_ERR_HIP;
-    return SCAP_OK;
+// exact widening of a 16-bit code on the host
+float code_to_float(uint32_t c, int xdt) {
+    uint32_t u;
+    if (xdt == kBF16) {
+        u = c << 16;
+    } else {
+        const uint32_t sign = (c & 0x8000u) << 16, e = (c >> 10) & 0x1Fu, f = c & 0x3FFu;
+        if (e == 0x1Fu) {
+            u = sign | 0x7F800000u | (f << 13);
+        } else if (e != 0) {
+            u = sign | ((e + 112u) << 23) | (f << 13);
+        } else if (f == 0) {
+            u = sign;
+        } else {  // subnormal half: normalise
+            int sh = 0;
+            uint32_t m = f;
+            while (!(m & 0x400u)) {
+                m <<= 1;
+                ++sh;
+            }
+            u = sign | ((113u - sh) << 23) | ((m & 0x3FFu) << 13);
+        }
+    }
+    float v;
+    memcpy(&v, &u, 4);
+    return v;
 }
 
-// k-th smallest (1-indexed, 1 <= k <= M) of the raw values (centred = 0) or of |x - m| (centred = 1)
-int select_rank(const Ctx& c, int centred, float m, int64_t k, float* out) {
-    uint32_t prefix = 0, mask = 0;
-    unsigned long long h[256];
-    unsigned long long want = (unsigned long long)k;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        int rc = launch_zero_words(reinterpret_cast<int32_t*>(c.d_hist), 512, c.stream);
-        if (rc != SCAP_OK) return rc;
-        hipLaunchKernelGGL(radix_hist_kernel, dim3(c.blocks), dim3(256), 0, c.stream, c.X, c.M, c.xdt, centred, m, prefix,
-                           mask, shift, c.d_hist);
-        if (!ok(hipGetLastError())) return SCAP_ERR_HIP;
-        rc = fetch(c, h, c.d_hist, sizeof(h));
-        if (rc != SCAP_OK) return rc;
-        int digit = 255;
-        for (int d = 0; d < 256; ++d) {
-            if (want <= h[d]) {
-                digit = d;
-                break;
-            }
-            want -= h[d];
+// The sample as (value, count) pairs in ascending value order; NaNs counted apart (they rank last).
+struct Table {
+    std::vector<float> val;
+    std::vector<unsigned long long> cnt;
+    unsigned long long nans = 0;
+};
+
+Table make_table(const std::vector<unsigned long long>& hist, int xdt) {
+    Table t;
+    auto push = [&](uint32_t c) {
+        if (!hist[c]) return;
+        const float v = code_to_float(c, xdt);
+        if (v != v) {
+            t.nans += hist[c];
+        } else {
+            t.val.push_back(v);
+            t.cnt.push_back(hist[c]);
         }
-        prefix |= (uint32_t)digit << shift;
-        mask |= 0xFFu << shift;
+    };
+    // both formats order like sign-magnitude integers: negatives from the largest magnitude down, then
+    // positives up (-0 sorts before +0; they are equal as numbers, which no statistic below can tell apart)
+    for (int c = 0xFFFF; c >= 0x8000; --c) push((uint32_t)c);
+    for (int c = 0x0000; c <= 0x7FFF; ++c) push((uint32_t)c);
+    return t;
+}
+
+float quiet_nan() {
+    const uint32_t u = 0x7FFFFFFFu;
+    float v;
+    memcpy(&v, &u, 4);
+    return v;
+}
+
+// k-th smallest of the raw values, 1 <= k <= M
+float select_raw(const Table& t, unsigned long long k) {
+    unsigned long long run = 0;
+    for (size_t i = 0; i < t.val.size(); ++i) {
+        run += t.cnt[i];
+        if (k <= run) return t.val[i];
     }
-    *out = key_to_float(prefix);
-    return SCAP_OK;
+    return quiet_nan();
+}
+
+// k-th smallest of |value - m| (one fp32 subtraction, as the pruner forms it).  Below m the importance
+// falls as the value rises, above m it rises (fp32 rounding is monotone), so the sorted order is a merge
+// of the two runs that start at the value nearest m.
+float select_centred(const Table& t, float m, unsigned long long k) {
+    if (m != m) return quiet_nan();
+    const size_t n = t.val.size();
+    std::vector<float> imp(n);
+    size_t p = n;  // first entry with value - m >= 0
+    bool any_nan = false;
+    for (size_t i = 0; i < n; ++i) {
+        volatile float d = t.val[i] - m;
+        imp[i] = fabsf(d);
+        any_nan |= imp[i] != imp[i];
+        if (p == n && !(d < 0.f)) p = i;
+    }
+    if (any_nan) {
+        // infinite m meeting an infinite sample: no monotone runs; sort outright, NaN importances last
+        std::vector<std::pair<float, unsigned long long>> e;
+        unsigned long long run = 0;
+        for (size_t i = 0; i < n; ++i)
+            if (imp[i] == imp[i]) e.emplace_back(imp[i], t.cnt[i]);
+        std::sort(e.begin(), e.end());
+        for (const auto& x : e) {
+            run += x.second;
+            if (k <= run) return x.first;
+        }
+        return quiet_nan();
+    }
+    size_t up = p;          // next candidate of the rising run
+    size_t down = p;        // one past the next candidate of the falling run
+    unsigned long long run = 0;
+    while (up < n || down > 0) {
+        size_t pick;
+        if (up >= n)
+            pick = --down;
+        else if (down == 0)
+            pick = up++;
+        else if (imp[down - 1] <= imp[up])
+            pick = --down;
+        else
+            pick = up++;
+        run += t.cnt[pick];
+        if (k <= run) return imp[pick];
+    }
+    return quiet_nan();
 }
 
 int64_t rank_of(double q, int64_t M) {
@@ -145,68 +193,56 @@ int64_t rank_of(double q, int64_t M) {
 
 int run_calibrate(const uint16_t* X, int64_t M, int xdt, float s, int est, float* m_out, float* tau_out, void* workspace,
                   hipStream_t stream) {
-    Ctx c;
-    c.X = X;
-    c.M = M;
-    c.xdt = xdt;
-    c.d_hist = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kOffHist);
-    c.d_sums = reinterpret_cast<double*>(static_cast<char*>(workspace) + kOffSums);
-    c.stream = stream;
-    int64_t blocks = (M + 256 * 16 - 1) / (256 * 16);
-    if (blocks < 1) blocks = 1;
-    if (blocks > kSumSlots) blocks = kSumSlots;
-    c.blocks = (int)blocks;
+    if (est < SCAP_MODE_ZERO || est > SCAP_MODE_HIST) return SCAP_ERR_DTYPE;
+    unsigned long long* d_hist = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kOffCodeHist);
+    int rc = launch_zero_words(reinterpret_cast<int32_t*>(d_hist), 2 * (size_t)kCodes, stream);
+    if (rc != SCAP_OK) return rc;
+    hipLaunchKernelGGL(code_hist_kernel, dim3(4 * kHistChunks), dim3(kHistThreads), 0, stream, X, M, d_hist);
+    if (!ok(hipGetLastError())) return SCAP_ERR_HIP;
+    std::vector<unsigned long long> hist(kCodes);
+    if (!ok(hipMemcpyAsync(hist.data(), d_hist, sizeof(unsigned long long) * kCodes, hipMemcpyDeviceToHost, stream)))
+        return SCAP_ERR_HIP;
+    if (!ok(hipStreamSynchronize(stream))) return SCAP_ERR_HIP;
+    const Table t = make_table(hist, xdt);
 
     float m = 0.f;
-    int rc;
     if (est == SCAP_MODE_MEAN) {
-        hipLaunchKernelGGL(block_sum_kernel, dim3(c.blocks), dim3(256), 0, stream, X, M, xdt, c.d_sums);
-        if (!ok(hipGetLastError())) return SCAP_ERR_HIP;
-        std::vector<double> part((size_t)c.blocks);
-        rc = fetch(c, part.data(), c.d_sums, sizeof(double) * (size_t)c.blocks);
-        if (rc != SCAP_OK) return rc;
-        double sum = 0.0;
-        for (double p : part) sum += p;
+        double sum = t.nans ? (double)quiet_nan() : 0.0;
+        for (size_t i = 0; i < t.val.size(); ++i) sum += (double)t.cnt[i] * (double)t.val[i];
         m = (float)(sum / (double)M);
     } else if (est == SCAP_MODE_MEDIAN) {
-        float a, b;
         if (M % 2 == 1) {
-            rc = select_rank(c, 0, 0.f, M / 2 + 1, &a);
-            if (rc != SCAP_OK) return rc;
-            m = a;
+            m = select_raw(t, (unsigned long long)(M / 2 + 1));
         } else {
-            rc = select_rank(c, 0, 0.f, M / 2, &a);
-            if (rc != SCAP_OK) return rc;
-            rc = select_rank(c, 0, 0.f, M / 2 + 1, &b);
-            if (rc != SCAP_OK) return rc;
+            const float a = select_raw(t, (unsigned long long)(M / 2));
+            const float b = select_raw(t, (unsigned long long)(M / 2 + 1));
             m = (float)(((double)a + (double)b) / 2.0);
         }
     } else if (est == SCAP_MODE_HIST) {
-        float lo, hi;
         int64_t klo = rank_of(0.001, M), khi = rank_of(0.999, M);
         if (klo < 1) klo = 1;
         if (khi < 1) khi = 1;
-        rc = select_rank(c, 0, 0.f, klo, &lo);
-        if (rc != SCAP_OK) return rc;
-        rc = select_rank(c, 0, 0.f, khi, &hi);
-        if (rc != SCAP_OK) return rc;
+        const float lo = select_raw(t, (unsigned long long)klo), hi = select_raw(t, (unsigned long long)khi);
         if (!(hi > lo)) {
             m = lo;
         } else {
+            // 2048 equal bins between lo and hi (inclusive), bin = floor((v - lo) / w) in fp64
             const double w = ((double)hi - (double)lo) / (double)kHistBins;
-            rc = launch_zero_words(reinterpret_cast<int32_t*>(c.d_hist), 2 * kHistBins, stream);
-            if (rc != SCAP_OK) return rc;
-            hipLaunchKernelGGL(mode_hist_kernel, dim3(c.blocks), dim3(256), 0, stream, X, M, xdt, lo, hi, w, c.d_hist);
-            if (!ok(hipGetLastError())) return SCAP_ERR_HIP;
-            std::vector<unsigned long long> cnt(kHistBins);
-            rc = fetch(c, cnt.data(), c.d_hist, sizeof(unsigned long long) * kHistBins);
-            if (rc != SCAP_OK) return rc;
+            std::vector<long long> cnt(kHistBins, 0);
+            for (size_t i = 0; i < t.val.size(); ++i) {
+                const float v = t.val[i];
+                if (!(v >= lo && v <= hi)) continue;
+                long long b = (long long)floor(((double)v - (double)lo) / w);
+                if (b > kHistBins - 1) b = kHistBins - 1;
+                if (b < 0) b = 0;
+                cnt[b] += (long long)t.cnt[i];
+            }
             long long best = -1;
             int bestb = 0;
             for (int b = 0; b < kHistBins; ++b) {
                 long long sum = 0;
-                for (int t = b - 2; t <= b + 2; ++t)
-                    if (t >= 0 && t < kHistBins) sum += (long long)cnt[t];
+                for (int q = b - 2; q <= b + 2; ++q)
+                    if (q >= 0 && q < kHistBins) sum += cnt[q];
                 if (sum > best) {
                     best = sum;
                     bestb = b;
@@ -216,16 +252,11 @@ int run_calibrate(const uint16_t* X, int64_t M, int xdt, float s, int est, float
             volatile double mode = (double)lo + centre;
             m = (float)mode;
         }
-    } else if (est != SCAP_MODE_ZERO) {
-        return SCAP_ERR_DTYPE;
     }
 
     float tau = 0.f;
     const int64_t k = rank_of((double)s, M);
-    if (k > 0) {
-        rc = select_rank(c, 1, m, k, &tau);
-        if (rc != SCAP_OK) return rc;
-    }
+    if (k > 0) tau = select_centred(t, m, (unsigned long long)k);
     *m_out = m;
     *tau_out = tau;
     return SCAP_OK;

@@ -21,25 +21,23 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 
 // ---------------------------------------------------------------------------------------------
 // Workspace layout (byte offsets into the caller's buffer)
-//   [4096, 20480)        uint64 hist[2048]       calibration histograms
-//   [20480, 28672)       double sums[1024]       calibration partial sums
 //   [65536, +32768)      int32 seg_cnt[17][256]  kept-channel counts per (token | union, K split)
 //   [131072, +1 MiB)     int32 counter per column tile, one every 1 KiB so that the arrival tickets of
 //                        different tiles go to different memory channels; zero at rest
-//   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums
+//   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums; during calibration the first
+//                        512 KiB hold the uint64 count of every 16-bit code
 //   [.., +68*(K+16384))  batched path (B >= 2): union list of every list segment (16 centred values and
 //                        the channel index per entry)
 // ---------------------------------------------------------------------------------------------
-constexpr size_t kOffHist = 4096;
-constexpr size_t kOffSums = 20480;
 constexpr size_t kOffSegCnt = 65536;
 constexpr size_t kOffCounters = 131072;
 constexpr int kCounterStride = 256;  // int32 words between the counters of neighbouring tiles
 constexpr size_t kOffPartial = kOffCounters + 1024 * (size_t)kCounterStride * 4;
+constexpr size_t kOffCodeHist = kOffPartial;
+constexpr size_t kCalibBytes = kOffCodeHist + 65536 * 8;  // workspace bytes calibration needs
 constexpr int kMaxTiles = 1024;
 constexpr int kMaxSplits = 256;
 constexpr int kHistBins = 2048;
-constexpr int kSumSlots = 1024;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -45,7 +45,7 @@ def test_status_strings_and_version(lib):
 
 def test_workspace_bytes(lib):
     assert scap.workspace_bytes(14336, 4096, 1) >= 4 * (1 << 20)
-    assert scap.workspace_bytes(1024, 0, 256) == 65536          # calibration-only
+    assert 0 < scap.workspace_bytes(1024, 0, 256) < scap.workspace_bytes(1024, 8, 1)   # calibration-only
     assert scap.workspace_bytes(0, 4096, 1) == 0
     assert scap.workspace_bytes(4096, 4096, 17) == 0
     assert scap.workspace_bytes(4096, 4096, 16) > scap.workspace_bytes(4096, 4096, 1)
@@ -82,13 +82,13 @@ def test_sparse_fc_argument_validation(lib):
 def test_other_entry_points_validate(lib):
     f = ctypes.c_float(0)
     p = ctypes.byref(f)
-    assert lib.scap_calibrate(None, 4, 8, 1, 0.5, 2, p, p, FAKE, 65536, None) == -1
-    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 2, None, p, FAKE, 65536, None) == -1
-    assert lib.scap_calibrate(FAKE, 4, 8, 2, 0.5, 2, p, p, FAKE, 65536, None) == -3
-    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 9, p, p, FAKE, 65536, None) == -3
-    assert lib.scap_calibrate(FAKE, 0, 8, 1, 0.5, 2, p, p, FAKE, 65536, None) == -2
-    assert lib.scap_calibrate(FAKE, 4, 8, 1, 1.0, 2, p, p, FAKE, 65536, None) == -5
-    assert lib.scap_calibrate(FAKE, 4, 8, 1, -0.1, 2, p, p, FAKE, 65536, None) == -5
+    assert lib.scap_calibrate(None, 4, 8, 1, 0.5, 2, p, p, FAKE, 1 << 21, None) == -1
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 2, None, p, FAKE, 1 << 21, None) == -1
+    assert lib.scap_calibrate(FAKE, 4, 8, 2, 0.5, 2, p, p, FAKE, 1 << 21, None) == -3
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 9, p, p, FAKE, 1 << 21, None) == -3
+    assert lib.scap_calibrate(FAKE, 0, 8, 1, 0.5, 2, p, p, FAKE, 1 << 21, None) == -2
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, 1.0, 2, p, p, FAKE, 1 << 21, None) == -5
+    assert lib.scap_calibrate(FAKE, 4, 8, 1, -0.1, 2, p, p, FAKE, 1 << 21, None) == -5
     assert lib.scap_calibrate(FAKE, 4, 8, 1, 0.5, 2, p, p, FAKE, 100, None) == -6
     assert lib.scap_fold_bias(None, None, 8, 8, 1, None, 0.0, FAKE, FAKE, 1 << 30, None) == -1
     assert lib.scap_fold_bias(FAKE, None, 8, 8, 1, None, float("nan"), FAKE, FAKE, 1 << 30, None) == -5

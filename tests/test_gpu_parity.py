@@ -387,3 +387,22 @@ def test_calibrate_paper_sized_sample():
     v = np.abs(wl.decode(X, BF16).astype(np.float32)).ravel()
     k = int(np.ceil(np.float64(np.float32(0.9)) * v.size))
     assert tau == float(np.partition(v, k - 1)[k - 1])
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+def test_calibrate_every_code_pattern(dt):
+    """Every 16-bit code at least once (subnormals, both zeros, infinities, NaNs) plus a random bulk, a count
+    that is not a multiple of the 8-code load; order statistics must still equal the oracle's sort."""
+    rng = np.random.default_rng(961 + dt)
+    bulk = wl.laplace(1, 50001, 962, dt, loc=0.3, scale=0.4)[0]
+    X = np.concatenate([np.arange(65536, dtype=np.uint16), bulk, rng.integers(0, 65536, 4099).astype(np.uint16)])
+    rng.shuffle(X)
+    X = X.reshape(1, -1)
+    Xd = to_dev(X, dt)
+    ws = scap.Workspace(X.shape[1], 0, 1)
+    for est in ("zero", "median", "hist"):
+        for s in (0.01, 0.3, 0.5, 0.9):
+            say(f"calibrate all codes dt={dt} est={est} s={s}")
+            got = scap.calibrate(Xd, s, oracle.EST[est], workspace=ws)
+            want = oracle.calibrate(X, dt, s, oracle.EST[est])
+            assert got == want, f"{est} s={s}: {got} vs {want}"
