@@ -53,7 +53,7 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& a) {
     // ------------------------------------------------------------------ 1. centre, threshold, compact
     int cnt;
     if constexpr (FUSE == kFuseList)
-        cnt = gather_lists<WAVES>(a, split, L);
+        cnt = gather_lists<WAVES, BT>(a, split, L);
     else
         cnt = compact_inputs<WAVES, BT>(a, tile, split, L);
 

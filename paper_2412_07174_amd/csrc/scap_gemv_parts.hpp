@@ -60,7 +60,7 @@ struct Lds {
     int* idx;    // [Kc] kept channel indices, ascending (LDS, or global for the batched path)
     float* d;    // centred values per token (0 where the token pruned the channel); see d_at()
     float* red;  // reduction buffer; reuses the list space once the rows have been streamed
-    float* fin;  // kFuseSwiglu: the tile's finished columns (after scale and bias), [TILE]
+    float* fin;  // kFuseSwiglu: the tile's finished columns (after scale and bias), [BT][TILE]
 };
 
 // Position of token b's value of list entry e in Lds::d: token-major [BT][Kc] (a wavefront reads
@@ -277,12 +277,19 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
 }
 
 // ---------------------------------------------------------------------------------------------- list input
-// kFuseList prologue: the workgroup's Kc channels are Kc/64 segments of the previous launch's lists.  The
-// segment counts and every entry slot are loaded together (one memory latency); entry r of a segment goes
-// to position (entries of the earlier segments) + r.  Requires Kc/64 <= 64.  Ends with a barrier.
-template <int WAVES>
+// Lists of the gated product (fused SwiGLU block), one segment per 64 channels, BT = tokens rounded up to
+// a power of two:
+//   zl_idx[seg*64 + r]            r-th channel of the segment kept by at least one token, ascending
+//   zl_d[(seg*64 + r)*BT + b]     token b's centred value there, 0 where token b pruned the channel
+//   zl_cnt[seg]                   entries of the segment;  zl_cnt[(1+b)*nsegs + seg]  those kept by token b
+//
+// kFuseList prologue: the workgroup's Kc channels are Kc/64 segments.  The segment counts and every entry
+// slot are loaded together (one memory latency); entry r of a segment goes to position (entries of the
+// earlier segments) + r.  Requires Kc/64 <= 64.  Ends with a barrier.
+template <int WAVES, int BT>
 __device__ __forceinline__ int gather_lists(const GemvArgs& a, int split, const Lds& L) {
     constexpr int PER_WAVE = kWave / WAVES;  // segments a wavefront may have to move
+    typedef float dvec_t __attribute__((ext_vector_type(BT)));
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
     const int lane = tid & 63;
@@ -292,16 +299,23 @@ __device__ __forceinline__ int gather_lists(const GemvArgs& a, int split, const 
     int cv = lane < nseg ? a.zl_cnt[seg0 + lane] : 0;
     cv = min(max(cv, 0), kWave);  // a segment never holds more; keeps LDS writes in range whatever the memory holds
     int vi[PER_WAVE];
-    float vd[PER_WAVE];
+    float vd[PER_WAVE][BT];
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
         const int sl = w + j * WAVES;
         vi[j] = 0;
-        vd[j] = 0.f;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) vd[j][b] = 0.f;
         if (sl < nseg) {
             const int64_t p = (int64_t)(seg0 + sl) * kWave + lane;
             vi[j] = a.zl_idx[p];
-            vd[j] = a.zl_d[p];
+            if constexpr (BT == 1) {
+                vd[j][0] = a.zl_d[p];
+            } else {
+                const dvec_t v = *reinterpret_cast<const dvec_t*>(a.zl_d + p * BT);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) vd[j][b] = v[b];
+            }
         }
     }
     const int inc = wave_inclusive_scan(cv);
@@ -315,7 +329,8 @@ __device__ __forceinline__ int gather_lists(const GemvArgs& a, int split, const 
             const int off = __shfl(excl, sl, kWave);
             if (lane < c) {
                 L.idx[off + lane] = vi[j];
-                L.d[off + lane] = vd[j];
+#pragma unroll
+                for (int b = 0; b < BT; ++b) L.d[b * a.Kc + off + lane] = vd[j][b];
             }
         }
     }
@@ -323,11 +338,11 @@ __device__ __forceinline__ int gather_lists(const GemvArgs& a, int split, const 
     return uniform(total);
 }
 
-// kFuseSwiglu: the finished columns of a tile hold, per 8 columns, 4 gate then the 4 matching up
-// pre-activations.  Form z = silu(gate) * up (Alg. 2), centre and threshold it like any other layer input
-// (Alg. 3 steps 1-2, strict compare of Eq. 2) and leave each 64-channel segment's kept channels, compacted,
-// for the down launch.  Called by every thread of the tile's last arrival.
-template <int WAVES, int TILE>
+// kFuseSwiglu: the finished columns of a tile (s_fin[b*TILE + column]) hold, per 8 columns, 4 gate then the 4
+// matching up pre-activations.  Form z = silu(gate) * up (Alg. 2), centre and threshold it like any other
+// layer input (Alg. 3 steps 1-2, strict compare of Eq. 2; each token its own mask) and leave each 64-channel
+// segment's kept channels, compacted, for the down launch.  Called by every thread of the tile's last arrival.
+template <int WAVES, int TILE, int BT>
 __device__ __forceinline__ void gate_and_compact(const GemvArgs& a, int tile, const float* s_fin) {
     constexpr int HALF = TILE / 2;  // gated outputs per tile; a multiple of 64
     constexpr int NT = WAVES * kWave;
@@ -337,25 +352,74 @@ __device__ __forceinline__ void gate_and_compact(const GemvArgs& a, int tile, co
     for (int t0 = 0; t0 < HALF; t0 += NT) {
         const int t = t0 + tid;
         const int c = tile * HALF + t;
-        float dv = 0.f;
-        bool keep = false;
-        if (t < HALF && c < a.F) {
-            const int p = (t >> 2) * 8 + (t & 3);
-            const float g = s_fin[p], u = s_fin[p + 4];
-            const float z = g / (1.f + expf(-g)) * u;
-            if (a.z_out) a.z_out[c] = z;
-            dv = z - a.m2;
-            keep = fabsf(dv) > a.tau2;
+        float dv[BT];
+        bool keep[BT];
+        bool any = false;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            dv[b] = 0.f;
+            keep[b] = false;
+            if (b < a.B && t < HALF && c < a.F) {
+                const int p = b * TILE + (t >> 2) * 8 + (t & 3);
+                const float g = s_fin[p], u = s_fin[p + 4];
+                const float z = g / (1.f + expf(-g)) * u;
+                if (a.z_out) a.z_out[(int64_t)b * a.F + c] = z;
+                const float d = z - a.m2;
+                keep[b] = fabsf(d) > a.tau2;
+                dv[b] = keep[b] ? d : 0.f;
+                any |= keep[b];
+            }
         }
-        const uint64_t bal = __ballot(keep);
+        const uint64_t bal = __ballot(any);
         const int seg = uniform((tile * HALF + t0 + (tid & ~63)) >> 6);
-        if (t0 + (tid & ~63) < HALF && seg < nsegs) {
-            if (keep) {
+        const bool seg_ok = t0 + (tid & ~63) < HALF && seg < nsegs;  // wave-uniform
+        if (seg_ok) {
+            if (any) {
                 const int64_t p = (int64_t)seg * kWave + lanes_below(bal);
                 a.zl_idx[p] = c;
-                a.zl_d[p] = dv;
+#pragma unroll
+                for (int b = 0; b < BT; ++b) a.zl_d[p * BT + b] = dv[b];
             }
             if (lane == 0) a.zl_cnt[seg] = __popcll(bal);
+        }
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            const uint64_t tb = __ballot(keep[b]);
+            if (seg_ok && lane == 0 && b < a.B) a.zl_cnt[(1 + b) * nsegs + seg] = __popcll(tb);
+        }
+    }
+}
+
+// kFuseList, last arrival of tile 0: kept-channel count and gap-free ascending list of every token, from the
+// segment lists (an entry belongs to token b where its centred value is non-zero: kept means |d| > tau >= 0).
+// Other workgroups may still be reading the segment lists, so those stay as they are.
+template <int WAVES, int BT>
+__device__ __forceinline__ void close_block_lists(const GemvArgs& a, const Lds& L) {
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    int* s_off = L.idx;  // [Sl] exclusive offsets of the token's entries
+    for (int b = 0; b < a.B; ++b) {
+        __syncthreads();
+        if (w == 0) {
+            int run = 0;
+            for (int s0 = 0; s0 < a.Sl; s0 += kWave) {
+                const int sp = s0 + lane;
+                const int v = sp < a.Sl ? a.zl_cnt[(1 + b) * a.Sl + sp] : 0;
+                const int inc = wave_inclusive_scan(v);
+                if (sp < a.Sl) s_off[sp] = run + inc - v;
+                run += __shfl(inc, kWave - 1, kWave);
+            }
+            if (lane == 0 && a.nnz_out) a.nnz_out[b] = run;
+        }
+        __syncthreads();
+        if (a.idx_out == nullptr) continue;
+        for (int seg = w; seg < a.Sl; seg += WAVES) {
+            const int n = min(max(a.zl_cnt[seg], 0), kWave);
+            const int64_t p = (int64_t)seg * kWave + lane;
+            const bool mine = lane < n && a.zl_d[p * BT + b] != 0.f;
+            const uint64_t bal = __ballot(mine);
+            if (mine) a.idx_out[(int64_t)b * a.K + s_off[seg] + lanes_below(bal)] = a.zl_idx[p];
         }
     }
 }
@@ -380,7 +444,7 @@ __device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int 
         s.w += bv.w;
     }
     if constexpr (FUSE == kFuseSwiglu)
-        *reinterpret_cast<float4*>(s_fin + 4 * g) = s;
+        *reinterpret_cast<float4*>(s_fin + b * TILE + 4 * g) = s;
     else
         *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
 }
@@ -473,7 +537,11 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
     }
     if constexpr (FUSE == kFuseSwiglu) {
         __syncthreads();  // the tile's columns are complete in L.fin
-        gate_and_compact<WAVES, TILE>(a, tile, L.fin);
+        gate_and_compact<WAVES, TILE, BT>(a, tile, L.fin);
+    }
+    if constexpr (FUSE == kFuseList) {
+        if (tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr)) close_block_lists<WAVES, BT>(a, L);
+        return;
     }
 
     if (!wants_lists) return;
@@ -494,8 +562,7 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
             int run = 0;
             for (int s0 = 0; s0 < a.Sl; s0 += kWave) {
                 const int sp = s0 + lane;
-                const int row = (FUSE == kFuseList) ? 0 : (is_union ? a.B : src_l);
-                const int v = sp < a.Sl ? load_dev(&a.seg_cnt[row * a.Sl + sp]) : 0;
+                const int v = sp < a.Sl ? load_dev(&a.seg_cnt[(is_union ? a.B : src_l) * a.Sl + sp]) : 0;
                 const int inc = wave_inclusive_scan(v);
                 if (sp < a.Sl) {
                     s_off[sp] = run + inc - v;
@@ -511,12 +578,8 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
             }
         }
         __syncthreads();
-        // list input: the source is the previous launch's segment lists, other workgroups may still be
-        // reading them, so the closed-up copy goes to idx_out and the source stays as it is
-        const bool in_place = FUSE != kFuseList;
-        if (!is_union && a.idx_out != nullptr && (a.Sl > 1 || !in_place)) {
+        if (!is_union && a.idx_out != nullptr && a.Sl > 1) {
             int32_t* base = a.idx_out + (int64_t)l * a.K;
-            const int32_t* src = in_place ? base : a.zl_idx;
             constexpr int PER = 16;
             for (int c0 = 0; c0 < a.K; c0 += NT * PER) {
                 int vals[PER], dsts[PER];
@@ -529,7 +592,7 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
                         const int seg = p / a.Kl;
                         const int r = p - seg * a.Kl;
                         if (r < s_cnt[seg]) {
-                            vals[j] = load_dev(&src[p]);
+                            vals[j] = load_dev(&base[p]);
                             dsts[j] = s_off[seg] + r;
                         }
                     }

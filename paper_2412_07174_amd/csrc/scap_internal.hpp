@@ -74,10 +74,10 @@ struct GemvArgs {
     // Fused SwiGLU block (Alg. 2).  The gate|up launch leaves the gated product z, centred and thresholded,
     // as one compacted list per 64 channels; the down launch takes those lists as its input.
     float m2, tau2;   // mode estimate and threshold of the gated product
-    float* z_out;     // optional fp32 [F]: the gated product itself
-    int32_t* zl_idx;  // [ceil(F/64)][64] kept channels of each 64-channel segment, ascending from the segment start
-    float* zl_d;      // [ceil(F/64)][64] their centred values
-    int32_t* zl_cnt;  // [ceil(F/64)] entries per segment
+    float* z_out;     // optional fp32 [B][F]: the gated product itself
+    int32_t* zl_idx;  // [ceil(F/64)][64] channels of each 64-channel segment kept by any token, ascending
+    float* zl_d;      // [ceil(F/64)][64][BT] their centred values per token (BT = B rounded up to 1, 2 or 4)
+    int32_t* zl_cnt;  // [1 + BT][ceil(F/64)] entries per segment: union first, then per token
     int F;            // channels of the gated product (half the columns of the gate|up launch)
 };
 
@@ -86,6 +86,7 @@ int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStrea
 
 // Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
 // `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.
+constexpr int kBlockMaxTokens = 4;  // tokens per fused-block call (the vector kernel's range)
 int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
 
 // Interleave two [rows, F] arrays of `elem_bytes`-byte elements in groups of 4 columns: out[rows, 2F].

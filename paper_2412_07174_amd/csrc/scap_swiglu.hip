@@ -16,50 +16,58 @@ constexpr int kBlockWaves = 8;
 constexpr int kBlockUnroll = 8;
 constexpr int kMaxListRows = 4096;  // input channels of one down workgroup: 64 segments of 64
 
-template <int WDT>
+template <int WDT, int BT>
 __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_up_kernel(const GemvArgs a) {
-    gemv_body<WDT, kBlockWaves, kBlockUnroll, 1, kWave, kFuseSwiglu>(a);
+    gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, kWave, kFuseSwiglu>(a);
 }
 
-template <int WDT>
+template <int WDT, int BT>
 __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_down_kernel(const GemvArgs a) {
-    gemv_body<WDT, kBlockWaves, kBlockUnroll, 1, kWave, kFuseList>(a);
+    gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, kWave, kFuseList>(a);
 }
 
-template <int WDT>
+template <int WDT, int BT>
 static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
     constexpr int TILE = kWave * Vec<WDT>::kElems;
     constexpr int NT = kBlockWaves * kWave;
     constexpr size_t RED = (size_t)(kBlockWaves * TILE > NT * 4 ? kBlockWaves * TILE : NT * 4);
 
-    int rc = plan_splits(up, TILE, 1, 0, false);
+    int rc = plan_splits(up, TILE, BT, 0, false);
     if (rc != SCAP_OK) return rc;
     up.Kl = up.Kc;
     up.Sl = up.S;
-    const size_t lds_up = lds_bytes(up.Kc, 1, (RED + TILE) * 4);
+    const size_t lds_up = lds_bytes(up.Kc, BT, (RED + (size_t)BT * TILE) * 4);
 
-    rc = plan_splits(dn, TILE, 1, 0, false);
-    if (rc == SCAP_OK && dn.Kc > kMaxListRows) rc = plan_splits(dn, TILE, 1, kMaxListRows, false);
+    rc = plan_splits(dn, TILE, BT, 0, false);
+    if (rc == SCAP_OK && dn.Kc > kMaxListRows) rc = plan_splits(dn, TILE, BT, kMaxListRows, false);
     if (rc != SCAP_OK) return rc;
     if (dn.Kc > kMaxListRows || dn.Kc % kWave != 0) return SCAP_ERR_SHAPE;
     dn.Kl = kWave;
     dn.Sl = (dn.K + kWave - 1) / kWave;
-    size_t lds_dn = lds_bytes(dn.Kc, 1, RED * 4);
-    const size_t tables = kHdrBytes + (size_t)dn.Sl * 8;  // offsets and counts of every segment (tile 0's last arrival)
+    size_t lds_dn = lds_bytes(dn.Kc, BT, RED * 4);
+    const size_t tables = kHdrBytes + (size_t)dn.Sl * 4;  // offsets of every segment (tile 0's last arrival)
     if (lds_dn < tables) lds_dn = tables;
     if (lds_up > 64 * 1024 || lds_dn > 64 * 1024) return SCAP_ERR_SHAPE;
 
-    hipLaunchKernelGGL((swiglu_up_kernel<WDT>), dim3((unsigned)(up.S * up.T)), dim3(NT), lds_up, stream, up);
+    hipLaunchKernelGGL((swiglu_up_kernel<WDT, BT>), dim3((unsigned)(up.S * up.T)), dim3(NT), lds_up, stream, up);
     if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
-    hipLaunchKernelGGL((swiglu_down_kernel<WDT>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn, stream, dn);
+    hipLaunchKernelGGL((swiglu_down_kernel<WDT, BT>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn, stream, dn);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
+}
+
+template <int WDT>
+static int launch_block_wdt(const GemvArgs& up, const GemvArgs& down, hipStream_t stream) {
+    if (up.B == 1) return launch_block<WDT, 1>(up, down, stream);
+    if (up.B == 2) return launch_block<WDT, 2>(up, down, stream);
+    if (up.B <= kBlockMaxTokens) return launch_block<WDT, 4>(up, down, stream);
+    return SCAP_ERR_UNIMPL;
 }
 
 int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream) {
     switch (wdt) {
-        case kF16: return launch_block<kF16>(up, down, stream);
-        case kBF16: return launch_block<kBF16>(up, down, stream);
-        case kI8: return launch_block<kI8>(up, down, stream);
+        case kF16: return launch_block_wdt<kF16>(up, down, stream);
+        case kBF16: return launch_block_wdt<kBF16>(up, down, stream);
+        case kI8: return launch_block_wdt<kI8>(up, down, stream);
     }
     return SCAP_ERR_DTYPE;
 }

@@ -44,7 +44,7 @@ def weights_of(dt, K, N, seed, std):
 
 
 class Block:
-    def __init__(self, K, F, N, dt, seed, std=0.05):
+    def __init__(self, K, F, N, dt, seed, std=0.05, B=1):
         self.K, self.F, self.N, self.dt = K, F, N, dt
         (self.Wg, self.sg), (self.Wu, self.su) = weights_of(dt, K, F, seed, std), weights_of(dt, K, F, seed + 1, std)
         self.Wd, self.sd = weights_of(dt, F, N, seed + 2, std)
@@ -52,7 +52,7 @@ class Block:
         self.gu_scale = None if dt != I8 else scap.pack_gate_up(to_dev(self.sg, F16), to_dev(self.su, F16))
         self.W_down = to_dev(self.Wd, dt)
         self.down_scale = None if dt != I8 else to_dev(self.sd, F16)
-        self.ws = scap.Workspace(K, N, 1, F=F)
+        self.ws = scap.Workspace(K, N, B, F=F)
         torch.cuda.synchronize()
         assert np.array_equal(self.W_gu.cpu().view(torch.int8 if dt == I8 else torch.int16).numpy()
                               .view(np.int8 if dt == I8 else np.uint16), pack_host(self.Wg, self.Wu))
@@ -82,11 +82,38 @@ class Block:
             out["idx_z"] = idx.cpu().numpy()[:n].copy()
         return out
 
+    def run_batch(self, X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd):
+        B = X_bits.shape[0]
+        b_gu = None if bg is None else scap.pack_gate_up(f32_dev(bg), f32_dev(bu))
+        z = torch.full((B, self.F), float("nan"), dtype=torch.float32, device="cuda")
+        idx = torch.full((B, self.F), -7, dtype=torch.int32, device="cuda")
+        nnz = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+        y = torch.full((B, self.N), float("nan"), dtype=torch.float32, device="cuda")
+        scap.swiglu_block(self.W_gu, self.W_down, to_dev(X_bits, xdt), m_x, tau_x, b_gu, m_z, tau_z, f32_dev(bd),
+                          gu_scale=self.gu_scale, down_scale=self.down_scale, y=y, z_out=z, idx_z_out=idx,
+                          nnz_z_out=nnz, workspace=self.ws)
+        torch.cuda.synchronize()
+        nn, ih, zh, yh = nnz.cpu().numpy(), idx.cpu().numpy(), z.cpu().numpy(), y.cpu().numpy()
+        assert np.all((nn >= 0) & (nn <= self.F))
+        return [{"y": yh[b], "z": zh[b], "idx_z": ih[b, :nn[b]].copy()} for b in range(B)]
+
+    def check_batch(self, X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what):
+        """Each token of a batch against the oracle's one-token block (tokens are independent: own masks)."""
+        gots = self.run_batch(X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd)
+        for b, got in enumerate(gots):
+            want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, X_bits[b], m_x, tau_x, m_z, tau_z, self.dt, xdt,
+                                       b_gate=bg, b_up=bu, b_down=bd, gate_scale=self.sg, up_scale=self.su,
+                                       down_scale=self.sd, nthreads=8)
+            self.compare(got, want, m_z, tau_z, f"{what} token {b}")
+
     def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what):
         want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, x_bits, m_x, tau_x, m_z, tau_z, self.dt, xdt,
                                    b_gate=bg, b_up=bu, b_down=bd, gate_scale=self.sg, up_scale=self.su,
                                    down_scale=self.sd, nthreads=8)
         got = self.run(x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd)
+        return got, want, self.compare(got, want, m_z, tau_z, what)
+
+    def compare(self, got, want, m_z, tau_z, what):
         zo = want["z"].astype(np.float64)
         fin = np.isfinite(zo)
         tol = 2e-5 + 2e-5 * np.abs(zo[fin])
@@ -112,7 +139,7 @@ class Block:
         if missing.size:
             y_want = y_want - d[missing].astype(np.float64) @ self.down_rows(missing)
         assert_y_close(got["y"], y_want, what)
-        return got, want, int(np.count_nonzero(diff))
+        return int(np.count_nonzero(diff))
 
 
 # ------------------------------------------------------------------ packing
@@ -174,6 +201,22 @@ def test_small_blocks_int8(K, F, N):
             blk.check(X[b], BF16, 0.0, tau_x, None, None, 0.0, tau_z, None, f"int8 K={K} F={F} N={N}")
 
 
+# ------------------------------------------------------------------ several tokens: own masks, union of rows
+@pytest.mark.parametrize("dt", [BF16, I8])
+@pytest.mark.parametrize("B", [2, 3, 4])
+def test_batched_blocks(B, dt):
+    K, F, N = 1000, 2056, 1040
+    blk = Block(K, F, N, dt, seed=840 + B, B=B)
+    X = wl.laplace(B, K, 850 + B, BF16, loc=0.1, scale=0.8)
+    rng = np.random.default_rng(860 + B)
+    bg, bu, bd = (rng.standard_normal(n).astype(np.float32) * 0.05 for n in (F, F, N))
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.1, 0.5, 0.0, 0.0, dt, BF16, b_gate=bg, b_up=bu,
+                                    gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd)["z"])
+    for tau_x, tau_z in ((0.0, 0.0), (0.5, float(np.median(zs))), (1.1, float(np.quantile(zs, 0.9))), (0.5, 1e9)):
+        say(f"batched block B={B} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
+        blk.check_batch(X, BF16, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"B={B} dt={dt} tau_z={tau_z}")
+
+
 # ------------------------------------------------------------------ degenerate cases
 def test_nothing_kept_and_everything_kept():
     K, F, N = 300, 520, 264
@@ -214,11 +257,12 @@ def test_block_is_bit_reproducible_and_workspace_is_reusable():
 def test_block_argument_errors():
     K, F, N = 64, 64, 16
     blk = Block(K, F, N, BF16, seed=920)
-    x = to_dev(wl.laplace(2, K, 921, BF16), BF16)
-    y = torch.empty((2, N), dtype=torch.float32, device="cuda")
+    x = to_dev(wl.laplace(5, K, 921, BF16), BF16)
+    y = torch.empty((5, N), dtype=torch.float32, device="cuda")
+    big = scap.Workspace(K, N, 5, F=F)
     with pytest.raises(scap.ScapError) as e:
-        scap.swiglu_block(blk.W_gu, blk.W_down, x, 0.0, 0.1, None, 0.0, 0.1, None, y=y, workspace=blk.ws)
-    assert e.value.status == -8      # two tokens: not implemented
+        scap.swiglu_block(blk.W_gu, blk.W_down, x, 0.0, 0.1, None, 0.0, 0.1, None, y=y, workspace=big)
+    assert e.value.status == -8      # five tokens: not implemented
     with pytest.raises(scap.ScapError) as e:
         scap.swiglu_block(blk.W_gu, blk.W_down, x[0], 0.0, -1.0, None, 0.0, 0.1, None, workspace=blk.ws)
     assert e.value.status == -5
