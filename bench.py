@@ -48,6 +48,7 @@ def run_suite(args, torch, scap, wl, dev):
     on the bytes actually needed.  Weights are random on the device (values do not matter for timing),
     inputs come from the seeded generators, thresholds from scap_calibrate.  Prints ONE JSON line."""
     steps = max(100, args.steps // 10)
+    steps_box = [steps]
 
     def dev16(bits, dt):
         t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
@@ -57,9 +58,10 @@ def run_suite(args, torch, scap, wl, dev):
         for i in range(10):
             fn(i)
         torch.cuda.synchronize()
+        n = steps_box[0]
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            for i in range(steps):
+            for i in range(n):
                 fn(i)
         g.replay()
         torch.cuda.synchronize()
@@ -68,7 +70,7 @@ def run_suite(args, torch, scap, wl, dev):
         g.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps * 1e3  # us
+        return e0.elapsed_time(e1) / n * 1e3  # us
 
     rows = []
 
@@ -196,6 +198,88 @@ def run_suite(args, torch, scap, wl, dev):
     run_block("mistral7b_ffn", 4096, 14336, 4096, (0.5, 0.7, 0.9))
     run_block("llama2_7b_ffn", 4096, 11008, 4096, (0.5,))
 
+    # Mixture-of-experts feed-forward (config 5): 8 int8 experts, top-2 routing from seeded logits, the tokens
+    # of a step grouped per expert; an expert's group goes through the fused block (up to 4 tokens) or through
+    # separate calls.  Routing is done beforehand on the host (it is not part of the library); gathering the
+    # group's tokens and the gate-weighted scatter-add are torch ops inside the timed region.
+    moe_rows = []
+
+    def run_moe():
+        K, F, N, E = 4096, 14336, 4096, 8
+        dt = torch.bfloat16
+        Wgu, sgu, Wdn, sdn = [], [], [], []
+        for e in range(E):
+            Wgu.append(torch.randint(-127, 128, (K, 2 * F), dtype=torch.int8, device=dev))
+            sgu.append((torch.rand(2 * F, device=dev) * 2e-4 + 1e-4).to(torch.float16))
+            Wdn.append(torch.randint(-127, 128, (F, N), dtype=torch.int8, device=dev))
+            sdn.append((torch.rand(N, device=dev) * 2e-4 + 1e-4).to(torch.float16))
+        site = wl.Site("moe_in", K, 2 * F, wl.I8, wl.BF16, "prenorm", 128, 5001, 5002, 5003)
+        X = dev16(site.draw(256, site.seed_test), wl.BF16)
+        calib = dev16(site.draw(128, site.seed_calib), wl.BF16)
+        ws = scap.Workspace(K, N, 8, F=F)
+        wsb = scap.Workspace(K, N, 4, F=F)
+        m_x, tau_x = scap.calibrate(calib, 0.4, scap.MODE_MEDIAN, workspace=ws)
+        bgu = [scap.fold_bias(Wgu[e], m_x, None, col_scale=sgu[e], workspace=ws) for e in range(E)]
+        ygu = torch.empty((8, 2 * F), dtype=torch.float32, device=dev)
+
+        def gate(yv):  # packed columns: groups of 4 gate, 4 up
+            v = yv.view(yv.shape[0], F // 4, 2, 4)
+            return (torch.nn.functional.silu(v[:, :, 0, :]) * v[:, :, 1, :]).reshape(yv.shape[0], F).to(dt)
+
+        zc = torch.empty((32, F), dtype=dt, device=dev)
+        for j in range(32):
+            scap.sparse_fc(Wgu[0], calib[j], m_x, tau_x, bgu[0], col_scale=sgu[0], y=ygu[:1], workspace=ws)
+            zc[j] = gate(ygu[:1])[0]
+        _, tau_z = scap.calibrate(zc, 0.7, scap.MODE_ZERO, workspace=ws)
+
+        for B in (1, 8):
+            nsteps = max(50, steps // 2)
+            order, gatew = wl.top2_route(wl.router_logits(B * nsteps, E, 5004 + B))
+            plans = []
+            for i in range(nsteps):
+                groups = []
+                for e in range(E):
+                    tok, slot = np.nonzero(order[i * B:(i + 1) * B] == e)
+                    if tok.size:
+                        groups.append((e, torch.from_numpy(tok + (i * B) % (256 - B)).to(dev),
+                                       torch.from_numpy(tok).to(dev),
+                                       torch.from_numpy(gatew[i * B + tok, slot].astype(np.float32)).to(dev)))
+                plans.append(groups)
+            out = torch.zeros((B, N), dtype=torch.float32, device=dev)
+            ybuf = torch.empty((8, N), dtype=torch.float32, device=dev)
+
+            def step(i, sparse, fused):
+                out.zero_()
+                for e, src, dst, gw in plans[i % nsteps]:
+                    n = src.numel()
+                    xg = X.index_select(0, src)
+                    y = ybuf[:n]
+                    if sparse and fused and n <= 4:
+                        scap.swiglu_block(Wgu[e], Wdn[e], xg, m_x, tau_x, bgu[e], 0.0, tau_z, None, gu_scale=sgu[e],
+                                          down_scale=sdn[e], y=y, workspace=wsb)
+                    elif sparse:
+                        scap.sparse_fc(Wgu[e], xg, m_x, tau_x, bgu[e], col_scale=sgu[e], y=ygu[:n], workspace=ws)
+                        scap.sparse_fc(Wdn[e], gate(ygu[:n]), 0.0, tau_z, None, col_scale=sdn[e], y=y, workspace=ws)
+                    else:
+                        scap.dense_fc(Wgu[e], xg, None, col_scale=sgu[e], y=ygu[:n], workspace=ws)
+                        scap.dense_fc(Wdn[e], gate(ygu[:n]), None, col_scale=sdn[e], y=y, workspace=ws)
+                    out.index_add_(0, dst, y * gw[:, None])
+
+            saved = steps_box[0]
+            steps_box[0] = nsteps
+            t_dense = timed(lambda i: step(i, False, False))
+            t_sep = timed(lambda i: step(i, True, False))
+            t_fused = timed(lambda i: step(i, True, True))
+            steps_box[0] = saved
+            active = float(np.mean([len(p) for p in plans]))
+            moe_rows.append({"tokens": B, "experts": E, "top_k": 2, "active_experts_per_step": round(active, 2),
+                             "target_x": 0.4, "target_z": 0.7, "dense_us": round(t_dense, 1),
+                             "sparse_separate_calls_us": round(t_sep, 1), "sparse_fused_blocks_us": round(t_fused, 1),
+                             "vs_dense": round(t_dense / t_fused, 3)})
+
+    run_moe()
+    torch.cuda.empty_cache()
+
     # Offline calibration at the paper's sample size (64 slices x 256 tokens per layer): wall time of the
     # synchronous call (one counting pass on the GPU, statistics on the host), median estimator + threshold.
     calib_rows = []
@@ -219,7 +303,7 @@ def run_suite(args, torch, scap, wl, dev):
     layer3 = [r for r in rows if r["cfg"] == 3]
     summary = {"mistral_layer_fc_set_dense_us": round(sum(r["us"] for r in layer3 if r["target"] is None), 2),
                "mistral_layer_fc_set_s50_us": round(sum(r["us"] for r in layer3 if r["target"] == 0.5), 2)}
-    print(json.dumps({"suite": rows, "blocks": blocks, "calibration": calib_rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
+    print(json.dumps({"suite": rows, "blocks": blocks, "moe": moe_rows, "calibration": calib_rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
                       "note": "GB/s = (rows read x N x sizeof(w) + x + bias + y) / time; density = union of the "
                               "batch's masks / K"}))
     return 0
