@@ -132,6 +132,10 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         if (lpr != 64 && lpr != 32) return SCAP_ERR_CONFIG;
     }
     const int elems = (wdt == kI8) ? 16 : 8;
+    // Few column tiles mean many K splits, and the tile's last arrival has to pull all their partial sums
+    // through one compute unit: with at most 4 full-width tiles (int8 weights and N = 4096, say) half-width
+    // tiles halve that (measured on 14336 x 4096 int8: 20.0 -> 18.4 us dense, 10.1 -> 8.1 us at 90 %).
+    if (!(cfg && cfg->lanes_per_row) && bt == 1 && (a.N + 64 * elems - 1) / (64 * elems) <= 4) lpr = 32;
     const int rc = plan_splits(a, lpr * elems, bt, kc, cfg && cfg->rows_per_group);
     if (rc != SCAP_OK) return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
     a.Kl = a.Kc;
