@@ -21,9 +21,9 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_up_kernel(const Gem
     gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, kWave, kFuseSwiglu>(a);
 }
 
-template <int WDT, int BT>
+template <int WDT, int BT, int LPR>
 __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_down_kernel(const GemvArgs a) {
-    gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, kWave, kFuseList>(a);
+    gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, LPR, kFuseList>(a);
 }
 
 template <int WDT, int BT>
@@ -38,8 +38,11 @@ static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
     up.Sl = up.S;
     const size_t lds_up = lds_bytes(up.Kc, BT, (RED + (size_t)BT * TILE) * 4);
 
-    rc = plan_splits(dn, TILE, BT, 0, false);
-    if (rc == SCAP_OK && dn.Kc > kMaxListRows) rc = plan_splits(dn, TILE, BT, kMaxListRows, false);
+    // one token and at most 4 full-width tiles of output: half-width tiles, as in the plain launch
+    const bool half = BT == 1 && (dn.N + TILE - 1) / TILE <= 4;
+    const int dn_tile = half ? TILE / 2 : TILE;
+    rc = plan_splits(dn, dn_tile, BT, 0, false);
+    if (rc == SCAP_OK && dn.Kc > kMaxListRows) rc = plan_splits(dn, dn_tile, BT, kMaxListRows, false);
     if (rc != SCAP_OK) return rc;
     if (dn.Kc > kMaxListRows || dn.Kc % kWave != 0) return SCAP_ERR_SHAPE;
     dn.Kl = kWave;
@@ -51,7 +54,14 @@ static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
 
     hipLaunchKernelGGL((swiglu_up_kernel<WDT, BT>), dim3((unsigned)(up.S * up.T)), dim3(NT), lds_up, stream, up);
     if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
-    hipLaunchKernelGGL((swiglu_down_kernel<WDT, BT>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn, stream, dn);
+    if constexpr (BT == 1) {
+        if (half) {
+            hipLaunchKernelGGL((swiglu_down_kernel<WDT, 1, kWave / 2>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn,
+                               stream, dn);
+            return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
+        }
+    }
+    hipLaunchKernelGGL((swiglu_down_kernel<WDT, BT, kWave>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn, stream, dn);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
