@@ -406,3 +406,47 @@ def test_calibrate_every_code_pattern(dt):
             got = scap.calibrate(Xd, s, oracle.EST[est], workspace=ws)
             want = oracle.calibrate(X, dt, s, oracle.EST[est])
             assert got == want, f"{est} s={s}: {got} vs {want}"
+
+
+def test_hip_graph_replays_match_eager_launches():
+    """bench.py times launches replayed from a HIP graph: every replay must give what the eager launch gives.
+    One-token kernel, the two-launch matrix-core path and the two-launch SwiGLU block, replayed several times with
+    eager work and synchronisation in between, on inputs that change between replays."""
+    K, F, N = 1500, 2056, 1032
+    W = to_dev(wl.weights(K, N, 971, BF16), BF16)
+    Wg, Wu, Wd = (to_dev(wl.weights(K, F, 972, BF16), BF16), to_dev(wl.weights(K, F, 973, BF16), BF16),
+                  to_dev(wl.weights(F, N, 974, BF16), BF16))
+    W_gu = scap.pack_gate_up(Wg, Wu)
+    ws = scap.Workspace(K, N, 8, F=F)
+    X = to_dev(wl.laplace(8, K, 975, BF16, loc=0.0, scale=1.0), BF16)
+    x1 = X[0].clone()
+    xb = X.clone()
+    y1 = torch.zeros((1, N), dtype=torch.float32, device="cuda")
+    y8 = torch.zeros((8, N), dtype=torch.float32, device="cuda")
+    yb = torch.zeros((1, N), dtype=torch.float32, device="cuda")
+    nnz = torch.zeros(8, dtype=torch.int32, device="cuda")
+
+    def work():
+        scap.sparse_fc(W, x1, 0.0, 0.5, None, y=y1, workspace=ws)
+        scap.sparse_fc(W, xb, 0.0, 0.5, None, y=y8, nnz_out=nnz, workspace=ws)        # 8 tokens: matrix cores
+        scap.swiglu_block(W_gu, Wd, x1, 0.0, 0.5, None, 0.0, 0.02, None, y=yb, workspace=ws)
+
+    work()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        work()
+    for rep in range(4):
+        say(f"graph replay {rep}")
+        x1.copy_(X[(rep + 1) % 8])
+        xb.copy_(torch.roll(X, rep + 1, dims=0))
+        work()
+        torch.cuda.synchronize()
+        want = (y1.clone(), y8.clone(), yb.clone(), nnz.clone())
+        for t in (y1, y8, yb, nnz):
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, (y1, y8, yb, nnz)):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager launch"
