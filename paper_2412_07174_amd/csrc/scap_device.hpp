@@ -24,6 +24,19 @@ __device__ __forceinline__ float act_to_f32(const uint16_t* __restrict__ x, int6
     return xdt == kBF16 ? bf16_bits_to_f32(b) : f16_bits_to_f32(b);
 }
 
+// 16 bytes of weights through a global pointer, marked non-temporal: every weight byte is used exactly once
+// per call, and streaming loads that do not claim cache lines read HBM about 15 % faster than plain ones
+// (6.1 against 5.3 TB/s in a pure read sweep on this part).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const u32x4_t global_u32x4_t;
+__device__ __forceinline__ uint4 load_weights16(global_u32x4_t* p) {
+    const u32x4_t v = __builtin_nontemporal_load(p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 load_weights16(const void* p) {
+    return load_weights16((global_u32x4_t*)(uint64_t)p);
+}
+
 // number of weight elements in one 16-byte load
 template <int WDT> struct Vec { static constexpr int kElems = (WDT == kI8) ? 16 : 8; static constexpr int kBytes = (WDT == kI8) ? 1 : 2; };
 

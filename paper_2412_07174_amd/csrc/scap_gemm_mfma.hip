@@ -252,7 +252,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
                 st.r[u][j] = make_uint4(0u, 0u, 0u, 0u);
                 dj[j] = 0.f;
                 if (j < I.nv[u]) {
-                    st.r[u][j] = *reinterpret_cast<const uint4*>(wbase + (uint64_t)(uint32_t)rows[j] * row_bytes + lane_off);
+                    st.r[u][j] = load_weights16(wbase + (uint64_t)(uint32_t)rows[j] * row_bytes + lane_off);
                     dj[j] = I.dp[u][j * BT];  // 16 lanes read 64 contiguous bytes of one list entry
                 }
             }

@@ -172,22 +172,23 @@ int launch_workspace_init(void* workspace, size_t bytes, hipStream_t stream) {
     return launch_fill_words(static_cast<uint32_t*>(workspace), head / 4, 0u, stream);
 }
 
-// Streaming read of `nvec` 16-byte vectors; a per-workgroup checksum keeps the loads alive.
+// Streaming read of `nvec` 16-byte vectors with the same non-temporal loads the GEMV uses for weights (the
+// fastest way found to read HBM on this part); a per-workgroup checksum keeps the loads alive.
 constexpr int kProbeGroups = 2048;
 __global__ __launch_bounds__(512) void read_probe_kernel(const uint4* __restrict__ src, size_t nvec, uint32_t* out) {
     __shared__ uint32_t sh[8];
     uint32_t acc = 0;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
-        acc += v0.x ^ v0.y ^ v0.z ^ v0.w;
-        acc += v1.x ^ v1.y ^ v1.z ^ v1.w;
-        acc += v2.x ^ v2.y ^ v2.z ^ v2.w;
-        acc += v3.x ^ v3.y ^ v3.z ^ v3.w;
+    for (; i + 7 * stride < nvec; i += 8 * stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = load_weights16(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     for (; i < nvec; i += stride) {
-        const uint4 v = src[i];
+        const uint4 v = load_weights16(src + i);
         acc += v.x ^ v.y ^ v.z ^ v.w;
     }
     acc = (uint32_t)wave_sum((int)acc);

@@ -14,11 +14,8 @@ __device__ __forceinline__ uint4 load_row_vec(const char* __restrict__ wbase, ui
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base >> 32));
     typedef __attribute__((address_space(1))) const char gchar_t;
-    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    typedef __attribute__((address_space(1))) const u32x4_t gvec_t;
     gchar_t* p = (gchar_t*)(((uint64_t)hi << 32) | lo);
-    const u32x4_t v = *(gvec_t*)(p + lane_off);
-    return make_uint4(v.x, v.y, v.z, v.w);
+    return load_weights16((global_u32x4_t*)(p + lane_off));
 }
 
 // LPR = lanes that share one weight row: 64 (a wavefront reads 1 KB of one row per load) or 32 (it reads
@@ -127,7 +124,7 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& a) {
                 for (int b = 0; b < BT; ++b) dv[q][b] = 0.f;
                 if (ok[q]) {
                     const uint32_t row = (uint32_t)s_idx[e];
-                    r[q] = *reinterpret_cast<const uint4*>(wbase + (uint64_t)row * row_bytes + lane_off);
+                    r[q] = load_weights16(wbase + (uint64_t)row * row_bytes + lane_off);
 #pragma unroll
                     for (int b = 0; b < BT; ++b) dv[q][b] = s_d[b * a.Kc + e];
                 }
