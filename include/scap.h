@@ -21,7 +21,9 @@
  *     enqueued; on an error nothing is launched and no output is written.  No call throws, aborts
  *     or prints.
  *   - Device pointers of W, x, y, bias, col_scale and the workspace must be 16-byte aligned.  N must
- *     be a multiple of 8 (16-bit weights) or 16 (int8 weights).
+ *     be a multiple of 8 (16-bit weights) or 16 (int8 weights).  A layer has at most 2^20 input channels
+ *     and 2^19 output columns (SCAP_ERR_SHAPE beyond; scap_calibrate pools up to 2^34 values of rows up to
+ *     2^24 wide).  An explicit launch shape that cannot hold such a layer is SCAP_ERR_CONFIG.
  *   - A workspace is a caller-allocated device buffer of at least scap_workspace_bytes(...) bytes
  *     that has been passed once to scap_workspace_init().  Kernels leave it ready for the next
  *     call.  Two calls that share one workspace must not overlap in time (use one workspace per

@@ -7,6 +7,9 @@ using namespace scap;
 
 namespace {
 
+constexpr int64_t kMaxK = (int64_t)1 << 20;  // input channels of a layer
+constexpr int64_t kMaxN = (int64_t)1 << 19;  // output columns of a layer
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 bool weight_dtype_ok(int wdt) { return wdt == SCAP_F16 || wdt == SCAP_BF16 || wdt == SCAP_I8_COLSCALE; }
@@ -16,7 +19,7 @@ int check_layer(const void* W, const void* col_scale, int64_t K, int64_t N, int 
     if (!W) return SCAP_ERR_NULL;
     if (!weight_dtype_ok(wdt)) return SCAP_ERR_DTYPE;
     if (wdt == SCAP_I8_COLSCALE && !col_scale) return SCAP_ERR_NULL;
-    if (K < 1 || N < 1 || K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19)) return SCAP_ERR_SHAPE;
+    if (K < 1 || N < 1 || K > kMaxK || N > kMaxN) return SCAP_ERR_SHAPE;
     const int64_t vec = (wdt == SCAP_I8_COLSCALE) ? 16 : 8;
     if (N % vec != 0) return SCAP_ERR_SHAPE;
     if (!aligned16(W) || (col_scale && !aligned16(col_scale))) return SCAP_ERR_ALIGN;
@@ -121,7 +124,7 @@ int scap_version(void) { return 100; }
 size_t scap_workspace_bytes(int64_t K, int64_t N, int64_t B) {
     if (K < 1 || N < 0 || B < 1) return 0;
     if (N == 0) return kCalibBytes;  // calibration only: fixed header + the code histogram
-    if (K > ((int64_t)1 << 24) || N > ((int64_t)1 << 19) || B > SCAP_MAX_TOKENS) return 0;
+    if (K > kMaxK || N > kMaxN || B > SCAP_MAX_TOKENS) return 0;
     return union_list_offset(N, B) + (B >= kMfmaMinTokens ? union_list_entries(K) * 68 : 0);
 }
 
@@ -185,7 +188,7 @@ int scap_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F,
 
 size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B) {
     if (K < 1 || F < 1 || N < 1 || B < 1 || B > SCAP_MAX_TOKENS) return 0;
-    if (K > ((int64_t)1 << 24) || F > kMaxGated || N > ((int64_t)1 << 19)) return 0;
+    if (K > kMaxK || F > kMaxGated || N > kMaxN) return 0;
     const size_t segs = (size_t)((F + 63) / 64);
     const size_t bt = B <= 1 ? 1 : (B == 2 ? 2 : 4);  // larger batches are refused by the block itself
     size_t bytes = block_list_offset(F, N, B) + segs * 64 * 4 * (1 + bt) + align_up(segs * 4 * (1 + bt), 256);

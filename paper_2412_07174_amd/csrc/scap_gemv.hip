@@ -120,7 +120,12 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     const int lanes = cfg ? cfg->lanes_per_row : 0;
     const bool mfma_ok = a.B >= kMfmaMinTokens && (wdt == kBF16 || wdt == kI8) && a.mode != kModeFold;
     if (lanes == 16 && !mfma_ok) return SCAP_ERR_CONFIG;
-    if (mfma_ok && (lanes == 16 || (lanes == 0 && a.B >= kMfmaAutoTokens))) return launch_gemm_mfma(a, wdt, cfg, stream);
+    if (mfma_ok && (lanes == 16 || (lanes == 0 && a.B >= kMfmaAutoTokens))) {
+        const int rc = launch_gemm_mfma(a, wdt, cfg, stream);
+        // chosen by default and the layer has more 128-column tiles than there are arrival counters: the
+        // vector kernel's tiles are four times wider
+        if (!(rc == SCAP_ERR_SHAPE && lanes == 0)) return rc;
+    }
 
     int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0, lpr = 64;
     if (cfg) {
@@ -137,7 +142,13 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     // tiles halve that (measured on 14336 x 4096 int8: 20.0 -> 18.4 us dense, 10.1 -> 8.1 us at 90 %).
     if (!(cfg && cfg->lanes_per_row) && bt == 1 && (a.N + 64 * elems - 1) / (64 * elems) <= 4) lpr = 32;
     const int rc = plan_splits(a, lpr * elems, bt, kc, cfg && cfg->rows_per_group);
-    if (rc != SCAP_OK) return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
+    if (rc != SCAP_OK) {
+        // a batch's kept-channel list of a very long input does not fit the vector kernel's LDS; the
+        // matrix-core path keeps its lists in the workspace
+        if (rc == SCAP_ERR_SHAPE && mfma_ok && lanes == 0 && !(cfg && cfg->rows_per_group))
+            return launch_gemm_mfma(a_in, wdt, cfg, stream);
+        return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
+    }
     a.Kl = a.Kc;
     a.Sl = a.S;
 

@@ -450,3 +450,17 @@ def test_hip_graph_replays_match_eager_launches():
         torch.cuda.synchronize()
         for a, b in zip(want, (y1, y8, yb, nnz)):
             assert torch.equal(a, b), f"replay {rep} differs from the eager launch"
+
+
+@pytest.mark.parametrize("K,N,B", [(1 << 20, 8, 1), (1 << 20, 16, 3), (64, 1 << 19, 1), (72, 1 << 19, 16), (1 << 20, 136, 8)])
+def test_maximum_sizes(K, N, B):
+    """The largest layer dimensions the library accepts: 2^20 input channels, 2^19 output columns (the 16-token case
+    has more 128-column tiles than the matrix-core path has counters and falls back to the vector kernel)."""
+    W = wl.weights(K, N, 981, BF16)
+    layer = Layer(W, BF16, B=16)
+    X = wl.swiglu(B, K, 982, BF16)
+    bf = np.random.default_rng(983).standard_normal(N).astype(np.float32)
+    for tau in (0.0, 0.3):
+        say(f"maximum sizes K={K} N={N} B={B} tau={tau}")
+        check_against_oracle(layer, X, BF16, 0.0, tau, bf, what=f"max K={K} N={N} B={B} tau={tau}")
+    assert scap.workspace_bytes((1 << 20) + 64, 8, 1) == 0 and scap.workspace_bytes(64, (1 << 19) + 8, 1) == 0
