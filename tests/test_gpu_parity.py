@@ -464,3 +464,28 @@ def test_maximum_sizes(K, N, B):
         say(f"maximum sizes K={K} N={N} B={B} tau={tau}")
         check_against_oracle(layer, X, BF16, 0.0, tau, bf, what=f"max K={K} N={N} B={B} tau={tau}")
     assert scap.workspace_bytes((1 << 20) + 64, 8, 1) == 0 and scap.workspace_bytes(64, (1 << 19) + 8, 1) == 0
+
+
+def test_two_streams_with_their_own_workspaces():
+    """Calls that overlap in time are allowed when each stream has its own workspace: results equal the
+    one-after-the-other results bit for bit."""
+    K, N = 4096, 4096
+    W = to_dev(wl.weights(K, N, 991, BF16), BF16)
+    X = to_dev(wl.swiglu(32, K, 992, BF16), BF16)
+    ws = [scap.Workspace(K, N, 8), scap.Workspace(K, N, 8)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ref1 = [scap.sparse_fc(W, X[i], 0.0, 0.2, None, workspace=ws[0]).clone() for i in range(16)]
+    ref8 = [scap.sparse_fc(W, X[i:i + 8], 0.0, 0.2, None, workspace=ws[0]).clone() for i in range(16)]
+    torch.cuda.synchronize()
+    out1 = [torch.empty((1, N), dtype=torch.float32, device="cuda") for _ in range(16)]
+    out8 = [torch.empty((8, N), dtype=torch.float32, device="cuda") for _ in range(16)]
+    for rep in range(3):
+        say(f"two streams rep {rep}")
+        for i in range(16):
+            with torch.cuda.stream(streams[0]):
+                scap.sparse_fc(W, X[i], 0.0, 0.2, None, y=out1[i], workspace=ws[0], stream=streams[0])
+            with torch.cuda.stream(streams[1]):
+                scap.sparse_fc(W, X[i:i + 8], 0.0, 0.2, None, y=out8[i], workspace=ws[1], stream=streams[1])
+        torch.cuda.synchronize()
+        for i in range(16):
+            assert torch.equal(out1[i], ref1[i]) and torch.equal(out8[i], ref8[i]), f"rep {rep} call {i}"
