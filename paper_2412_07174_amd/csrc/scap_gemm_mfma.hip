@@ -11,8 +11,11 @@
 // when the caller wants them).  Doing this inside every (split, column tile) workgroup, as the one-token
 // kernel does, repeats 16 tokens' worth of work per tile and took longer than the GEMM itself.
 // `gemm_mfma_kernel` (split, tile of 128 columns) then streams the listed rows; the centred values come
-// from the list, 16 tokens of an entry side by side, so that the 16 lanes of a row group read 64 contiguous
-// bytes (gathering them from x instead touches one cache line per token and row and throttles the kernel).
+// from the list, stored per 16-entry block exactly as the MFMA wants them: lane l of a block finds its A
+// operand (bf16 heads and tails of token l%16 at entries 4*(l/16)+0..3) in 16 contiguous bytes, a wavefront
+// reads 1 KB in one instruction (gathering from x instead touches one cache line per token and row, and
+// per-value loads from a plain [entry][token] array cost four instructions per block; both throttled the
+// weight stream).
 //
 // Operand layout without any transposition.  For this instruction lane l holds
 //     A[m = l%16][k = 4*(l/16) + j],   B[k = 4*(l/16) + j][n = l%16],   C[m = 4*(l/16) + i][n = l%16],  i,j = 0..3.
@@ -65,7 +68,8 @@ __device__ __forceinline__ void split_bf16x4(const float4& d, s16x4_t& hi, s16x4
 // scan over the wavefronts.  Segments are short (512 channels unless K is huge) so that the whole input is
 // handled in one round of loads by many workgroups.
 //   u_idx[seg*Kl ...]        ascending channels kept by at least one token
-//   u_d[(seg*Kl + e)*16 + b] centred value of token b at list entry e (0 where token b pruned it)
+//   u_d as [block of 16 entries][lane 0..63][4 bf16 heads, 4 bf16 tails]: lane = 16*(entry%16/4) + token,
+//                            value j = entry%4; 0 where the token pruned the channel or the list has ended
 //   seg_cnt[B*Sl + seg]      their number;   seg_cnt[b*Sl + seg], idx_out: per-token lists on request
 __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(const GemvArgs a) {
     constexpr int BT = kMfmaTokens;
@@ -80,7 +84,9 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
     const bool per_token = a.nnz_out != nullptr || a.idx_out != nullptr;
     const bool want_idx = a.idx_out != nullptr;
     int32_t* __restrict__ out = a.u_idx + (int64_t)seg * a.Kl;
-    float* __restrict__ out_d = a.u_d + (int64_t)seg * a.Kl * BT;
+    // operand blocks of this segment: (Kl / 16) blocks of 64 lanes x 16 bytes
+    uint4* __restrict__ out_a = reinterpret_cast<uint4*>(a.u_d) + (int64_t)seg * (a.Kl / kMfmaBlock) * kWave;
+    __shared__ float s_val[NT][BT + 1];  // centred values of the entries placed in this pass (+1: no bank conflicts)
 
     int run_u = 0;
     int run_t[BT];
@@ -121,12 +127,46 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
             if (i < w) below += v;
             total += v;
         }
+        // This pass places entries [run_u, run_u + total) of the segment's list.  Their values go through
+        // LDS so that whole operand blocks can be written; a block that straddles two passes is completed
+        // by the later one, which re-reads the earlier entries' values from the block itself.
+        const int first_blk = run_u / kMfmaBlock;
+        const int carry = run_u - first_blk * kMfmaBlock;  // entries of the first block placed by earlier passes
         if (any) {
             const int pos = run_u + below + lanes_below(ub);
             out[pos] = k;
-            float4* dst = reinterpret_cast<float4*>(out_d + (int64_t)pos * BT);
 #pragma unroll
-            for (int q = 0; q < BT / 4; ++q) dst[q] = make_float4(dm[4 * q], dm[4 * q + 1], dm[4 * q + 2], dm[4 * q + 3]);
+            for (int b = 0; b < BT; ++b) s_val[pos - run_u][b] = dm[b];
+        }
+        __syncthreads();
+        const int n_items = ((carry + total + kMfmaBlock - 1) / kMfmaBlock) * kWave;  // (block, lane) pairs
+        for (int it = tid; it < n_items; it += NT) {
+            const int blk = first_blk + it / kWave;
+            const int l = it % kWave;
+            const int tok = l & 15, kg = l >> 4;
+            uint4 prev = make_uint4(0u, 0u, 0u, 0u);
+            if (carry != 0 && it < kWave) prev = out_a[(int64_t)blk * kWave + l];
+            float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
+            float* dv = &d.x;
+            bool from_prev[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = (it / kWave) * kMfmaBlock + 4 * kg + j - carry;  // index into this pass's entries
+                from_prev[j] = e < 0;
+                if (e >= 0 && e < total) dv[j] = s_val[e][tok];
+            }
+            s16x4_t hi, lo;
+            split_bf16x4(d, hi, lo);
+            union { uint4 q; short h[8]; } pk;
+            pk.q = prev;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (!from_prev[j]) {
+                    pk.h[j] = hi[j];
+                    pk.h[4 + j] = lo[j];
+                }
+            }
+            out_a[(int64_t)blk * kWave + l] = pk.q;
         }
         run_u += total;
         if (per_token) {
@@ -162,12 +202,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     constexpr int BT = kMfmaTokens;
     constexpr int ELEMS = Vec<WDT>::kElems;  // columns in a lane's 16-byte load = MFMAs per block
     constexpr int TILE = 16 * ELEMS;
-    constexpr int NT = WAVES * kWave;
-    constexpr int GROUPS = TILE / 4;
 
     extern __shared__ uint4 smem_raw[];
     const Lds L = carve_lds<WAVES, BT>(reinterpret_cast<char*>(smem_raw), 0);
-    float* s_red = L.red;  // [WAVES][4 token groups][TILE]
+    float* s_red = L.red;  // tree reduction buffer, then the final reduction's
 
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
@@ -196,8 +234,6 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     __syncthreads();
     const int n_blocks = uniform(s_pre[nseg]);
 
-    const int tok = lane & 15;  // token whose centred values this lane supplies (A index m)
-
     const int cg = lane & 15;   // column group: columns ELEMS*cg .. +ELEMS-1 of the tile (B/C index n)
     const int kg = lane >> 4;   // row group: list rows 4*kg .. 4*kg+3 of a block (k of A and B); token group of C
     const int col0 = tile * TILE + cg * ELEMS;
@@ -210,20 +246,22 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     for (int e = 0; e < ELEMS; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // Block blk (wave-uniform) -> its four list entries for this lane's row group: the int4 of channel
-    // indices and how many of them are valid (0..4).  Blocks past the end give 0 valid entries.
-    auto fetch = [&](int blk, int4& rows, const float*& dptr) -> int {
+    // indices, how many of them are valid (0..4), and where this lane's A operand of the block lies.
+    // Blocks past the end give 0 valid entries.
+    const uint4* const a_base = reinterpret_cast<const uint4*>(a.u_d);
+    auto fetch = [&](int blk, int4& rows, const uint4*& aptr) -> int {
         rows = make_int4(0, 0, 0, 0);
-        dptr = a.u_d;
-        if (blk >= n_blocks) return 0;
+        aptr = a_base + lane;  // any readable address; nothing is loaded through it (see issue())
+        if (blk >= n_blocks) return -1;
         int i = 0;
         while (i + 1 < nseg && s_pre[i + 1] <= blk) ++i;  // nseg is small
         i = uniform(i);
         const int local = blk - s_pre[i];
+        aptr = a_base + ((int64_t)(seg0 + i) * (a.Kl / kMfmaBlock) + local) * kWave + lane;
         const int left = s_segcnt[i] - local * kMfmaBlock - 4 * kg;  // entries from this lane's first one on
         if (left <= 0) return 0;
         const int64_t e = (int64_t)(seg0 + i) * a.Kl + local * kMfmaBlock + 4 * kg;  // this lane's first entry
         rows = *reinterpret_cast<const int4*>(a.u_idx + e);
-        dptr = a.u_d + e * BT + tok;
         return left < 4 ? left : 4;
     };
 
@@ -232,38 +270,45 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     struct IdxSet {
         int4 ix[UB];
         int nv[UB];
-        const float* dp[UB];
+        const uint4* ap[UB];
     };
     struct Stage {
         uint4 r[UB][4];
-        float4 dv[UB];
+        uint4 av[UB];  // A operand: 4 bf16 heads, 4 bf16 tails
     };
     auto fetch_set = [&](int it, IdxSet& I) {
 #pragma unroll
-        for (int u = 0; u < UB; ++u) I.nv[u] = fetch(w + (it * UB + u) * WAVES, I.ix[u], I.dp[u]);
+        for (int u = 0; u < UB; ++u) I.nv[u] = fetch(w + (it * UB + u) * WAVES, I.ix[u], I.ap[u]);
     };
     auto issue = [&](const IdxSet& I, Stage& st) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             const int rows[4] = {I.ix[u].x, I.ix[u].y, I.ix[u].z, I.ix[u].w};
-            float dj[4];
+            // one 1 KB read per wavefront and block, issued without a branch; past the end of the list the
+            // value read is replaced by zeros
+            const uint4 av = *I.ap[u];
+            const bool live = I.nv[u] >= 0;
+            st.av[u] = make_uint4(live ? av.x : 0u, live ? av.y : 0u, live ? av.z : 0u, live ? av.w : 0u);
+            // The row loads carry no branch either: a slot past the end of the list reads row 0 (a handful
+            // of extra 256-byte reads per list segment) and is zeroed afterwards.
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                st.r[u][j] = make_uint4(0u, 0u, 0u, 0u);
-                dj[j] = 0.f;
-                if (j < I.nv[u]) {
-                    st.r[u][j] = load_weights16(wbase + (uint64_t)(uint32_t)rows[j] * row_bytes + lane_off);
-                    dj[j] = I.dp[u][j * BT];  // 16 lanes read 64 contiguous bytes of one list entry
-                }
+                const bool ok = j < I.nv[u];
+                const uint32_t row = ok ? (uint32_t)rows[j] : 0u;
+                const uint4 v = load_weights16(wbase + (uint64_t)row * row_bytes + lane_off);
+                st.r[u][j] = make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
             }
-            st.dv[u] = make_float4(dj[0], dj[1], dj[2], dj[3]);
         }
     };
     auto compute = [&](const Stage& st) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
-            s16x4_t a_hi, a_lo;
-            split_bf16x4(st.dv[u], a_hi, a_lo);
+            union { uint32_t u32[2]; s16x4_t v; } ah, al;
+            ah.u32[0] = st.av[u].x;
+            ah.u32[1] = st.av[u].y;
+            al.u32[0] = st.av[u].z;
+            al.u32[1] = st.av[u].w;
+            const s16x4_t a_hi = ah.v, a_lo = al.v;
             const uint32_t q0[4] = {st.r[u][0].x, st.r[u][0].y, st.r[u][0].z, st.r[u][0].w};
             const uint32_t q1[4] = {st.r[u][1].x, st.r[u][1].y, st.r[u][1].z, st.r[u][1].w};
             const uint32_t q2[4] = {st.r[u][2].x, st.r[u][2].y, st.r[u][2].z, st.r[u][2].w};
@@ -317,31 +362,46 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     }
 
     // ------------------------------------------------------------------ add the wavefronts' sums
-    // acc[e][i] = token 4*kg + i, column col0 + e.  One pass per i: 4 tokens x TILE columns per wavefront.
+    // Every wavefront holds a full [16 tokens x TILE columns] tile of sums in the same lane layout
+    // (acc[e][i] = token 4*kg + i, column col0 + e), so they are added as a binary tree over the wavefronts
+    // through LDS, CH accumulators at a time: the upper half of the surviving wavefronts writes, the lower
+    // half adds lane by lane (conflict-free 16-byte accesses, every lane busy, fixed order), until wavefront
+    // 0 holds the workgroup's sums and stores them straight from its registers.
     const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
+    constexpr int CH = (WAVES <= 8) ? 8 : 4;  // (WAVES/2) * CH * 64 lanes * 16 bytes = 32 KB of LDS
+    static_assert(ELEMS % CH == 0, "accumulators are handed over in whole chunks");
+    f32x4_t* s_tree = reinterpret_cast<f32x4_t*>(s_red);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float4* dst = reinterpret_cast<float4*>(s_red + (w * 4 + kg) * TILE + cg * ELEMS);
+    for (int c0 = 0; c0 < ELEMS; c0 += CH) {
 #pragma unroll
-        for (int v = 0; v < ELEMS / 4; ++v)
-            dst[v] = make_float4(acc[4 * v][i], acc[4 * v + 1][i], acc[4 * v + 2][i], acc[4 * v + 3][i]);
-        __syncthreads();
-        for (int t = tid; t < 4 * GROUPS; t += NT) {
-            const int mg = t / GROUPS, g = t % GROUPS;
-            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int half = WAVES / 2; half >= 1; half >>= 1) {
+            __syncthreads();  // the buffer is free (previous level or chunk has been read)
+            if (w >= half && w < 2 * half) {
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) {
-                const float4 v = *reinterpret_cast<const float4*>(s_red + (ww * 4 + mg) * TILE + 4 * g);
-                s.x += v.x;
-                s.y += v.y;
-                s.z += v.z;
-                s.w += v.w;
+                for (int e = 0; e < CH; ++e) s_tree[((w - half) * CH + e) * kWave + lane] = acc[c0 + e];
             }
-            const int b = 4 * mg + i;
-            if (b < a.B) emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, s);
+            __syncthreads();
+            if (w < half) {
+#pragma unroll
+                for (int e = 0; e < CH; ++e) acc[c0 + e] += s_tree[(w * CH + e) * kWave + lane];
+            }
         }
-        __syncthreads();
+        if (w == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int b = 4 * kg + i;
+                if (b < a.B) {
+#pragma unroll
+                    for (int v = 0; v < CH / 4; ++v) {
+                        const float4 sum = make_float4(acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i],
+                                                       acc[c0 + 4 * v + 3][i]);
+                        emit_group<WDT, TILE>(a, pbuf, tile, split, b, (cg * ELEMS + c0) / 4 + v, sum);
+                    }
+                }
+            }
+        }
     }
+    __syncthreads();
 
     finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L);
 }
@@ -351,7 +411,7 @@ int launch_gemm_mfma(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, 
     if (wdt != kBF16 && wdt != kI8) return SCAP_ERR_CONFIG;
     const int tile_cols = wdt == kI8 ? 2 * kMfmaTile : kMfmaTile;
     if (!a.u_idx || !a.u_d) return SCAP_ERR_WORKSPACE;
-    int kc = 0, waves = 8, ub = 2;
+    int kc = 0, waves = 8, ub = 1;
     if (cfg) {
         if (cfg->rows_per_group) kc = cfg->rows_per_group;
         if (kc < 0 || (kc % kWave) != 0) return SCAP_ERR_CONFIG;
@@ -392,8 +452,8 @@ int launch_gemm_mfma(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, 
     hipLaunchKernelGGL(batch_union_kernel, dim3((unsigned)a.Sl), dim3(kCompactWaves * kWave), 0, stream, a);
     if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
 
-    // reduction buffers: waves x 4 token groups x 128 columns (the final reduction needs less)
-    const size_t lds = lds_bytes(0, 0, (size_t)waves * 4 * tile_cols * 4);
+    // tree reduction buffer: 32 KB (the final reduction needs less)
+    const size_t lds = lds_bytes(0, 0, (size_t)32 * 1024);
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
     const dim3 grid((unsigned)(a.S * a.T));
     const dim3 block(waves * kWave);
