@@ -96,9 +96,10 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
     for (int p0 = k0; p0 < kend; p0 += NT) {
         const int k = p0 + tid;
         const bool valid = k < kend;
-        uint32_t xb[BT];
+        uint32_t xb[BT];  // branch-free loads: slots past the batch or the end re-read a valid element, masked below
+        const int kc_ = min(k, a.K - 1);
 #pragma unroll
-        for (int b = 0; b < BT; ++b) xb[b] = (valid && b < a.B) ? (uint32_t)a.x[(int64_t)b * a.K + k] : 0u;
+        for (int b = 0; b < BT; ++b) xb[b] = (uint32_t)a.x[(int64_t)min(b, a.B - 1) * a.K + kc_];
         uint32_t keepmask = 0;
         float dm[BT];  // centred value where the token keeps the channel, else 0
 #pragma unroll

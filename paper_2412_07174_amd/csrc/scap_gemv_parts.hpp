@@ -105,10 +105,16 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
     // Centred value and keep test of every token at channel k.  The loads of all tokens are issued
     // together (no control flow between them) so that one memory latency covers the whole batch.
     auto eval_all = [&](int k, bool valid, float (&d)[BT], bool (&keep)[BT]) {
+        // branch-free loads: a lane past the end or a token slot past the batch re-reads the last valid
+        // element (it is masked below); only the bias-folding mode, which has no input, skips them
         uint32_t xb[BT];
+        const int kc_ = min(k, a.K - 1);
 #pragma unroll
-        for (int b = 0; b < BT; ++b)
-            xb[b] = (valid && b < a.B && a.mode != kModeFold) ? (uint32_t)a.x[(int64_t)b * a.K + k] : 0u;
+        for (int b = 0; b < BT; ++b) xb[b] = 0u;
+        if (a.mode != kModeFold) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b) xb[b] = (uint32_t)a.x[(int64_t)min(b, a.B - 1) * a.K + kc_];
+        }
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
             const float xf = a.xdt == kBF16 ? bf16_bits_to_f32(xb[b]) : f16_bits_to_f32(xb[b]);
