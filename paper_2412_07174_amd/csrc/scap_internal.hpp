@@ -26,7 +26,7 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 //                        different tiles go to different memory channels; zero at rest
 //   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums; during calibration the first
 //                        512 KiB hold the uint64 count of every 16-bit code
-//   [.., +68*(K+16384))  batched path (B >= 2): union list of every list segment (16 centred values and
+//   [.., +68*(K+16384))  batched path (B >= 2): union list of every list segment (64 bytes of A operands and
 //                        the channel index per entry)
 // ---------------------------------------------------------------------------------------------
 constexpr size_t kOffSegCnt = 65536;
@@ -67,7 +67,8 @@ struct GemvArgs {
     int32_t* seg_cnt;
     float* partial;
     int32_t* u_idx;  // batched path: union list of each segment, [Sl][Kl] channel indices
-    float* u_d;      // batched path: centred values of the union list, [Sl][Kl][16 tokens]
+    float* u_d;      // batched path: the union list's centred values as MFMA A operands: per 16 entries 64 lanes x
+                     // (4 bf16 heads, 4 bf16 tails) = 1 KB, i.e. 64 bytes per entry
     int K, N, B, Kc, S, T, mode, xdt;
     int Kl, Sl;  // segmentation of the kept-channel lists: Sl segments of Kl channels (= S, Kc unless batched)
     float m, tau;
