@@ -26,27 +26,41 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv_kernel(const GemvArgs a) {
 int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced) {
     a.T = (int)((a.N + tile - 1) / tile);
     if (a.T > kMaxTiles) return SCAP_ERR_SHAPE;
-    if (kc == 0) {
-        // about one workgroup per compute unit (256): more splits only lengthen the final reduction,
-        // fewer leave compute units -- each limited to ~100 GB/s of misses -- without work
-        const int want_groups = 256;
-        int s = (want_groups + a.T - 1) / a.T;
-        if (s < 1) s = 1;
-        kc = (int)align_up((size_t)((a.K + s - 1) / s), kWave);
-        if (kc < 128) kc = 128;
-    }
-    // bounds from the workspace: at most kMaxSplits splits and partial_capacity floats per token
+    // bounds from the workspace (at most kMaxSplits splits and partial_capacity floats per token) and from
+    // LDS (the kept-channel list of one workgroup must fit)
     const size_t tile_cols = (size_t)a.T * tile;
     size_t s_cap = partial_capacity(a.N) / tile_cols;
     if (s_cap > (size_t)kMaxSplits) s_cap = kMaxSplits;
     if (s_cap < 1) s_cap = 1;
+    const int kc_lds = (int)((64 * 1024 - kHdrBytes) / (4 * (1 + floats_per_entry)) / kWave * kWave);
+    if (kc == 0) {
+        // Rows per workgroup, a multiple of 64.  Workgroups are spread over the 256 compute units, so the
+        // launch takes about as long as the busiest unit: ceil(workgroups / 256) workgroups, each costing
+        // its kc rows plus a fixed part (prologue, reduction, hand-over) worth about kFixedRows rows.
+        // Slightly more than 256 workgroups is the worst case (on 4096 x 28672, 280 workgroups of 832 rows
+        // took 50.8 us, 224 of 1024 rows 38.2 us); more splits than needed only lengthen the final
+        // reduction, so ties go to the larger kc.
+        constexpr int kFixedRows = 128;
+        int kc_max = (int)align_up((size_t)a.K, kWave);
+        if (kc_max > kc_lds) kc_max = kc_lds;
+        long best_cost = -1;
+        for (int c = kc_max; c >= kWave; c -= kWave) {
+            const long splits = (a.K + c - 1) / c;
+            if ((size_t)splits > s_cap) break;  // smaller c only means more splits
+            const long cost = ((splits * a.T + 255) / 256) * (c + kFixedRows);
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                kc = c;
+            }
+        }
+        if (kc == 0) return SCAP_ERR_SHAPE;
+    }
     int s = (a.K + kc - 1) / kc;
     if ((size_t)s > s_cap) {
+        if (kc_forced) return SCAP_ERR_CONFIG;
         kc = (int)align_up((size_t)((a.K + s_cap - 1) / s_cap), kWave);
         s = (a.K + kc - 1) / kc;
     }
-    // LDS budget: the list of one workgroup must fit
-    const int kc_lds = (int)((64 * 1024 - kHdrBytes) / (4 * (1 + floats_per_entry)) / kWave * kWave);
     if (kc > kc_lds) {
         if (kc_forced) return SCAP_ERR_CONFIG;
         kc = kc_lds;
