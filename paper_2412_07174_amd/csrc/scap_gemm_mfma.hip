@@ -242,6 +242,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     const uint32_t row_bytes = (uint32_t)a.N * Vec<WDT>::kBytes;
     const char* wbase = reinterpret_cast<const char*>(a.W);
 
+    // constants of the column group this thread finishes if its workgroup is the tile's last arrival
+    const ColConst mine = load_col_const<WDT, TILE>(a, tile, tid % (TILE / 4));
+
     f32x4_t acc[ELEMS];
 #pragma unroll
     for (int e = 0; e < ELEMS; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -396,7 +399,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
                     for (int v = 0; v < CH / 4; ++v) {
                         const float4 sum = make_float4(acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i],
                                                        acc[c0 + 4 * v + 3][i]);
-                        emit_group<WDT, TILE>(a, pbuf, tile, split, b, (cg * ELEMS + c0) / 4 + v, sum);
+                        const int g = (cg * ELEMS + c0) / 4 + v;
+                        // one split: this is the finished value, and the group's constants are loaded here
+                        emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, sum, nullptr,
+                                              a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
                     }
                 }
             }
@@ -404,7 +410,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     }
     __syncthreads();
 
-    finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L);
+    finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L, mine);
 }
 
 int launch_gemm_mfma(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipStream_t stream) {

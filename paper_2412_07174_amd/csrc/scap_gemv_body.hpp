@@ -30,6 +30,7 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& a) {
     constexpr int RPI = kWave / LPR;  // rows per load instruction
     constexpr int NT = WAVES * kWave;
     constexpr int GROUPS = TILE / 4;  // 4-column groups of a tile
+    static_assert(GROUPS <= NT && NT % GROUPS == 0, "thread t finishes group t % GROUPS in every pass");
 
     extern __shared__ uint4 smem_raw[];
     Lds L = carve_lds<WAVES, BT>(reinterpret_cast<char*>(smem_raw), a.Kc);
@@ -46,6 +47,9 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& a) {
     const int lane = tid & 63;
     const int tile = blockIdx.x % a.T;
     const int split = blockIdx.x / a.T;
+
+    // constants of the column group this thread will finish (needed only at the very end: loaded now)
+    const ColConst mine = load_col_const<WDT, TILE>(a, tile, tid % GROUPS);
 
     // ------------------------------------------------------------------ 1. centre, threshold, compact
     int cnt;
@@ -161,14 +165,14 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& a) {
                     s.z += v.z;
                     s.w += v.w;
                 }
-                emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, s, L.fin);
+                emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, s, L.fin, mine);  // g == tid here
             }
             __syncthreads();
         }
     }
 
     // ------------------------------------------------------------------ 4. last arrival finishes the tile
-    finish_tile<WDT, WAVES, TILE, BT, FUSE>(a, pbuf, tile, L);
+    finish_tile<WDT, WAVES, TILE, BT, FUSE>(a, pbuf, tile, L, mine);
 }
 
 }  // namespace scap

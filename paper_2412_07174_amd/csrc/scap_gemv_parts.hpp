@@ -431,24 +431,45 @@ __device__ __forceinline__ void close_block_lists(const GemvArgs& a, const Lds& 
 }
 
 // ---------------------------------------------------------------------------------------------- epilogue
+// Per-column constants of a 4-column group: fused bias and (int8) column scales.  A thread that will finish
+// group g loads them when the kernel starts, so that the tile's last arrival does not add another memory
+// round trip after it has read the partial sums.
+struct ColConst {
+    float4 bias, scale;
+};
+template <int WDT, int TILE>
+__device__ __forceinline__ ColConst load_col_const(const GemvArgs& a, int tile, int g) {
+    ColConst c;
+    c.bias = make_float4(0.f, 0.f, 0.f, 0.f);
+    c.scale = make_float4(1.f, 1.f, 1.f, 1.f);
+    const int col = tile * TILE + 4 * g;
+    if (col < a.N) {  // N is a multiple of 8: a group is inside or outside as a whole
+        if (a.bias) c.bias = *reinterpret_cast<const float4*>(a.bias + col);
+        if (WDT == kI8) {
+            const uint2 h = *reinterpret_cast<const uint2*>(a.col_scale + col);
+            c.scale = make_float4(f16_bits_to_f32(h.x & 0xFFFFu), f16_bits_to_f32(h.x >> 16), f16_bits_to_f32(h.y & 0xFFFFu),
+                                  f16_bits_to_f32(h.y >> 16));
+        }
+    }
+    return c;
+}
+
 // scale (int8), add the fused bias, store 4 columns of y
 template <int WDT, int TILE, int FUSE = kFusePlain>
-__device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int b, int g, float4 s, float* s_fin) {
+__device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int b, int g, float4 s, float* s_fin,
+                                               const ColConst& c) {
     const int col = tile * TILE + 4 * g;
-    if (col >= a.N) return;  // N is a multiple of 8: a group is inside or outside as a whole
+    if (col >= a.N) return;
     if (WDT == kI8) {
-        s.x *= f16_bits_to_f32(a.col_scale[col]);
-        s.y *= f16_bits_to_f32(a.col_scale[col + 1]);
-        s.z *= f16_bits_to_f32(a.col_scale[col + 2]);
-        s.w *= f16_bits_to_f32(a.col_scale[col + 3]);
+        s.x *= c.scale.x;
+        s.y *= c.scale.y;
+        s.z *= c.scale.z;
+        s.w *= c.scale.w;
     }
-    if (a.bias) {
-        const float4 bv = *reinterpret_cast<const float4*>(a.bias + col);
-        s.x += bv.x;
-        s.y += bv.y;
-        s.z += bv.z;
-        s.w += bv.w;
-    }
+    s.x += c.bias.x;
+    s.y += c.bias.y;
+    s.z += c.bias.z;
+    s.w += c.bias.w;
     if constexpr (FUSE == kFuseSwiglu)
         *reinterpret_cast<float4*>(s_fin + b * TILE + 4 * g) = s;
     else
@@ -462,11 +483,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t partial_buffer(const GemvArgs&
 }
 
 // the workgroup's sum of 4 columns for token b: final output if there is one split, else a partial
+// (`c` = constants of group g, loaded beforehand or here)
 template <int WDT, int TILE, int FUSE = kFusePlain>
 __device__ __forceinline__ void emit_group(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, int split, int b,
-                                           int g, float4 s, float* s_fin = nullptr) {
+                                           int g, float4 s, float* s_fin, const ColConst& c) {
     if (a.S == 1)
-        finish_columns<WDT, TILE, FUSE>(a, tile, b, g, s, s_fin);
+        finish_columns<WDT, TILE, FUSE>(a, tile, b, g, s, s_fin, c);
     else
         store_coherent16(pbuf, (uint32_t)((((b * a.S + split) * a.T + tile) * TILE + 4 * g) * 4), s);
 }
@@ -474,8 +496,10 @@ __device__ __forceinline__ void emit_group(const GemvArgs& a, __amdgpu_buffer_rs
 // Arrival ticket; the last arrival of a tile adds the S partials (fixed association), writes y and clears
 // the counter; the last arrival of tile 0 also closes the gaps between the per-split index lists.
 // Every thread of the workgroup must call this after its last emit_group().
+// `mine` = constants of group (tid % GROUPS), the group this thread finishes in every pass.
 template <int WDT, int WAVES, int TILE, int BT, int FUSE = kFusePlain>
-__device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, const Lds& L) {
+__device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, const Lds& L,
+                                            const ColConst& mine) {
     constexpr int NT = WAVES * kWave;
     constexpr int GROUPS = TILE / 4;
     const int tid = threadIdx.x;
@@ -535,7 +559,7 @@ __device__ __forceinline__ void finish_tile(const GemvArgs& a, __amdgpu_buffer_r
                     s.z += v.z;
                     s.w += v.w;
                 }
-                finish_columns<WDT, TILE, FUSE>(a, tile, b, g, s, L.fin);
+                finish_columns<WDT, TILE, FUSE>(a, tile, b, g, s, L.fin, mine);  // g == tid % GROUPS
             }
             __syncthreads();
         }
