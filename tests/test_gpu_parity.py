@@ -489,3 +489,28 @@ def test_two_streams_with_their_own_workspaces():
         torch.cuda.synchronize()
         for i in range(16):
             assert torch.equal(out1[i], ref1[i]) and torch.equal(out8[i], ref8[i]), f"rep {rep} call {i}"
+
+
+def test_random_shapes_and_thresholds():
+    """Seeded sweep over odd shapes: K from 1 to ~6000, N any multiple of the vector width up to ~7000, 1-16 tokens,
+    every weight dtype, thresholds from 'keep all' to 'keep almost nothing', with and without bias and centring."""
+    rng = np.random.default_rng(20241207)
+    for case in range(90):
+        wdt = (F16, BF16, I8)[case % 3]
+        xdt = BF16 if wdt == I8 else wdt
+        vec = 16 if wdt == I8 else 8
+        K = int(rng.choice([1, 7, 63, 64, 65, 129, 500, 1023, 2049, 4097, 6001])) if case % 4 == 0 else int(rng.integers(1, 6000))
+        N = vec * int(rng.integers(1, 7000 // vec))
+        B = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 7, 8, 11, 16]))
+        m = float(rng.choice([0.0, 0.13, -0.4]))
+        if wdt == I8:
+            W, scale = wl.quantize_i8(K, N, 3000 + case)
+        else:
+            W, scale = wl.weights(K, N, 3000 + case, wdt), None
+        layer = Layer(W, wdt, col_scale_bits=scale, B=16)
+        X = wl.laplace(B, K, 4000 + case, xdt, loc=m, scale=0.7)
+        d = np.abs(wl.decode(X, xdt).astype(np.float32) - np.float32(m))
+        tau = float(np.quantile(d, rng.choice([0.0, 0.3, 0.5, 0.8, 0.97, 1.0])))
+        bf = rng.standard_normal(N).astype(np.float32) if case % 2 else None
+        say(f"random case {case}: wdt={wdt} K={K} N={N} B={B} m={m} tau={tau:.4g}")
+        check_against_oracle(layer, X, xdt, m, tau, bf, what=f"random case {case} K={K} N={N} B={B}")

@@ -300,3 +300,23 @@ def test_mistral_ffn_block_full_size(s_x, s_z):
         dens = got["idx_z"].size / F
         assert abs(dens - (1 - s_z)) < 0.05
         assert flips <= 3
+
+
+def test_random_blocks():
+    """Seeded sweep over odd block shapes, 1-4 tokens, every weight dtype."""
+    rng = np.random.default_rng(20241208)
+    for case in range(24):
+        dt = (F16, BF16, I8)[case % 3]
+        xdt = BF16 if dt == I8 else dt
+        K = int(rng.integers(8, 3000))
+        F = (8 if dt == I8 else 4) * int(rng.integers(1, 600))
+        N = (16 if dt == I8 else 8) * int(rng.integers(1, 300))
+        B = int(rng.choice([1, 1, 2, 3, 4]))
+        blk = Block(K, F, N, dt, seed=5000 + case, B=B)
+        X = wl.laplace(B, K, 6000 + case, xdt, loc=0.05, scale=0.9)
+        zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.05, 0.3, 0.0, 0.0, dt, xdt, gate_scale=blk.sg,
+                                        up_scale=blk.su, down_scale=blk.sd)["z"])
+        tau_x = float(rng.choice([0.0, 0.3, 0.9]))
+        tau_z = float(np.quantile(zs, rng.choice([0.0, 0.4, 0.9])))
+        say(f"random block {case}: dt={dt} K={K} F={F} N={N} B={B} tau_x={tau_x} tau_z={tau_z:.4g}")
+        blk.check_batch(X, xdt, 0.05, tau_x, None, None, 0.001, tau_z, None, f"random block {case}")
