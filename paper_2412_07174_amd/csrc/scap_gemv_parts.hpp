@@ -58,17 +58,10 @@ struct Lds {
     int* hdr;    // [(1+BT)][WAVES] per-wave kept counts (union first, then per token)
     int* flag;   // [0] last-arrival flag
     int* idx;    // [Kc] kept channel indices, ascending (LDS, or global for the batched path)
-    float* d;    // centred values per token (0 where the token pruned the channel); see d_at()
+    float* d;    // centred values, token-major [BT][Kc] (0 where the token pruned the channel)
     float* red;  // reduction buffer; reuses the list space once the rows have been streamed
     float* fin;  // kFuseSwiglu: the tile's finished columns (after scale and bias), [BT][TILE]
 };
-
-// Position of token b's value of list entry e in Lds::d: token-major [BT][Kc] (a wavefront reads
-// consecutive entries of one token).
-template <int DSTRIDE>
-__device__ __forceinline__ int d_at(int b, int e, int Kc) {
-    return b * Kc + e;
-}
 
 template <int WAVES, int BT>
 __device__ __forceinline__ Lds carve_lds(char* smem, int Kc) {
@@ -87,7 +80,7 @@ __device__ __forceinline__ Lds carve_lds(char* smem, int Kc) {
 // token into an ascending list in LDS (wave64 ballot + prefix counts; cross-wave offsets through LDS).
 // Workgroups of column tile 0 also leave the per-token lists in idx_out and the counts in seg_cnt when
 // the caller asked for them.  Returns the list length (wave-uniform); ends with a barrier.
-template <int WAVES, int BT, int DSTRIDE = 0>
+template <int WAVES, int BT>
 __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int split, const Lds& L) {
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
@@ -174,7 +167,7 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
                     const int k = k0 + c * kWave + lane;
                     const int pos = ubase + lanes_below(breg[j]);
                     L.idx[pos] = k;
-                    L.d[d_at<DSTRIDE>(0, pos, a.Kc)] = dreg[j];
+                    L.d[pos] = dreg[j];
                     if (want_idx) store_dev(&a.idx_out[k0 + pos], k);
                 }
                 ubase += __popcll(breg[j]);
@@ -254,7 +247,7 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
                 const int pos = ubase + lanes_below(ub);
                 L.idx[pos] = k;
 #pragma unroll
-                for (int b = 0; b < BT; ++b) L.d[d_at<DSTRIDE>(b, pos, a.Kc)] = d[b];
+                for (int b = 0; b < BT; ++b) L.d[b * a.Kc + pos] = d[b];
                 if (BT == 1 && want_idx) store_dev(&a.idx_out[k0 + pos], k);
             }
             ubase += __popcll(ub);

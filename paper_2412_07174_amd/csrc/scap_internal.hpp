@@ -96,7 +96,7 @@ int launch_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t 
 
 // Batched tokens over bf16 or int8 weights on the matrix cores: possible from kMfmaMinTokens tokens on (the
 // workspace then carries the union lists), chosen by default from kMfmaAutoTokens on -- at 4 tokens the
-// single-launch vector kernel is still faster (measured 31 vs 41 us on 14336 x 4096).
+// single-launch vector kernel is still faster (measured 29 vs 35 us on 14336 x 4096).
 constexpr int kMfmaMinTokens = 2;
 constexpr int kMfmaAutoTokens = 5;
 int launch_gemm_mfma(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
