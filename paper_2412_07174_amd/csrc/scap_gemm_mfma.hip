@@ -141,12 +141,18 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
         }
         __syncthreads();
         const int n_items = ((carry + total + kMfmaBlock - 1) / kMfmaBlock) * kWave;  // (block, lane) pairs
-        for (int it = tid; it < n_items; it += NT) {
+        constexpr int kItemRounds = (NT / kMfmaBlock + 2) * kWave / NT + 1;  // covers carry + NT entries
+#pragma unroll
+        for (int q = 0; q < kItemRounds; ++q) {
+            const int it = tid + q * NT;
+            if (it >= n_items) break;
             const int blk = first_blk + it / kWave;
             const int l = it % kWave;
             const int tok = l & 15, kg = l >> 4;
             uint4 prev = make_uint4(0u, 0u, 0u, 0u);
-            if (carry != 0 && it < kWave) prev = out_a[(int64_t)blk * kWave + l];
+            if (carry != 0) {  // only a segment longer than one pass can have a block that straddles passes
+                if (it < kWave) prev = out_a[(int64_t)blk * kWave + l];
+            }
             float4 d = make_float4(0.f, 0.f, 0.f, 0.f);
             float* dv = &d.x;
             bool from_prev[4];
@@ -158,8 +164,8 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
             }
             s16x4_t hi, lo;
             split_bf16x4(d, hi, lo);
-            union { uint4 q; short h[8]; } pk;
-            pk.q = prev;
+            union { uint4 q4; short h[8]; } pk;
+            pk.q4 = prev;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (!from_prev[j]) {
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(kCompactWaves * kWave) void batch_union_kernel(cons
                     pk.h[4 + j] = lo[j];
                 }
             }
-            out_a[(int64_t)blk * kWave + l] = pk.q;
+            out_a[(int64_t)blk * kWave + l] = pk.q4;
         }
         run_u += total;
         if (per_token) {
@@ -222,15 +228,15 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     const int per_split = a.Kc / a.Kl;
     const int seg0 = split * per_split;
     const int nseg = min(per_split, a.Sl - seg0);
-    if (tid < nseg) s_segcnt[tid] = a.seg_cnt[a.B * a.Sl + seg0 + tid];
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int i = 0; i < nseg; ++i) {
-            s_pre[i] = run;
-            run += (s_segcnt[i] + kMfmaBlock - 1) / kMfmaBlock;
+    if (w == 0) {  // nseg <= 64: one wavefront loads the counts and scans the block numbers
+        const int cnt = lane < nseg ? a.seg_cnt[a.B * a.Sl + seg0 + lane] : 0;
+        const int blocks = (cnt + kMfmaBlock - 1) / kMfmaBlock;
+        const int inc = wave_inclusive_scan(blocks);
+        if (lane < nseg) {
+            s_segcnt[lane] = cnt;
+            s_pre[lane] = inc - blocks;
         }
-        s_pre[nseg] = run;
+        if (lane == kWave - 1) s_pre[nseg] = inc;
     }
     __syncthreads();
     const int n_blocks = uniform(s_pre[nseg]);
