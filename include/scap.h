@@ -114,8 +114,10 @@ int scap_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  *                            tau is the k-th smallest of |fp32(x) - m| over the pool, k = ceil(s*n*K),
  *                            no interpolation (k = 0 gives tau = 0); |.| is formed exactly as
  *                            scap_sparse_fc forms it, so the sample's own sparsity is >= s.
- *   workspace        DEVICE  scap_workspace_bytes(K, 0, n) bytes, initialised.
- * NaN samples rank above every number.
+ *   workspace        DEVICE  scap_workspace_bytes(K, 0, n) bytes, initialised (a layer's workspace is large
+ *                            enough as well).
+ * The sample is read in one pass that counts the occurrences of each 16-bit code; the statistics are then
+ * exact functions of those counts.  NaN samples rank above every number.
  */
 int scap_calibrate(const void* X_calib, int64_t n, int64_t K, int xdt, float target_sparsity, int est,
                    float* m_out, float* tau_out, void* workspace, size_t workspace_bytes, void* stream);
@@ -132,7 +134,9 @@ int scap_fold_bias(const void* W, const void* col_scale, int64_t K, int64_t N, i
 
 /*
  * ASYNC, the decode-time hot path (Alg. 3 with the strict compare of Eq. 2; Eq. 3 / Eq. 6).
- * One launch: centre, threshold, compact the kept channels, read only their weight rows, reduce.
+ * One launch: centre, threshold, compact the kept channels, read only their weight rows, reduce
+ * (two launches -- union of the masks, then the gathered product on the matrix cores -- from 5 tokens on over
+ * bf16 or int8 weights).
  *   W, col_scale   as in scap_fold_bias.
  *   x              DEVICE  [B, K] row-major, dtype xdt (SCAP_F16 or SCAP_BF16).
  *   m, tau         layer constants from scap_calibrate (tau >= 0, both finite).
