@@ -68,18 +68,19 @@ typedef enum {
                              0.001 and 0.999 order statistics, 5-bin box smoothing, fullest bin */
 } scap_mode_est;
 
-/* Optional launch shape of the GEMV kernels (for tuning sweeps).  Zero fields mean "choose".
- * With 5 or more tokens over bf16 or int8 weights the matrix-core kernel runs unless lanes_per_row says
- * otherwise (64 / 32: vector kernel; 16: matrix-core kernel, allowed from 2 tokens on); there waves_per_group
- * is 8 or 16 (int8: 8), unroll (1, 2, 4; int8: 1, 2) counts 16-row blocks in flight per wavefront, and
- * rows_per_group is rounded up to whole 512-channel list segments. */
+/* Optional launch shape of the kernels (for tuning sweeps and tests).  Zero fields mean "choose".
+ * lanes_per_row selects the kernel: 64 or 32 = the vector kernel (column tile = lanes_per_row x 8 columns,
+ * x 16 for int8; batches: 64 only); 16 = the single-launch matrix-core kernel and 1 = the two-launch
+ * matrix-core form with its lists in the workspace (both: 2..16 tokens over bf16 or int8 weights; there
+ * waves_per_group must be 0 or 8 -- the two-launch form also takes 16 with bf16 -- and rows_per_group is a
+ * multiple of 64, rounded up to whole 512-channel list segments by the two-launch form, whose unroll
+ * (1, 2, 4; int8: 1, 2) counts 16-row blocks in flight per wavefront).  By default batches of 5 or more tokens
+ * over bf16 weights and of 3 or more over int8 weights run on the matrix cores. */
 typedef struct {
     int32_t waves_per_group; /* 4, 8 or 16 wavefronts per workgroup */
     int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */
     int32_t unroll;          /* weight rows in flight per wavefront: 4, 8 or 16 */
-    int32_t lanes_per_row;   /* lanes sharing one weight row per load: 64 or 32 (column tile =
-                                lanes_per_row x 8 columns, x 16 for int8; batch > 1: 64 only), or 16 =
-                                the matrix-core kernel (2..16 tokens, bf16 or int8 weights) */
+    int32_t lanes_per_row;   /* 64, 32, 16 or 1: see above */
 } scap_launch_cfg;
 
 /* Static, NUL-terminated description of a status code.  Never freed. */
@@ -134,9 +135,9 @@ int scap_fold_bias(const void* W, const void* col_scale, int64_t K, int64_t N, i
 
 /*
  * ASYNC, the decode-time hot path (Alg. 3 with the strict compare of Eq. 2; Eq. 3 / Eq. 6).
- * One launch: centre, threshold, compact the kept channels, read only their weight rows, reduce
- * (two launches -- union of the masks, then the gathered product on the matrix cores -- from 5 tokens on over
- * bf16 or int8 weights).
+ * One launch: centre, threshold, compact the kept channels, read only their weight rows, reduce (two
+ * launches -- union of the masks, then the gathered product -- only for a batch whose input is too long for a
+ * workgroup's share of it to fit LDS: more than about 600 000 channels).
  *   W, col_scale   as in scap_fold_bias.
  *   x              DEVICE  [B, K] row-major, dtype xdt (SCAP_F16 or SCAP_BF16).
  *   m, tau         layer constants from scap_calibrate (tau >= 0, both finite).

@@ -17,50 +17,12 @@
 // per-value loads from a plain [entry][token] array cost four instructions per block; both throttled the
 // weight stream).
 //
-// Operand layout without any transposition.  For this instruction lane l holds
-//     A[m = l%16][k = 4*(l/16) + j],   B[k = 4*(l/16) + j][n = l%16],   C[m = 4*(l/16) + i][n = l%16],  i,j = 0..3.
-// The weights are K-major, so a lane cannot fetch four rows of one column in one access; but it can fetch
-// 16 bytes = 8 columns of one row.  Lane l therefore loads columns 8*(l%16) .. +7 of the four list rows
-// 4*(l/16) + j of a 16-row block (a load instruction covers four 256-byte row segments), and element e of
-// those four vectors is exactly this lane's B operand of the MFMA that produces columns {8*n + e}.  Eight
-// MFMAs (e = 0..7) per block cover the wavefront's 128 columns; the C registers of lane l then hold tokens
-// 4*(l/16)+i and 8 consecutive columns.  The A operand (centred values of token l%16 at rows 4*(l/16)+j)
-// is read from the list; it is split into a bf16 head and a bf16
-// tail (d = hi + lo) and fed through two MFMAs, so the bf16 rounding of d costs about 2^-17 relative
-// instead of 2^-9.
-//
-// int8 weights (one fp16 scale per column) go through the same instruction: every int8 value is exactly a
-// bf16 number, so the 16 bytes a lane loads are widened in registers to the bf16 B operands of 16 MFMAs
-// (tile = 256 columns) and the column scale is applied to the finished sums, as in the vector kernel.
-#include "scap_gemv_parts.hpp"
+// Operand layout, bf16 head/tail split of the centred values and the int8 widening: see scap_mfma_parts.hpp.
+// This two-launch form keeps its lists in the workspace, so the input length is not bounded by LDS; the
+// single-launch form (scap_gemm_inline.hip) is preferred whenever a workgroup's list fits LDS.
+#include "scap_mfma_parts.hpp"
 
 namespace scap {
-
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-constexpr int kMfmaTile = 128;    // columns per workgroup with bf16 weights (16 lanes x 8); int8: 256
-constexpr int kMfmaTokens = 16;   // M of the MFMA; tokens beyond B are zero rows
-constexpr int kMfmaBlock = 16;    // list rows per MFMA (K of the MFMA)
-constexpr int kCompactWaves = 8;
-
-__device__ __forceinline__ uint32_t bf16_rne_bits(float v) {
-    const uint32_t u = __float_as_uint(v);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // finite or infinite input (NaN never reaches the list)
-}
-
-// 4 centred values -> bf16 head and tail operands
-__device__ __forceinline__ void split_bf16x4(const float4& d, s16x4_t& hi, s16x4_t& lo) {
-    const float v[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t h = bf16_rne_bits(v[j]);
-        const float hf = __uint_as_float(h << 16);
-        const float rest = ((h & 0x7FFFu) != 0x7F80u) ? v[j] - hf : 0.f;  // an infinite head has no tail
-        hi[j] = (short)h;
-        lo[j] = (short)bf16_rne_bits(rest);
-    }
-}
 
 // ---------------------------------------------------------------------------------------------- launch 1
 // Workgroup `seg` owns channels [seg*Kl, (seg+1)*Kl): one channel per thread and pass; the x values of all
@@ -318,39 +280,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
             ah.u32[1] = st.av[u].y;
             al.u32[0] = st.av[u].z;
             al.u32[1] = st.av[u].w;
-            const s16x4_t a_hi = ah.v, a_lo = al.v;
-            const uint32_t q0[4] = {st.r[u][0].x, st.r[u][0].y, st.r[u][0].z, st.r[u][0].w};
-            const uint32_t q1[4] = {st.r[u][1].x, st.r[u][1].y, st.r[u][1].z, st.r[u][1].w};
-            const uint32_t q2[4] = {st.r[u][2].x, st.r[u][2].y, st.r[u][2].z, st.r[u][2].w};
-            const uint32_t q3[4] = {st.r[u][3].x, st.r[u][3].y, st.r[u][3].z, st.r[u][3].w};
-#pragma unroll
-            for (int e = 0; e < ELEMS; ++e) {
-                uint32_t lo01, lo23;  // rows (0,1) and (2,3) of column element e, packed as two bf16
-                if constexpr (WDT == kBF16) {
-                    const int q = e >> 1;
-                    if ((e & 1) == 0) {
-                        lo01 = (q0[q] & 0xFFFFu) | (q1[q] << 16);
-                        lo23 = (q2[q] & 0xFFFFu) | (q3[q] << 16);
-                    } else {
-                        lo01 = (q0[q] >> 16) | (q1[q] & 0xFFFF0000u);
-                        lo23 = (q2[q] >> 16) | (q3[q] & 0xFFFF0000u);
-                    }
-                } else {
-                    // byte e of each row, sign-extended, as a float: its low 16 bits are zero (|v| <= 128)
-                    const int q = e >> 2, sh = 24 - 8 * (e & 3);
-                    const uint32_t f0 = __float_as_uint((float)(((int)(q0[q] << sh)) >> 24));
-                    const uint32_t f1 = __float_as_uint((float)(((int)(q1[q] << sh)) >> 24));
-                    const uint32_t f2 = __float_as_uint((float)(((int)(q2[q] << sh)) >> 24));
-                    const uint32_t f3 = __float_as_uint((float)(((int)(q3[q] << sh)) >> 24));
-                    lo01 = (f0 >> 16) | f1;
-                    lo23 = (f2 >> 16) | f3;
-                }
-                union { uint32_t u32[2]; s16x4_t v; } bop;
-                bop.u32[0] = lo01;
-                bop.u32[1] = lo23;
-                acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bop.v, acc[e], 0, 0, 0);
-                acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop.v, acc[e], 0, 0, 0);
-            }
+            mfma_block<WDT>(acc, ah.v, al.v, st.r[u]);
         }
     };
 
@@ -372,49 +302,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_mfma_kernel(const GemvArgs
     }
 
     // ------------------------------------------------------------------ add the wavefronts' sums
-    // Every wavefront holds a full [16 tokens x TILE columns] tile of sums in the same lane layout
-    // (acc[e][i] = token 4*kg + i, column col0 + e), so they are added as a binary tree over the wavefronts
-    // through LDS, CH accumulators at a time: the upper half of the surviving wavefronts writes, the lower
-    // half adds lane by lane (conflict-free 16-byte accesses, every lane busy, fixed order), until wavefront
-    // 0 holds the workgroup's sums and stores them straight from its registers.
     const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
-    constexpr int CH = (WAVES <= 8) ? 8 : 4;  // (WAVES/2) * CH * 64 lanes * 16 bytes = 32 KB of LDS
-    static_assert(ELEMS % CH == 0, "accumulators are handed over in whole chunks");
-    f32x4_t* s_tree = reinterpret_cast<f32x4_t*>(s_red);
-#pragma unroll
-    for (int c0 = 0; c0 < ELEMS; c0 += CH) {
-#pragma unroll
-        for (int half = WAVES / 2; half >= 1; half >>= 1) {
-            __syncthreads();  // the buffer is free (previous level or chunk has been read)
-            if (w >= half && w < 2 * half) {
-#pragma unroll
-                for (int e = 0; e < CH; ++e) s_tree[((w - half) * CH + e) * kWave + lane] = acc[c0 + e];
-            }
-            __syncthreads();
-            if (w < half) {
-#pragma unroll
-                for (int e = 0; e < CH; ++e) acc[c0 + e] += s_tree[(w * CH + e) * kWave + lane];
-            }
-        }
-        if (w == 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int b = 4 * kg + i;
-                if (b < a.B) {
-#pragma unroll
-                    for (int v = 0; v < CH / 4; ++v) {
-                        const float4 sum = make_float4(acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i],
-                                                       acc[c0 + 4 * v + 3][i]);
-                        const int g = (cg * ELEMS + c0) / 4 + v;
-                        // one split: this is the finished value, and the group's constants are loaded here
-                        emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, sum, nullptr,
-                                              a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
+    reduce_waves_and_emit<WDT, WAVES>(a, pbuf, tile, split, acc, s_red);
 
     finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L, mine);
 }

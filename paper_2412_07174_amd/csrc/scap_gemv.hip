@@ -18,7 +18,7 @@
 namespace scap {
 
 // ---------------------------------------------------------------------------------------------- launch
-int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced) {
+int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced, size_t lds_budget) {
     a.T = (int)((a.N + tile - 1) / tile);
     if (a.T > kMaxTiles) return SCAP_ERR_SHAPE;
     // bounds from the workspace (at most kMaxSplits splits and partial_capacity floats per token) and from
@@ -27,7 +27,7 @@ int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_for
     size_t s_cap = partial_capacity(a.N) / tile_cols;
     if (s_cap > (size_t)kMaxSplits) s_cap = kMaxSplits;
     if (s_cap < 1) s_cap = 1;
-    const int kc_lds = (int)((64 * 1024 - kHdrBytes) / (4 * (1 + floats_per_entry)) / kWave * kWave);
+    const int kc_lds = (int)((lds_budget - kHdrBytes) / (4 * (1 + floats_per_entry)) / kWave * kWave);
     if (kc == 0) {
         // Rows per workgroup, a multiple of 64.  Workgroups are spread over the 256 compute units, so the
         // launch takes about as long as the busiest unit: ceil(workgroups / 256) workgroups, each costing
@@ -82,15 +82,29 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
     // Several tokens over bf16 or int8 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
-    // lanes_per_row = 16 asks for that kernel (its lane layout), 64 or 32 for the vector kernel.
+    // lanes_per_row = 16 asks for the single-launch matrix-core kernel (its lane layout), 1 for the
+    // two-launch form whose lists live in the workspace, 64 or 32 for the vector kernel.  By default the
+    // single-launch kernel runs from kMfmaAutoTokens (bf16) / kMfmaAutoTokensI8 (int8) tokens on, the
+    // two-launch form when the input is too long for LDS-sized pieces, the vector kernel otherwise.
     const int lanes = cfg ? cfg->lanes_per_row : 0;
     const bool mfma_ok = a.B >= kMfmaMinTokens && (wdt == kBF16 || wdt == kI8) && a.mode != kModeFold;
-    if (lanes == 16 && !mfma_ok) return SCAP_ERR_CONFIG;
-    if (mfma_ok && (lanes == 16 || (lanes == 0 && a.B >= kMfmaAutoTokens))) {
-        const int rc = launch_gemm_mfma(a, wdt, cfg, stream);
-        // chosen by default and the layer has more 128-column tiles than there are arrival counters: the
-        // vector kernel's tiles are four times wider
-        if (!(rc == SCAP_ERR_SHAPE && lanes == 0)) return rc;
+    if ((lanes == 16 || lanes == 1) && !mfma_ok) return SCAP_ERR_CONFIG;
+    if (lanes == 16) {
+        const int rc = launch_gemm_inline(a, wdt, cfg, stream);
+        return rc == SCAP_ERR_SHAPE ? SCAP_ERR_CONFIG : rc;
+    }
+    if (lanes == 1) return launch_gemm_mfma(a, wdt, cfg, stream);
+    const bool mfma_auto = mfma_ok && lanes == 0 && a.B >= (wdt == kI8 ? kMfmaAutoTokensI8 : kMfmaAutoTokens);
+    if (mfma_auto) {
+        // Short inputs into wide layers (2K <= N, more than 4 tokens): the single launch would repeat a
+        // 16-token prologue in very many narrow tiles while the separate union launch is small, and the
+        // two-launch form measures a few percent faster (4096 -> 14336, 16 tokens, 90 %: 24.9 against 27.1 us).
+        const bool prefer_lists = a.B > 4 && 2 * (int64_t)a.K <= (int64_t)a.N;
+        int rc = prefer_lists ? launch_gemm_mfma(a, wdt, cfg, stream) : launch_gemm_inline(a, wdt, cfg, stream);
+        if (rc == SCAP_ERR_SHAPE)
+            rc = prefer_lists ? launch_gemm_inline(a, wdt, cfg, stream) : launch_gemm_mfma(a, wdt, cfg, stream);
+        // more narrow tiles than there are arrival counters: the vector kernel's tiles are four times wider
+        if (rc != SCAP_ERR_SHAPE) return rc;
     }
 
     int waves = 8, unroll = (bt <= 4) ? 8 : 4, kc = 0, lpr = 64;
@@ -100,7 +114,7 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         if (cfg->rows_per_group) kc = cfg->rows_per_group;
         if (cfg->lanes_per_row) lpr = cfg->lanes_per_row;
         if (kc < 0 || (kc % kWave) != 0) return SCAP_ERR_CONFIG;
-        if (lpr != 64 && lpr != 32) return SCAP_ERR_CONFIG;
+        if (lpr != 64 && lpr != 32) return SCAP_ERR_CONFIG;  // 16 and 1 were handled above
     }
     const int elems = (wdt == kI8) ? 16 : 8;
     // Few column tiles mean many K splits, and the tile's last arrival has to pull all their partial sums
@@ -111,8 +125,10 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (rc != SCAP_OK) {
         // a batch's kept-channel list of a very long input does not fit the vector kernel's LDS; the
         // matrix-core path keeps its lists in the workspace
-        if (rc == SCAP_ERR_SHAPE && mfma_ok && lanes == 0 && !(cfg && cfg->rows_per_group))
-            return launch_gemm_mfma(a_in, wdt, cfg, stream);
+        if (rc == SCAP_ERR_SHAPE && mfma_ok && lanes == 0 && !(cfg && cfg->rows_per_group)) {
+            const int rc2 = launch_gemm_inline(a_in, wdt, cfg, stream);
+            return rc2 == SCAP_ERR_SHAPE ? launch_gemm_mfma(a_in, wdt, cfg, stream) : rc2;
+        }
         return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
     }
     a.Kl = a.Kc;

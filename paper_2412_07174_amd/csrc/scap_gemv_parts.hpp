@@ -275,6 +275,124 @@ __device__ __forceinline__ int compact_inputs(const GemvArgs& a, int tile, int s
     return cnt;
 }
 
+// The same prologue for the matrix-core kernel, whose workgroups own long channel ranges: a wavefront handles
+// up to MAXC chunks of 64 channels and issues the loads of ALL its chunks and tokens before it looks at any of
+// them (one memory round trip instead of one per chunk and pass; the chunk loop of compact_inputs has a
+// loop-carried wait).  Centred values, per-token keep bits and the union ballots stay in registers between
+// the counting and the placing pass.  Requires Kc <= WAVES * 64 * MAXC.
+template <int WAVES, int BT, int MAXC>
+__device__ __forceinline__ int compact_inputs_wide(const GemvArgs& a, int tile, int split, const Lds& L) {
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    const int k0 = split * a.Kc;
+    const int kend = min(k0 + a.Kc, a.K);
+    const bool per_token = tile == 0 && (a.nnz_out != nullptr || a.idx_out != nullptr);
+    const bool want_idx = tile == 0 && a.idx_out != nullptr;
+    const int nchunk = (kend - k0 + kWave - 1) / kWave;
+    const int cpw = (nchunk + WAVES - 1) / WAVES;
+    const int c_begin = min(w * cpw, nchunk);
+    const int c_end = min(c_begin + cpw, nchunk);
+
+    // ---- all loads, branch-free: chunk slots past c_end and token slots past B re-read a valid element
+    uint32_t xb[MAXC][BT];
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int k = min(k0 + (c_begin + j) * kWave + lane, a.K - 1);
+#pragma unroll
+        for (int b = 0; b < BT; ++b) xb[j][b] = (uint32_t)a.x[(int64_t)min(b, a.B - 1) * a.K + k];
+    }
+    // ---- centre, threshold, count
+    float d[MAXC][BT];
+    uint32_t keepmask[MAXC];
+    uint64_t ub[MAXC];
+    int ucount = 0;
+    int tcount[BT];
+#pragma unroll
+    for (int b = 0; b < BT; ++b) tcount[b] = 0;
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int k = k0 + (c_begin + j) * kWave + lane;
+        const bool valid = (c_begin + j) < c_end && k < kend;
+        keepmask[j] = 0;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+            const float xf = a.xdt == kBF16 ? bf16_bits_to_f32(xb[j][b]) : f16_bits_to_f32(xb[j][b]);
+            const float dv = (a.mode == kModeDense) ? xf : xf - a.m;  // one fp32 subtraction
+            const bool keep = valid && b < a.B && (a.mode == kModeDense || fabsf(dv) > a.tau);  // strict; NaN is pruned
+            keepmask[j] |= keep ? (1u << b) : 0u;
+            d[j][b] = keep ? dv : 0.f;
+        }
+        ub[j] = __ballot(keepmask[j] != 0);
+        ucount += __popcll(ub[j]);
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b) tcount[b] += __popcll(__ballot((keepmask[j] >> b) & 1u));
+        }
+    }
+    if (lane == 0) {
+        L.hdr[w] = ucount;
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b) L.hdr[(1 + b) * WAVES + w] = tcount[b];
+        }
+    }
+    __syncthreads();
+    int ubase = 0, cnt = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+        const int v = L.hdr[i];
+        if (i < w) ubase += v;
+        cnt += v;
+    }
+    cnt = uniform(cnt);
+    ubase = uniform(ubase);
+    int tbase[BT], ttotal[BT];
+#pragma unroll
+    for (int b = 0; b < BT; ++b) {
+        tbase[b] = 0;
+        ttotal[b] = 0;
+        if (per_token) {
+            for (int i = 0; i < WAVES; ++i) {
+                const int v = L.hdr[(1 + b) * WAVES + i];
+                if (i < w) tbase[b] += v;
+                ttotal[b] += v;
+            }
+        }
+    }
+    // ---- place
+#pragma unroll
+    for (int j = 0; j < MAXC; ++j) {
+        const int k = k0 + (c_begin + j) * kWave + lane;
+        if (keepmask[j] != 0) {
+            const int pos = ubase + lanes_below(ub[j]);
+            L.idx[pos] = k;
+#pragma unroll
+            for (int b = 0; b < BT; ++b) L.d[b * a.Kc + pos] = d[j][b];
+        }
+        ubase += __popcll(ub[j]);
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b) {
+                const bool kb = (keepmask[j] >> b) & 1u;
+                const uint64_t tb = __ballot(kb);
+                if (want_idx && kb) store_dev(&a.idx_out[(int64_t)b * a.K + k0 + tbase[b] + lanes_below(tb)], k);
+                tbase[b] += __popcll(tb);
+            }
+        }
+    }
+    if (tile == 0 && tid == 0) {
+        store_dev(&a.seg_cnt[a.B * a.Sl + split], cnt);  // union
+        if (per_token) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+                if (b < a.B) store_dev(&a.seg_cnt[b * a.Sl + split], ttotal[b]);
+        }
+    }
+    __syncthreads();
+    return cnt;
+}
+
 // ---------------------------------------------------------------------------------------------- list input
 // Lists of the gated product (fused SwiGLU block), one segment per 64 channels, BT = tokens rounded up to
 // a power of two:
@@ -641,6 +759,7 @@ inline size_t lds_bytes(int Kc, int floats_per_entry, size_t red_bytes) {
 
 // Choose the K split of a launch: fills a.T, a.Kc, a.S.  `tile` = columns per workgroup, `kc` = requested
 // rows per workgroup (0 = about one workgroup per compute unit).  Returns a scap_status.
-int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced);
+// `lds_budget` = LDS bytes one workgroup may use for its list.
+int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced, size_t lds_budget = 64 * 1024);
 
 }  // namespace scap

@@ -95,11 +95,17 @@ int launch_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t 
                         hipStream_t stream);
 
 // Batched tokens over bf16 or int8 weights on the matrix cores: possible from kMfmaMinTokens tokens on (the
-// workspace then carries the union lists), chosen by default from kMfmaAutoTokens on -- at 4 tokens the
-// single-launch vector kernel is still faster (measured 29 vs 35 us on 14336 x 4096).
+// workspace then carries the union lists of the two-launch form), chosen by default from kMfmaAutoTokens
+// (bf16) / kMfmaAutoTokensI8 (int8) tokens on.  Below that the vector kernel is as fast or faster (bf16, 4
+// tokens on 14336 x 4096: 28.9 us against 28.3 us; 2 tokens: 25.1 against 27.5); with int8 weights the vector
+// kernel is bound by its per-element converts from 3 tokens on (34.6 us against 20.7 us).
 constexpr int kMfmaMinTokens = 2;
 constexpr int kMfmaAutoTokens = 5;
+constexpr int kMfmaAutoTokensI8 = 3;
 int launch_gemm_mfma(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+// The same in one launch: each workgroup compacts its own inputs into LDS (up to 160 KB on gfx950).
+// SCAP_ERR_SHAPE when the input is too long to split into LDS-sized pieces.
+int launch_gemm_inline(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
 
 // Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).
 int launch_zero_words(int32_t* p, size_t n, hipStream_t stream);

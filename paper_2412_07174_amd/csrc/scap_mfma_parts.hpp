@@ -1,0 +1,139 @@
+// Pieces shared by the kernels that run the gathered product on the matrix cores (gfx950 MFMA):
+//
+//     Y[16 tokens, 16 columns] += D[16 tokens, 16 rows] * W[16 rows, 16 columns]     v_mfma_f32_16x16x16_bf16
+//
+// Operand layout without any transposition.  For this instruction lane l holds
+//     A[m = l%16][k = 4*(l/16) + j],   B[k = 4*(l/16) + j][n = l%16],   C[m = 4*(l/16) + i][n = l%16],  i,j = 0..3.
+// The weights are K-major, so a lane cannot fetch four rows of one column in one access; but it can fetch
+// 16 bytes = ELEMS columns of one row.  Lane l loads columns ELEMS*(l%16) .. of the four list rows 4*(l/16) + j
+// of a 16-row block, and element e of those four vectors is exactly this lane's B operand of the MFMA that
+// produces columns {ELEMS*n + e}.  The C registers of lane l then hold tokens 4*(l/16)+i and ELEMS
+// consecutive columns.  The A operand (centred values of token l%16 at rows 4*(l/16)+j) is split into a
+// bf16 head and a bf16 tail (d = hi + lo) and fed through two MFMAs, so the bf16 rounding of d costs about
+// 2^-17 relative instead of 2^-9.  int8 weights are widened exactly to bf16 in registers.
+#pragma once
+
+#include "scap_gemv_parts.hpp"
+
+namespace scap {
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kMfmaTile = 128;    // columns per workgroup with bf16 weights (16 lanes x 8); int8: 256
+constexpr int kMfmaTokens = 16;   // M of the MFMA; tokens beyond B are zero rows
+constexpr int kMfmaBlock = 16;    // list rows per MFMA (K of the MFMA)
+constexpr int kCompactWaves = 8;
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float v) {
+    const uint32_t u = __float_as_uint(v);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;  // finite or infinite input (NaN never reaches the list)
+}
+
+// 4 centred values -> bf16 head and tail operands
+__device__ __forceinline__ void split_bf16x4(const float4& d, s16x4_t& hi, s16x4_t& lo) {
+    const float v[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t h = bf16_rne_bits(v[j]);
+        const float hf = __uint_as_float(h << 16);
+        const float rest = ((h & 0x7FFFu) != 0x7F80u) ? v[j] - hf : 0.f;  // an infinite head has no tail
+        hi[j] = (short)h;
+        lo[j] = (short)bf16_rne_bits(rest);
+    }
+}
+
+// One 16-row block: r[j] = this lane's 16 bytes of list row 4*(l/16)+j (zeros for a slot past the list),
+// a_hi / a_lo = its A operand.  acc[e] += A * B_e for the ELEMS column elements.
+template <int WDT>
+__device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_hi, s16x4_t a_lo, const uint4 (&r)[4]) {
+    constexpr int ELEMS = Vec<WDT>::kElems;
+    const uint32_t q0[4] = {r[0].x, r[0].y, r[0].z, r[0].w};
+    const uint32_t q1[4] = {r[1].x, r[1].y, r[1].z, r[1].w};
+    const uint32_t q2[4] = {r[2].x, r[2].y, r[2].z, r[2].w};
+    const uint32_t q3[4] = {r[3].x, r[3].y, r[3].z, r[3].w};
+#pragma unroll
+    for (int e = 0; e < ELEMS; ++e) {
+        uint32_t lo01, lo23;  // rows (0,1) and (2,3) of column element e, packed as two bf16
+        if constexpr (WDT == kBF16) {
+            const int q = e >> 1;
+            if ((e & 1) == 0) {
+                lo01 = (q0[q] & 0xFFFFu) | (q1[q] << 16);
+                lo23 = (q2[q] & 0xFFFFu) | (q3[q] << 16);
+            } else {
+                lo01 = (q0[q] >> 16) | (q1[q] & 0xFFFF0000u);
+                lo23 = (q2[q] >> 16) | (q3[q] & 0xFFFF0000u);
+            }
+        } else {
+            // byte e of each row, sign-extended, as a float: its low 16 bits are zero (|v| <= 128)
+            const int q = e >> 2, sh = 24 - 8 * (e & 3);
+            const uint32_t f0 = __float_as_uint((float)(((int)(q0[q] << sh)) >> 24));
+            const uint32_t f1 = __float_as_uint((float)(((int)(q1[q] << sh)) >> 24));
+            const uint32_t f2 = __float_as_uint((float)(((int)(q2[q] << sh)) >> 24));
+            const uint32_t f3 = __float_as_uint((float)(((int)(q3[q] << sh)) >> 24));
+            lo01 = (f0 >> 16) | f1;
+            lo23 = (f2 >> 16) | f3;
+        }
+        union { uint32_t u32[2]; s16x4_t v; } bop;
+        bop.u32[0] = lo01;
+        bop.u32[1] = lo23;
+        acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bop.v, acc[e], 0, 0, 0);
+        acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop.v, acc[e], 0, 0, 0);
+    }
+}
+
+// Every wavefront holds a full [16 tokens x TILE columns] tile of sums in the same lane layout
+// (acc[e][i] = token 4*(l/16) + i, column ELEMS*(l%16) + e of the tile), so they are added as a binary tree over
+// the wavefronts through LDS (32 KB at s_tree), CH accumulators at a time: the upper half of the surviving
+// wavefronts writes, the lower half adds lane by lane (conflict-free 16-byte accesses, every lane busy, fixed
+// order), until wavefront 0 holds the workgroup's sums and stores them straight from its registers.
+// Ends with a barrier.
+template <int WDT, int WAVES>
+__device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, int split,
+                                                      f32x4_t* __restrict__ acc, float* s_red) {
+    constexpr int ELEMS = Vec<WDT>::kElems;
+    constexpr int TILE = 16 * ELEMS;
+    constexpr int CH = (WAVES <= 8) ? 8 : 4;  // (WAVES/2) * CH * 64 lanes * 16 bytes = 32 KB of LDS
+    static_assert(ELEMS % CH == 0, "accumulators are handed over in whole chunks");
+    const int tid = threadIdx.x;
+    const int w = uniform(tid >> 6);
+    const int lane = tid & 63;
+    const int cg = lane & 15, kg = lane >> 4;
+    f32x4_t* s_tree = reinterpret_cast<f32x4_t*>(s_red);
+#pragma unroll
+    for (int c0 = 0; c0 < ELEMS; c0 += CH) {
+#pragma unroll
+        for (int half = WAVES / 2; half >= 1; half >>= 1) {
+            __syncthreads();  // the buffer is free (previous level or chunk has been read)
+            if (w >= half && w < 2 * half) {
+#pragma unroll
+                for (int e = 0; e < CH; ++e) s_tree[((w - half) * CH + e) * kWave + lane] = acc[c0 + e];
+            }
+            __syncthreads();
+            if (w < half) {
+#pragma unroll
+                for (int e = 0; e < CH; ++e) acc[c0 + e] += s_tree[(w * CH + e) * kWave + lane];
+            }
+        }
+        if (w == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int b = 4 * kg + i;
+                if (b < a.B) {
+#pragma unroll
+                    for (int v = 0; v < CH / 4; ++v) {
+                        const float4 sum = make_float4(acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i],
+                                                       acc[c0 + 4 * v + 3][i]);
+                        const int g = (cg * ELEMS + c0) / 4 + v;
+                        // one split: this is the finished value, and the group's constants are loaded here
+                        emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, sum, nullptr,
+                                              a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+}
+
+}  // namespace scap

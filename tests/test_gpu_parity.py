@@ -209,22 +209,24 @@ def test_headline_layer_three_sparsities_and_dense():
 
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
-@pytest.mark.parametrize("path", ["auto", "vector", "matrix"])
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix", "lists"])
 @pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 13, 16])
 def test_batched_tokens_moderate(B, path):
-    """auto: bf16 weights and B >= 5 run on the matrix cores; vector / matrix: the batch forced onto one kernel."""
+    """auto: the library's choice; vector / matrix / lists: the batch forced onto the vector kernel, the
+    single-launch matrix-core kernel, or the two-launch matrix-core form with its lists in the workspace."""
     K, N = 2500, 1032
     W = wl.weights(K, N, 501, BF16)
     layer = Layer(W, BF16, B=16)
     X = wl.swiglu(B, K, 502 + B, BF16)
     bf = np.random.default_rng(503).standard_normal(N).astype(np.float32)
-    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16)}[path]
+    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16), "lists": (0, 0, 0, 1)}[path]
     for tau in (0.0, 0.15, 0.8, 50.0):
         say(f"batched B={B} path={path} tau={tau}")
         check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"B={B} {path} tau={tau}")
 
 
-def test_batched_matrix_core_edge_cases():
+@pytest.mark.parametrize("lanes", [16, 1])
+def test_batched_matrix_core_edge_cases(lanes):
     """Ragged list lengths (not multiples of the 16-row MFMA block), infinities, one split and many splits."""
     K, N = 1000, 264
     W = wl.weights(K, N, 511, BF16)
@@ -238,8 +240,8 @@ def test_batched_matrix_core_edge_cases():
     for rows in (0, 64, 128, 832):
         for tau in (0.0, 0.3, 1.5, 2.5):
             say(f"matrix-core edge rows={rows} tau={tau}")
-            check_against_oracle(layer, X, BF16, 0.01, tau, None, cfg=(0, rows, 0, 16),
-                                 what=f"mfma rows={rows} tau={tau}")
+            check_against_oracle(layer, X, BF16, 0.01, tau, None, cfg=(0, rows, 0, lanes),
+                                 what=f"mfma lanes={lanes} rows={rows} tau={tau}")
 
 
 @pytest.mark.parametrize("B", [4, 16])
@@ -283,7 +285,7 @@ def test_int8_weights(K, N, B):
     assert np.allclose(bf.cpu().numpy(), bf_want, rtol=1e-5, atol=1e-5)
 
 
-@pytest.mark.parametrize("path", ["auto", "vector", "matrix"])
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix", "lists"])
 @pytest.mark.parametrize("B", [2, 5, 8, 13, 16])
 def test_int8_batched_tokens(B, path):
     """int8 weights with several tokens: the matrix-core kernel widens int8 to bf16 exactly (auto from 5 tokens)."""
@@ -292,7 +294,7 @@ def test_int8_batched_tokens(B, path):
     layer = Layer(q, I8, col_scale_bits=scale, B=16)
     X = wl.swiglu(B, K, 612 + B, BF16)
     bf = np.random.default_rng(613).standard_normal(N).astype(np.float32)
-    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16)}[path]
+    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16), "lists": (0, 0, 0, 1)}[path]
     for tau in (0.0, 0.15, 0.8, 50.0):
         say(f"int8 batched B={B} path={path} tau={tau}")
         check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"int8 B={B} {path} tau={tau}")
