@@ -199,8 +199,7 @@ def run_suite(args, torch, scap, wl, dev):
     run_block("llama2_7b_ffn", 4096, 11008, 4096, (0.5,))
 
     # Mixture-of-experts feed-forward (config 5): 8 int8 experts, top-2 routing from seeded logits, the tokens
-    # of a step grouped per expert; an expert's group goes through the fused block (up to 4 tokens) or through
-    # separate calls.  Routing is done beforehand on the host (it is not part of the library); gathering the
+    # of a step grouped per expert; an expert's group goes through the fused block or through separate calls.  Routing is done beforehand on the host (it is not part of the library); gathering the
     # group's tokens and the gate-weighted scatter-add are torch ops inside the timed region.
     moe_rows = []
 
@@ -217,7 +216,7 @@ def run_suite(args, torch, scap, wl, dev):
         X = dev16(site.draw(256, site.seed_test), wl.BF16)
         calib = dev16(site.draw(128, site.seed_calib), wl.BF16)
         ws = scap.Workspace(K, N, 8, F=F)
-        wsb = scap.Workspace(K, N, 4, F=F)
+        wsb = scap.Workspace(K, N, 8, F=F)
         m_x, tau_x = scap.calibrate(calib, 0.4, scap.MODE_MEDIAN, workspace=ws)
         bgu = [scap.fold_bias(Wgu[e], m_x, None, col_scale=sgu[e], workspace=ws) for e in range(E)]
         ygu = torch.empty((8, 2 * F), dtype=torch.float32, device=dev)
@@ -254,7 +253,7 @@ def run_suite(args, torch, scap, wl, dev):
                     n = src.numel()
                     xg = X.index_select(0, src)
                     y = ybuf[:n]
-                    if sparse and fused and n <= 4:
+                    if sparse and fused:
                         scap.swiglu_block(Wgu[e], Wdn[e], xg, m_x, tau_x, bgu[e], 0.0, tau_z, None, gu_scale=sgu[e],
                                           down_scale=sdn[e], y=y, workspace=wsb)
                     elif sparse:

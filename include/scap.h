@@ -189,7 +189,7 @@ int scap_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F,
 size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B);
 
 /*
- * ASYNC.  SwiGLU feed-forward block of 1 to 4 tokens (Appendix B, Alg. 2; each scap_fc in the centred form of
+ * ASYNC.  SwiGLU feed-forward block of 1 to 16 tokens (Appendix B, Alg. 2; each scap_fc in the centred form of
  * Alg. 3):   z = scap_fc(x; W_up) * silu(scap_fc(x; W_gate)),   y = scap_fc(z; W_down)
  * in two launches.  The first reads the kept rows of the interleaved gate|up matrix; the workgroup that
  * completes a column tile forms z in fp32 (silu(t) = t / (1 + exp(-t))), subtracts m_z, applies the strict
@@ -197,8 +197,9 @@ size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B);
  * its input.  z is never rounded to 16 bits.
  *   W_gu, gu_scale   DEVICE  [K, 2F] from scap_pack_gate_up (and its packed fp16 scales for int8, else NULL).
  *   W_down, down_scale DEVICE [F, N] K-major (scales for int8, else NULL); same dtype wdt as W_gu.
- *   x                DEVICE  [B, K], dtype xdt.   B <= 4 (larger batches: SCAP_ERR_UNIMPL); each token has its
- *                            own masks, a weight row is read when any token keeps its channel (Appendix C).
+ *   x                DEVICE  [B, K], dtype xdt.   B <= 16 over bf16 or int8 weights (matrix cores from 5 tokens,
+ *                            int8 from 3), B <= 4 over fp16 weights (beyond: SCAP_ERR_UNIMPL); each token has
+ *                            its own masks, a weight row is read when any token keeps its channel (Appendix C).
  *   m_x, tau_x       constants of the block input;  b_gu_fused  DEVICE fp32 [2F] packed fused bias or NULL
  *                    (scap_fold_bias on W_gu with the packed bias gives it).
  *   m_z, tau_z       constants of the gated product;  b_down_fused  DEVICE fp32 [N] or NULL.

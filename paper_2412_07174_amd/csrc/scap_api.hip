@@ -190,7 +190,7 @@ size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B) {
     if (K < 1 || F < 1 || N < 1 || B < 1 || B > SCAP_MAX_TOKENS) return 0;
     if (K > kMaxK || F > kMaxGated || N > kMaxN) return 0;
     const size_t segs = (size_t)((F + 63) / 64);
-    const size_t bt = B <= 1 ? 1 : (B == 2 ? 2 : 4);  // larger batches are refused by the block itself
+    const size_t bt = (size_t)block_token_slots(B);
     size_t bytes = block_list_offset(F, N, B) + segs * 64 * 4 * (1 + bt) + align_up(segs * 4 * (1 + bt), 256);
     const size_t a = scap_workspace_bytes(K, 2 * F, B), b = scap_workspace_bytes(F, N, B);
     if (bytes < a) bytes = a;
@@ -212,7 +212,7 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
     if (!x || !y) return SCAP_ERR_NULL;
     if (!act_dtype_ok(xdt)) return SCAP_ERR_DTYPE;
     if (B < 1 || B > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
-    if (B > kBlockMaxTokens) return SCAP_ERR_UNIMPL;
+    if (B > kBlockVectorTokens && wdt == SCAP_F16) return SCAP_ERR_UNIMPL;
     if (!aligned16(x) || !aligned16(y) || (b_gu_fused && !aligned16(b_gu_fused)) ||
         (b_down_fused && !aligned16(b_down_fused)) || (z_out && !aligned16(z_out)))
         return SCAP_ERR_ALIGN;
@@ -246,7 +246,7 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
     up.m2 = m_z;
     up.tau2 = tau_z;
     up.z_out = z_out;
-    const size_t bt = B <= 1 ? 1 : (B == 2 ? 2 : 4);
+    const size_t bt = (size_t)block_token_slots(B);
     up.zl_d = reinterpret_cast<float*>(lists);
     up.zl_idx = reinterpret_cast<int32_t*>(lists + segs * 256 * bt);
     up.zl_cnt = reinterpret_cast<int32_t*>(lists + segs * 256 * (bt + 1));

@@ -23,14 +23,19 @@ constexpr int kInlineWaves = 8;
 // chunks of 64 channels a wavefront compacts from registers: 5 x 16 or 8 x 4 values per lane
 constexpr int inline_max_chunks(int bt) { return bt == 16 ? 5 : 8; }
 
-template <int WDT, int BT>
+constexpr int kTreeFloats = 32 * 1024 / 4;  // LDS floats of the reduction tree (and of the final reduction)
+
+// FUSE (kFusePlain / kFuseSwiglu / kFuseList) as in the vector kernel: where the inputs come from and what the
+// tile's last arrival does with the finished columns (the two launches of the fused SwiGLU block, Alg. 2).
+template <int WDT, int BT, int FUSE>
 __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_kernel(const GemvArgs a) {
     constexpr int WAVES = kInlineWaves;
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr int TILE = 16 * ELEMS;
 
     extern __shared__ uint4 smem_raw[];
-    const Lds L = carve_lds<WAVES, BT>(reinterpret_cast<char*>(smem_raw), a.Kc);
+    Lds L = carve_lds<WAVES, BT>(reinterpret_cast<char*>(smem_raw), a.Kc);
+    if constexpr (FUSE == kFuseSwiglu) L.fin = L.red + kTreeFloats;  // behind both uses of the reduction buffer
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
     const int lane = tid & 63;
@@ -41,7 +46,11 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_kernel(const 
     const ColConst mine = load_col_const<WDT, TILE>(a, tile, tid % (TILE / 4));
 
     // ------------------------------------------------------------------ 1. centre, threshold, compact
-    const int cnt = compact_inputs_wide<WAVES, BT, inline_max_chunks(BT)>(a, tile, split, L);
+    int cnt;
+    if constexpr (FUSE == kFuseList)
+        cnt = gather_lists<WAVES, BT>(a, split, L);
+    else
+        cnt = compact_inputs_wide<WAVES, BT, inline_max_chunks(BT)>(a, tile, split, L);
     const int n_blocks = (cnt + kMfmaBlock - 1) / kMfmaBlock;
 
     // ------------------------------------------------------------------ 2. stream the kept rows
@@ -116,52 +125,99 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_kernel(const 
 
     // ------------------------------------------------------------------ 3. add the wavefronts' sums
     const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
-    reduce_waves_and_emit<WDT, WAVES>(a, pbuf, tile, split, acc, L.red);  // starts with a barrier: the list is done with
+    reduce_waves_and_emit<WDT, WAVES, FUSE>(a, pbuf, tile, split, acc, L.red, L.fin);  // starts with a barrier: the list is done with
 
     // ------------------------------------------------------------------ 4. last arrival finishes the tile
-    finish_tile<WDT, WAVES, TILE, BT>(a, pbuf, tile, L, mine);
+    finish_tile<WDT, WAVES, TILE, BT, FUSE>(a, pbuf, tile, L, mine);
 }
 
-template <int WDT, int BT>
+template <int WDT, int BT, int FUSE>
 static int launch_inline(const GemvArgs& a, size_t lds, hipStream_t stream) {
+    if (lds > kInlineLdsBudget) return SCAP_ERR_SHAPE;
     if (lds > 64 * 1024) {
         // more dynamic LDS than the default limit: ask once per kernel (the call is cheap and idempotent)
         static std::once_flag once;
         static hipError_t attr_rc = hipSuccess;
         std::call_once(once, [] {
-            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_inline_kernel<WDT, BT>),
+            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_inline_kernel<WDT, BT, FUSE>),
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kInlineLdsBudget);
         });
         if (attr_rc != hipSuccess) return SCAP_ERR_HIP;
     }
-    hipLaunchKernelGGL((gemm_inline_kernel<WDT, BT>), dim3((unsigned)(a.S * a.T)), dim3(kInlineWaves * kWave), lds, stream, a);
+    hipLaunchKernelGGL((gemm_inline_kernel<WDT, BT, FUSE>), dim3((unsigned)(a.S * a.T)), dim3(kInlineWaves * kWave), lds,
+                       stream, a);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
+}
+
+template <int FUSE>
+static int launch_inline_any(const GemvArgs& a, int wdt, int bt, size_t lds, hipStream_t stream) {
+    if (wdt == kBF16) return bt == 4 ? launch_inline<kBF16, 4, FUSE>(a, lds, stream) : launch_inline<kBF16, 16, FUSE>(a, lds, stream);
+    if (wdt == kI8) return bt == 4 ? launch_inline<kI8, 4, FUSE>(a, lds, stream) : launch_inline<kI8, 16, FUSE>(a, lds, stream);
+    return SCAP_ERR_CONFIG;
+}
+
+// Plan one launch: token slots, rows per workgroup (bounded by LDS and, for the input prologue, by the
+// registers that hold a wavefront's chunks), LDS bytes.
+static int plan_inline(GemvArgs& a, int wdt, int kc, bool kc_forced, int fuse, int* bt_out, size_t* lds_out) {
+    if (wdt != kBF16 && wdt != kI8) return SCAP_ERR_CONFIG;
+    if (a.B < 1 || a.B > kMfmaTokens) return SCAP_ERR_CONFIG;
+    const int bt = a.B <= 4 ? 4 : 16;
+    const int tile_cols = wdt == kI8 ? 2 * kMfmaTile : kMfmaTile;
+    size_t budget = kInlineLdsBudget;
+    int kc_cap = kMaxSplits * kWave * 1024;  // no cap
+    if (fuse == kFuseList) {
+        kc_cap = 64 * kWave;  // gather_lists: at most 64 segments of 64 channels per workgroup
+    } else {
+        kc_cap = kInlineWaves * kWave * inline_max_chunks(bt);
+    }
+    const size_t by_cap = kHdrBytes + (size_t)kc_cap * 4 * (1 + bt);
+    if (by_cap < budget) budget = by_cap;
+    const int rc = plan_splits(a, tile_cols, bt, kc, kc_forced, budget);
+    if (rc != SCAP_OK) return rc;
+    if (a.Kc > kc_cap) return SCAP_ERR_SHAPE;
+    size_t red = (size_t)kTreeFloats * 4;
+    if (fuse == kFuseSwiglu) red += (size_t)bt * tile_cols * 4;
+    *bt_out = bt;
+    *lds_out = lds_bytes(a.Kc, bt, red);
+    return SCAP_OK;
 }
 
 int launch_gemm_inline(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipStream_t stream) {
     GemvArgs a = a_in;
-    if (wdt != kBF16 && wdt != kI8) return SCAP_ERR_CONFIG;
-    if (a.B < kMfmaMinTokens || a.B > kMfmaTokens) return SCAP_ERR_CONFIG;
+    if (a.B < kMfmaMinTokens) return SCAP_ERR_CONFIG;
     int kc = 0;
     if (cfg) {
         if (cfg->rows_per_group) kc = cfg->rows_per_group;
         if (kc < 0 || (kc % kWave) != 0) return SCAP_ERR_CONFIG;
         if (cfg->waves_per_group && cfg->waves_per_group != kInlineWaves) return SCAP_ERR_CONFIG;
     }
-    const int bt = a.B <= 4 ? 4 : 16;
-    const int tile_cols = wdt == kI8 ? 2 * kMfmaTile : kMfmaTile;
-    // rows per workgroup: what LDS holds and what the prologue's registers hold
-    size_t budget = kHdrBytes + (size_t)kInlineWaves * kWave * inline_max_chunks(bt) * 4 * (1 + bt);
-    if (budget > kInlineLdsBudget) budget = kInlineLdsBudget;
-    const int rc = plan_splits(a, tile_cols, bt, kc, kc != 0, budget);
+    int bt = 0;
+    size_t lds = 0;
+    const int rc = plan_inline(a, wdt, kc, kc != 0, kFusePlain, &bt, &lds);
     if (rc != SCAP_OK) return rc;
-    if (a.Kc > kInlineWaves * kWave * inline_max_chunks(bt)) return SCAP_ERR_SHAPE;
     a.Kl = a.Kc;
     a.Sl = a.S;
-    const size_t lds = lds_bytes(a.Kc, bt, (size_t)32 * 1024);
-    if (lds > kInlineLdsBudget) return SCAP_ERR_SHAPE;
-    if (wdt == kBF16) return bt == 4 ? launch_inline<kBF16, 4>(a, lds, stream) : launch_inline<kBF16, 16>(a, lds, stream);
-    return bt == 4 ? launch_inline<kI8, 4>(a, lds, stream) : launch_inline<kI8, 16>(a, lds, stream);
+    return launch_inline_any<kFusePlain>(a, wdt, bt, lds, stream);
+}
+
+// The two launches of the fused SwiGLU block on the matrix cores (see scap_swiglu.hip for the vector form).
+int launch_swiglu_block_inline(const GemvArgs& up_in, const GemvArgs& dn_in, int wdt, hipStream_t stream) {
+    GemvArgs up = up_in, dn = dn_in;
+    int bt_up = 0, bt_dn = 0;
+    size_t lds_up = 0, lds_dn = 0;
+    int rc = plan_inline(up, wdt, 0, false, kFuseSwiglu, &bt_up, &lds_up);
+    if (rc != SCAP_OK) return rc;
+    up.Kl = up.Kc;
+    up.Sl = up.S;
+    rc = plan_inline(dn, wdt, 0, false, kFuseList, &bt_dn, &lds_dn);
+    if (rc != SCAP_OK) return rc;
+    dn.Kl = kWave;
+    dn.Sl = (dn.K + kWave - 1) / kWave;
+    const size_t tables = kHdrBytes + (size_t)dn.Sl * 4;  // offsets of every segment (tile 0's last arrival)
+    if (lds_dn < tables) lds_dn = tables;
+    rc = launch_inline_any<kFuseSwiglu>(up, wdt, bt_up, lds_up, stream);
+    if (rc != SCAP_OK) return rc;
+    return launch_inline_any<kFuseList>(dn, wdt, bt_dn, lds_dn, stream);
 }
 
 }  // namespace scap

@@ -87,7 +87,10 @@ int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStrea
 
 // Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
 // `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.
-constexpr int kBlockMaxTokens = 4;  // tokens per fused-block call (the vector kernel's range)
+constexpr int kBlockVectorTokens = 4;  // tokens per fused-block call on the vector kernel (any weight dtype)
+constexpr int kBlockMaxTokens = 16;    // ... on the matrix cores (bf16 and int8 weights)
+// token slots of the block's lists for B tokens
+inline int block_token_slots(int64_t B) { return B <= 1 ? 1 : (B == 2 ? 2 : (B <= 4 ? 4 : 16)); }
 int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
 
 // Interleave two [rows, F] arrays of `elem_bytes`-byte elements in groups of 4 columns: out[rows, 2F].
@@ -106,6 +109,8 @@ int launch_gemm_mfma(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hip
 // The same in one launch: each workgroup compacts its own inputs into LDS (up to 160 KB on gfx950).
 // SCAP_ERR_SHAPE when the input is too long to split into LDS-sized pieces.
 int launch_gemm_inline(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+// The fused block's two launches on the same kernel (bf16 / int8, up to 16 tokens).
+int launch_swiglu_block_inline(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
 
 // Fill `n` int32 words with zero using a kernel (safe to record into a HIP graph).
 int launch_zero_words(int32_t* p, size_t n, hipStream_t stream);

@@ -88,9 +88,10 @@ __device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_
 // wavefronts writes, the lower half adds lane by lane (conflict-free 16-byte accesses, every lane busy, fixed
 // order), until wavefront 0 holds the workgroup's sums and stores them straight from its registers.
 // Ends with a barrier.
-template <int WDT, int WAVES>
+// (FUSE / s_fin: see finish_columns -- with one split the sums are final and may go to the gating step)
+template <int WDT, int WAVES, int FUSE = kFusePlain>
 __device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, int split,
-                                                      f32x4_t* __restrict__ acc, float* s_red) {
+                                                      f32x4_t* __restrict__ acc, float* s_red, float* s_fin = nullptr) {
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr int TILE = 16 * ELEMS;
     constexpr int CH = (WAVES <= 8) ? 8 : 4;  // (WAVES/2) * CH * 64 lanes * 16 bytes = 32 KB of LDS
@@ -126,8 +127,8 @@ __device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgp
                                                        acc[c0 + 4 * v + 3][i]);
                         const int g = (cg * ELEMS + c0) / 4 + v;
                         // one split: this is the finished value, and the group's constants are loaded here
-                        emit_group<WDT, TILE>(a, pbuf, tile, split, b, g, sum, nullptr,
-                                              a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
+                        emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, sum, s_fin,
+                                                    a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
                     }
                 }
             }

@@ -69,11 +69,19 @@ template <int WDT>
 static int launch_block_wdt(const GemvArgs& up, const GemvArgs& down, hipStream_t stream) {
     if (up.B == 1) return launch_block<WDT, 1>(up, down, stream);
     if (up.B == 2) return launch_block<WDT, 2>(up, down, stream);
-    if (up.B <= kBlockMaxTokens) return launch_block<WDT, 4>(up, down, stream);
+    if (up.B <= kBlockVectorTokens) return launch_block<WDT, 4>(up, down, stream);
     return SCAP_ERR_UNIMPL;
 }
 
 int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream) {
+    // Matrix cores: more than 4 tokens (bf16, int8), and int8 from 3 tokens on, where the vector kernel is
+    // bound by its per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
+    // 3-4 tokens, so the choice only has to be the same for both launches.
+    const bool matrix = (wdt == kBF16 || wdt == kI8) && (up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3));
+    if (matrix) {
+        const int rc = launch_swiglu_block_inline(up, down, wdt, stream);
+        if (rc != SCAP_ERR_SHAPE || up.B > kBlockVectorTokens) return rc == SCAP_ERR_SHAPE ? SCAP_ERR_UNIMPL : rc;
+    }
     switch (wdt) {
         case kF16: return launch_block_wdt<kF16>(up, down, stream);
         case kBF16: return launch_block_wdt<kBF16>(up, down, stream);

@@ -2,7 +2,8 @@
 C ABI against the CPU oracle on the same seeded inputs.
 
 The second pruner decides on a floating-point value (the gated product z) that the two sides sum in different
-orders, so a channel whose |z - m_z| lies within a rounding-sized band of tau_z may legitimately fall either way.
+orders (and, on the matrix cores, with the centred inputs carried as bf16 head + tail), so a channel whose
+|z - m_z| lies within a rounding-sized band of tau_z (3e-4 * max(1, |z|)) may legitimately fall either way.
 The tests require: every channel outside the band decided exactly as the oracle decides it; the kept list
 ascending, duplicate-free and consistent with its count; z within rounding of the oracle's; and y within the
 usual bar of the oracle's y for the decisions actually taken (the oracle's y plus/minus the band channels'
@@ -116,12 +117,13 @@ class Block:
     def compare(self, got, want, m_z, tau_z, what):
         zo = want["z"].astype(np.float64)
         fin = np.isfinite(zo)
-        tol = 2e-5 + 2e-5 * np.abs(zo[fin])
+        # fp32 sums in another order, or (matrix cores) centred values carried as bf16 head + tail, 2^-17 relative
+        tol = 1e-4 + 1e-4 * np.abs(zo[fin])
         assert np.all(np.abs(got["z"][fin] - zo[fin]) <= tol), f"{what}: z off by {np.abs(got['z'][fin] - zo[fin]).max()}"
         # decisions: exact outside the band
         d = (want["z"] - np.float32(m_z)).astype(np.float32)
         margin = np.abs(np.abs(d.astype(np.float64)) - float(np.float32(tau_z)))
-        band = margin <= 1e-4 * np.maximum(1.0, np.abs(zo))
+        band = margin <= 3e-4 * np.maximum(1.0, np.abs(zo))
         gi = got["idx_z"]
         assert np.all(np.diff(gi) > 0), f"{what}: kept list not strictly ascending"
         assert gi.size == 0 or (gi[0] >= 0 and gi[-1] < self.F)
@@ -203,7 +205,7 @@ def test_small_blocks_int8(K, F, N):
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
 @pytest.mark.parametrize("dt", [BF16, I8])
-@pytest.mark.parametrize("B", [2, 3, 4])
+@pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 13, 16])
 def test_batched_blocks(B, dt):
     K, F, N = 1000, 2056, 1040
     blk = Block(K, F, N, dt, seed=840 + B, B=B)
@@ -256,13 +258,15 @@ def test_block_is_bit_reproducible_and_workspace_is_reusable():
 
 def test_block_argument_errors():
     K, F, N = 64, 64, 16
-    blk = Block(K, F, N, BF16, seed=920)
-    x = to_dev(wl.laplace(5, K, 921, BF16), BF16)
+    blk16 = Block(K, F, N, F16, seed=919)
+    x16 = to_dev(wl.laplace(5, K, 921, F16), F16)
     y = torch.empty((5, N), dtype=torch.float32, device="cuda")
     big = scap.Workspace(K, N, 5, F=F)
     with pytest.raises(scap.ScapError) as e:
-        scap.swiglu_block(blk.W_gu, blk.W_down, x, 0.0, 0.1, None, 0.0, 0.1, None, y=y, workspace=big)
-    assert e.value.status == -8      # five tokens: not implemented
+        scap.swiglu_block(blk16.W_gu, blk16.W_down, x16, 0.0, 0.1, None, 0.0, 0.1, None, y=y, workspace=big)
+    assert e.value.status == -8      # five tokens over fp16 weights: not implemented (no matrix-core form)
+    blk = Block(K, F, N, BF16, seed=920)
+    x = to_dev(wl.laplace(5, K, 921, BF16), BF16)
     with pytest.raises(scap.ScapError) as e:
         scap.swiglu_block(blk.W_gu, blk.W_down, x[0], 0.0, -1.0, None, 0.0, 0.1, None, workspace=blk.ws)
     assert e.value.status == -5
