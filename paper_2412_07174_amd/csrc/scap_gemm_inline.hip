@@ -12,7 +12,7 @@
 // The column tile is narrow (128 columns for bf16, 256 for int8), so the prologue is repeated by more
 // workgroups than in the vector kernel; it is loads from L2 and a few hundred ALU operations per thread
 // and costs less than the kernel boundary it replaces.
-#include <mutex>
+#include <atomic>
 
 #include "scap_mfma_parts.hpp"
 
@@ -135,14 +135,17 @@ template <int WDT, int BT, int FUSE>
 static int launch_inline(const GemvArgs& a, size_t lds, hipStream_t stream) {
     if (lds > kInlineLdsBudget) return SCAP_ERR_SHAPE;
     if (lds > 64 * 1024) {
-        // more dynamic LDS than the default limit: ask once per kernel (the call is cheap and idempotent)
-        static std::once_flag once;
-        static hipError_t attr_rc = hipSuccess;
-        std::call_once(once, [] {
-            attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_inline_kernel<WDT, BT, FUSE>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kInlineLdsBudget);
-        });
-        if (attr_rc != hipSuccess) return SCAP_ERR_HIP;
+        // more dynamic LDS than the default limit: ask once per kernel and device
+        constexpr int kMaxDevices = 64;
+        static std::atomic<bool> asked[kMaxDevices];
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SCAP_ERR_HIP;
+        if (!asked[dev].load(std::memory_order_acquire)) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_inline_kernel<WDT, BT, FUSE>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kInlineLdsBudget) != hipSuccess)
+                return SCAP_ERR_HIP;
+            asked[dev].store(true, std::memory_order_release);
+        }
     }
     hipLaunchKernelGGL((gemm_inline_kernel<WDT, BT, FUSE>), dim3((unsigned)(a.S * a.T)), dim3(kInlineWaves * kWave), lds,
                        stream, a);
