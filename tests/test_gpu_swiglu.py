@@ -324,3 +324,39 @@ def test_random_blocks():
         tau_z = float(np.quantile(zs, rng.choice([0.0, 0.4, 0.9])))
         say(f"random block {case}: dt={dt} K={K} F={F} N={N} B={B} tau_x={tau_x} tau_z={tau_z:.4g}")
         blk.check_batch(X, xdt, 0.05, tau_x, None, None, 0.001, tau_z, None, f"random block {case}")
+
+
+def test_mixture_of_experts_layer_grouped_by_expert():
+    """Config-5 style layer at small size: 8 int8 experts, top-2 routing from seeded logits (harness level, the same
+    on both sides), tokens grouped per expert on the GPU side (each group one fused block call with its own batch
+    size), one token at a time on the oracle side; outputs combined with the gate weights."""
+    K, F, N, E, B = 256, 512, 256, 8, 8
+    experts = [Block(K, F, N, I8, seed=7000 + 10 * e, B=B) for e in range(E)]
+    X = wl.laplace(B, K, 7100, BF16, loc=0.0, scale=0.8)
+    order, gate = wl.top2_route(wl.router_logits(B, E, 7101))
+    m_x, tau_x, m_z = 0.0, 0.35, 0.0
+    zs = np.abs(oracle.swiglu_block(experts[0].Wg, experts[0].Wu, experts[0].Wd, X[0], m_x, tau_x, 0.0, 0.0, I8, BF16,
+                                    gate_scale=experts[0].sg, up_scale=experts[0].su, down_scale=experts[0].sd)["z"])
+    tau_z = float(np.quantile(zs, 0.7))
+    want = np.zeros((B, N))
+    for t in range(B):
+        for slot in range(2):
+            e = int(order[t, slot])
+            blk = experts[e]
+            y = oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[t], m_x, tau_x, m_z, tau_z, I8, BF16, gate_scale=blk.sg,
+                                    up_scale=blk.su, down_scale=blk.sd)["y"]
+            want[t] += gate[t, slot] * y.astype(np.float64)
+    got = np.zeros((B, N))
+    sizes = []
+    for e in range(E):
+        tok, slot = np.nonzero(order == e)
+        if tok.size == 0:
+            continue
+        sizes.append(int(tok.size))
+        say(f"expert {e}: tokens {tok.tolist()}")
+        outs = experts[e].run_batch(X[tok], BF16, m_x, tau_x, None, None, m_z, tau_z, None)
+        for j, t in enumerate(tok):
+            got[t] += gate[t, slot[j]] * outs[j]["y"].astype(np.float64)
+    assert sum(sizes) == 2 * B and max(sizes) >= 2
+    # a band decision on z moves y by about tau_z * |w| ~ 1e-3, inside the bar; compare the combined outputs
+    assert_y_close(got, want, "mixture of experts")
