@@ -412,8 +412,9 @@ def test_calibrate_every_code_pattern(dt):
 
 def test_hip_graph_replays_match_eager_launches():
     """bench.py times launches replayed from a HIP graph: every replay must give what the eager launch gives.
-    One-token kernel, the two-launch matrix-core path and the two-launch SwiGLU block, replayed several times with
-    eager work and synchronisation in between, on inputs that change between replays."""
+    One-token kernel, both matrix-core forms (single launch, union kernel + product kernel), the one-token and the
+    8-token SwiGLU block, replayed several times with eager work and synchronisation in between, on inputs that change
+    between replays."""
     K, F, N = 1500, 2056, 1032
     W = to_dev(wl.weights(K, N, 971, BF16), BF16)
     Wg, Wu, Wd = (to_dev(wl.weights(K, F, 972, BF16), BF16), to_dev(wl.weights(K, F, 973, BF16), BF16),
@@ -425,13 +426,18 @@ def test_hip_graph_replays_match_eager_launches():
     xb = X.clone()
     y1 = torch.zeros((1, N), dtype=torch.float32, device="cuda")
     y8 = torch.zeros((8, N), dtype=torch.float32, device="cuda")
+    y8l = torch.zeros((8, N), dtype=torch.float32, device="cuda")
     yb = torch.zeros((1, N), dtype=torch.float32, device="cuda")
+    yb8 = torch.zeros((8, N), dtype=torch.float32, device="cuda")
     nnz = torch.zeros(8, dtype=torch.int32, device="cuda")
+    two_launch = scap.LaunchCfg(0, 0, 0, 1)
 
     def work():
         scap.sparse_fc(W, x1, 0.0, 0.5, None, y=y1, workspace=ws)
         scap.sparse_fc(W, xb, 0.0, 0.5, None, y=y8, nnz_out=nnz, workspace=ws)        # 8 tokens: matrix cores
+        scap.sparse_fc(W, xb, 0.0, 0.5, None, y=y8l, workspace=ws, cfg=two_launch)
         scap.swiglu_block(W_gu, Wd, x1, 0.0, 0.5, None, 0.0, 0.02, None, y=yb, workspace=ws)
+        scap.swiglu_block(W_gu, Wd, xb, 0.0, 0.5, None, 0.0, 0.02, None, y=yb8, workspace=ws)
 
     work()
     torch.cuda.synchronize()
@@ -444,13 +450,15 @@ def test_hip_graph_replays_match_eager_launches():
         xb.copy_(torch.roll(X, rep + 1, dims=0))
         work()
         torch.cuda.synchronize()
-        want = (y1.clone(), y8.clone(), yb.clone(), nnz.clone())
-        for t in (y1, y8, yb, nnz):
+        outs = (y1, y8, y8l, yb, yb8, nnz)
+        want = tuple(t.clone() for t in outs)
+        assert torch.equal(y8, y8l) or float((y8 - y8l).abs().max()) < 1e-4
+        for t in outs:
             t.zero_()
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        for a, b in zip(want, (y1, y8, yb, nnz)):
+        for a, b in zip(want, outs):
             assert torch.equal(a, b), f"replay {rep} differs from the eager launch"
 
 

@@ -306,6 +306,30 @@ def test_mistral_ffn_block_full_size(s_x, s_z):
         assert flips <= 3
 
 
+@pytest.mark.parametrize("dt,B", [(BF16, 16), (I8, 8)])
+def test_ffn_block_full_size_batched(dt, B):
+    """The Mistral / expert feed-forward block at its real shape with a batch on the matrix cores; tokens sampled
+    against the oracle (each token has its own masks, so any token checks the whole launch's plumbing)."""
+    K, F, N = 4096, 14336, 4096
+    site = wl.sites(3)[2]
+    blk = Block(K, F, N, dt, seed=3103, std=0.02, B=B)
+    m_x, tau_x = oracle.calibrate(site.calib(), site.xdt, 0.5, oracle.MODE_MEDIAN)
+    X = site.draw(B, 3104)
+    zc = oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], m_x, tau_x, 0.0, 0.0, dt, BF16, gate_scale=blk.sg,
+                             up_scale=blk.su, down_scale=blk.sd, nthreads=8)["z"]
+    tau_z = float(np.sort(np.abs(zc))[int(np.ceil(0.6 * zc.size)) - 1])
+    bgf = oracle.fold_bias(blk.Wg, m_x, None, dt, col_scale=blk.sg)
+    buf = oracle.fold_bias(blk.Wu, m_x, None, dt, col_scale=blk.su)
+    say(f"full-size batched block dt={dt} B={B}")
+    gots = blk.run_batch(X, BF16, m_x, tau_x, bgf, buf, 0.0, tau_z, None)
+    for b in sorted({0, B // 2, B - 1}):
+        want = oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[b], m_x, tau_x, 0.0, tau_z, dt, BF16, b_gate=bgf, b_up=buf,
+                                   gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd, nthreads=8)
+        flips = blk.compare(gots[b], want, 0.0, tau_z, f"full-size batched block token {b}")
+        assert flips <= 3
+        assert abs(gots[b]["idx_z"].size / F - 0.4) < 0.06
+
+
 def test_random_blocks():
     """Seeded sweep over odd block shapes, 1-4 tokens, every weight dtype."""
     rng = np.random.default_rng(20241208)
