@@ -96,13 +96,9 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (lanes == 1) return launch_gemm_mfma(a, wdt, cfg, stream);
     const bool mfma_auto = mfma_ok && lanes == 0 && a.B >= (wdt == kI8 ? kMfmaAutoTokensI8 : kMfmaAutoTokens);
     if (mfma_auto) {
-        // Short inputs into wide layers (2K <= N, more than 4 tokens): the single launch would repeat a
-        // 16-token prologue in very many narrow tiles while the separate union launch is small, and the
-        // two-launch form measures a few percent faster (4096 -> 14336, 16 tokens, 90 %: 24.9 against 27.1 us).
-        const bool prefer_lists = a.B > 4 && 2 * (int64_t)a.K <= (int64_t)a.N;
-        int rc = prefer_lists ? launch_gemm_mfma(a, wdt, cfg, stream) : launch_gemm_inline(a, wdt, cfg, stream);
-        if (rc == SCAP_ERR_SHAPE)
-            rc = prefer_lists ? launch_gemm_inline(a, wdt, cfg, stream) : launch_gemm_mfma(a, wdt, cfg, stream);
+        // one launch; the two-launch form takes over where the input is too long for LDS-sized pieces
+        int rc = launch_gemm_inline(a, wdt, cfg, stream);
+        if (rc == SCAP_ERR_SHAPE) rc = launch_gemm_mfma(a, wdt, cfg, stream);
         // more narrow tiles than there are arrival counters: the vector kernel's tiles are four times wider
         if (rc != SCAP_ERR_SHAPE) return rc;
     }
