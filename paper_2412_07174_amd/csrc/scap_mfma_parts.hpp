@@ -86,7 +86,7 @@ __device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_
 // (acc[e][i] = token 4*(l/16) + i, column ELEMS*(l%16) + e of the tile), so they are added as a binary tree over
 // the wavefronts through LDS (32 KB at s_tree), CH accumulators at a time: the upper half of the surviving
 // wavefronts writes, the lower half adds lane by lane (conflict-free 16-byte accesses, every lane busy, fixed
-// order), until wavefront 0 holds the workgroup's sums and stores them straight from its registers.
+// order), until wavefront 0 holds the workgroup's sums; those go through LDS to all threads, which store them.
 // Ends with a barrier.
 // (FUSE / s_fin: see finish_columns -- with one split the sums are final and may go to the gating step)
 template <int WDT, int WAVES, int FUSE = kFusePlain>
@@ -116,21 +116,28 @@ __device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgp
                 for (int e = 0; e < CH; ++e) acc[c0 + e] += s_tree[(w * CH + e) * kWave + lane];
             }
         }
-        if (w == 0) {
+        // Wavefront 0 holds the chunk's sums (lane = column group x row group).  They pass through LDS once more
+        // so that every thread emits one 4-column group of one token and a wavefront's 64 stores are contiguous
+        // (straight from wavefront 0's registers they were 8 strided stores per lane, ~2 us of the kernel).
+        constexpr int GPC = 16 * (CH / 4);  // 4-column groups of the chunk per token
+        if (w == 0) {  // the only reader of the last tree level: no barrier needed before it writes
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int b = 4 * kg + i;
-                if (b < a.B) {
 #pragma unroll
-                    for (int v = 0; v < CH / 4; ++v) {
-                        const float4 sum = make_float4(acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i],
-                                                       acc[c0 + 4 * v + 3][i]);
-                        const int g = (cg * ELEMS + c0) / 4 + v;
-                        // one split: this is the finished value, and the group's constants are loaded here
-                        emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, sum, s_fin,
-                                                    a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
-                    }
-                }
+                for (int v = 0; v < CH / 4; ++v)
+                    s_tree[(4 * kg + i) * GPC + cg * (CH / 4) + v] =
+                        f32x4_t{acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i], acc[c0 + 4 * v + 3][i]};
+            }
+        }
+        __syncthreads();
+        for (int item = tid; item < kMfmaTokens * GPC; item += WAVES * kWave) {
+            const int b = item / GPC, gi = item - b * GPC;
+            if (b < a.B) {
+                const f32x4_t t = s_tree[item];
+                const int g = ((gi / (CH / 4)) * ELEMS + c0) / 4 + gi % (CH / 4);
+                // one split: this is the finished value, and the group's constants are loaded here
+                emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, make_float4(t[0], t[1], t[2], t[3]), s_fin,
+                                            a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
             }
         }
     }
