@@ -330,6 +330,41 @@ def test_ffn_block_full_size_batched(dt, B):
         assert abs(gots[b]["idx_z"].size / F - 0.4) < 0.06
 
 
+def test_blocks_on_two_streams_with_their_own_workspaces():
+    """Independent blocks (experts of a mixture) may overlap in time when each stream has its own workspace:
+    results equal the one-after-the-other results bit for bit."""
+    K, F, N = 1024, 2048, 1024
+    blks = [Block(K, F, N, I8, seed=8100, B=8), Block(K, F, N, BF16, seed=8200, B=8)]
+    X = to_dev(wl.laplace(16, K, 8300, BF16, loc=0.0, scale=1.0), BF16)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+
+    def call(blk, x, y, stream=None):
+        scap.swiglu_block(blk.W_gu, blk.W_down, x, 0.0, 0.4, None, 0.0, 0.05, None, gu_scale=blk.gu_scale,
+                          down_scale=blk.down_scale, y=y, workspace=blk.ws, stream=stream)
+
+    cases = [(blks[0], X[i], (1, N)) for i in range(8)] + [(blks[0], X[i:i + 5], (5, N)) for i in range(4)]
+    cases2 = [(blks[1], X[i:i + 8], (8, N)) for i in range(8)] + [(blks[1], X[i], (1, N)) for i in range(4)]
+    refs = []
+    for group in (cases, cases2):
+        for blk, x, shape in group:
+            y = torch.empty(shape, dtype=torch.float32, device="cuda")
+            call(blk, x, y)
+            refs.append(y)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        say(f"blocks on two streams rep {rep}")
+        outs = [torch.full(r.shape, float("nan"), dtype=torch.float32, device="cuda") for r in refs]
+        torch.cuda.synchronize()
+        for i in range(len(cases)):
+            for s, group, base in ((0, cases, 0), (1, cases2, len(cases))):
+                blk, x, _ = group[i]
+                with torch.cuda.stream(streams[s]):
+                    call(blk, x, outs[base + i], stream=streams[s])
+        torch.cuda.synchronize()
+        for i, (o, r) in enumerate(zip(outs, refs)):
+            assert torch.equal(o, r), f"rep {rep} call {i}"
+
+
 def test_random_blocks():
     """Seeded sweep over odd block shapes, 1-4 tokens, every weight dtype."""
     rng = np.random.default_rng(20241208)
