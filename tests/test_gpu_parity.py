@@ -244,6 +244,35 @@ def test_batched_matrix_core_edge_cases(lanes):
                                  what=f"mfma lanes={lanes} rows={rows} tau={tau}")
 
 
+STAGED = [
+    # K (multiple of 8: the staged-tile kernel), N, tokens, weight dtype, activation dtype
+    (8, 128, 5, BF16, BF16), (16, 136, 16, BF16, BF16), (56, 264, 7, BF16, F16), (64, 128, 16, I8, BF16),
+    (72, 272, 9, I8, F16), (120, 520, 5, BF16, BF16), (512, 1032, 16, BF16, F16), (2048, 264, 11, I8, BF16),
+    (2568, 136, 16, BF16, BF16), (4104, 528, 6, I8, BF16), (6000, 128, 13, BF16, BF16),
+]
+
+
+@pytest.mark.parametrize("K,N,B,wdt,xdt", STAGED)
+def test_staged_tile_kernel_shapes(K, N, B, wdt, xdt):
+    """More than 4 tokens with K a multiple of 8 run on the kernel that stages the raw input tile: shortest inputs,
+    one chunk and many, ragged last split, both activation types with both weight types, centring on and off, from
+    everything kept to almost nothing kept; and the dense call on the same kernel."""
+    if wdt == I8:
+        N = (N + 15) // 16 * 16
+        W, scale = wl.quantize_i8(K, N, 7000 + K)
+    else:
+        W, scale = wl.weights(K, N, 7000 + K, wdt), None
+    layer = Layer(W, wdt, col_scale_bits=scale, B=16)
+    X = wl.laplace(B, K, 7100 + K, xdt, loc=0.1, scale=0.8)
+    bias = np.random.default_rng(7200 + K).standard_normal(N).astype(np.float32)
+    for m, tau, bf in ((0.0, 0.0, None), (0.13, 0.5, bias), (-0.4, 3.0, None), (0.0, 50.0, bias)):
+        say(f"staged tile K={K} N={N} B={B} wdt={wdt} xdt={xdt} m={m} tau={tau}")
+        check_against_oracle(layer, X, xdt, m, tau, bf, what=f"staged K={K} B={B} m={m} tau={tau}")
+    y = scap.dense_fc(layer.W, to_dev(X, xdt), f32_dev(bias), col_scale=layer.scale, workspace=layer.ws)
+    torch.cuda.synchronize()
+    assert_y_close(y.cpu().numpy(), oracle.dense_fc(W, X, bias, wdt, xdt, col_scale=scale), "staged dense")
+
+
 @pytest.mark.parametrize("B", [4, 16])
 def test_batched_tokens_fp16_weights(B):
     K, N = 1500, 1032
