@@ -460,12 +460,44 @@ __device__ __forceinline__ int gather_lists(const GemvArgs& a, int split, const 
 // layer input (Alg. 3 steps 1-2, strict compare of Eq. 2; each token its own mask) and leave each 64-channel
 // segment's kept channels, compacted, for the down launch.  Called by every thread of the tile's last arrival.
 template <int WAVES, int TILE, int BT>
-__device__ __forceinline__ void gate_and_compact(const GemvArgs& a, int tile, const float* s_fin) {
+__device__ __forceinline__ void gate_and_compact(const GemvArgs& a, int tile, float* s_fin) {
     constexpr int HALF = TILE / 2;  // gated outputs per tile; a multiple of 64
     constexpr int NT = WAVES * kWave;
+    constexpr bool SPREAD = BT >= 4;  // several tokens: the activation is evaluated by all threads first
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int nsegs = (a.F + kWave - 1) / kWave;
+    // centred, thresholded gated product of (token b, channel t of the tile); 0 where pruned or absent
+    auto gated = [&](int b, int t) {
+        const int c = tile * HALF + t;
+        if (!(b < a.B && t < HALF && c < a.F)) return 0.f;
+        const int p = b * TILE + (t >> 2) * 8 + (t & 3);
+        const float g = s_fin[p], u = s_fin[p + 4];
+        const float z = g / (1.f + expf(-g)) * u;
+        if (a.z_out) a.z_out[(int64_t)b * a.F + c] = z;
+        const float d = z - a.m2;
+        return fabsf(d) > a.tau2 ? d : 0.f;
+    };
+    if constexpr (SPREAD) {
+        // One thread per (token, channel) instead of one per channel with the tokens in sequence (the exponential
+        // and the division are ~50 instructions each, and only HALF of the NT threads have a channel).  The
+        // results replace the gate values in s_fin; kept means |d| > tau >= 0, so a kept value is never 0.
+        constexpr int PER = (BT * HALF + NT - 1) / NT;
+        float dreg[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int item = i * NT + tid;
+            dreg[i] = item < BT * HALF ? gated(item / HALF, item % HALF) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int item = i * NT + tid;
+            const int b = item / HALF, t = item % HALF;
+            if (item < BT * HALF) s_fin[b * TILE + (t >> 2) * 8 + (t & 3)] = dreg[i];
+        }
+        __syncthreads();
+    }
     for (int t0 = 0; t0 < HALF; t0 += NT) {
         const int t = t0 + tid;
         const int c = tile * HALF + t;
@@ -474,18 +506,12 @@ __device__ __forceinline__ void gate_and_compact(const GemvArgs& a, int tile, co
         bool any = false;
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-            dv[b] = 0.f;
-            keep[b] = false;
-            if (b < a.B && t < HALF && c < a.F) {
-                const int p = b * TILE + (t >> 2) * 8 + (t & 3);
-                const float g = s_fin[p], u = s_fin[p + 4];
-                const float z = g / (1.f + expf(-g)) * u;
-                if (a.z_out) a.z_out[(int64_t)b * a.F + c] = z;
-                const float d = z - a.m2;
-                keep[b] = fabsf(d) > a.tau2;
-                dv[b] = keep[b] ? d : 0.f;
-                any |= keep[b];
-            }
+            if constexpr (SPREAD)
+                dv[b] = (b < a.B && t < HALF && c < a.F) ? s_fin[b * TILE + (t >> 2) * 8 + (t & 3)] : 0.f;
+            else
+                dv[b] = gated(b, t);
+            keep[b] = dv[b] != 0.f;
+            any |= keep[b];
         }
         const uint64_t bal = __ballot(any);
         const int seg = uniform((tile * HALF + t0 + (tid & ~63)) >> 6);
