@@ -70,7 +70,7 @@ typedef enum {
 
 /* Optional launch shape of the kernels (for tuning sweeps and tests).  Zero fields mean "choose".
  * lanes_per_row selects the kernel: 64 or 32 = the vector kernel (column tile = lanes_per_row x 8 columns,
- * x 16 for int8; batches: 64 only); 16 = the single-launch matrix-core kernel and 1 = the two-launch
+ * x 16 for int8; more than 4 tokens: 64 only); 16 = the single-launch matrix-core kernel and 1 = the two-launch
  * matrix-core form with its lists in the workspace (both: 2..16 tokens over bf16 or int8 weights; there
  * waves_per_group must be 0 or 8 -- the two-launch form also takes 16 with bf16 -- and rows_per_group is a
  * multiple of 64, rounded up to whole 512-channel list segments by the two-launch form, whose unroll

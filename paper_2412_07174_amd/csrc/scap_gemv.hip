@@ -116,7 +116,13 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     // Few column tiles mean many K splits, and the tile's last arrival has to pull all their partial sums
     // through one compute unit: with at most 4 full-width tiles (int8 weights and N = 4096, say) half-width
     // tiles halve that (measured on 14336 x 4096 int8: 20.0 -> 18.4 us dense, 10.1 -> 8.1 us at 90 %).
-    if (!(cfg && cfg->lanes_per_row) && bt == 1 && (a.N + 64 * elems - 1) / (64 * elems) <= 4) lpr = 32;
+    // With 2-4 tokens the partial sums are 2-4 times larger, and half-width tiles also pay off at 8 full-width
+    // tiles when the input is short (4096 x 4096 bf16, 4 tokens: 16.2 -> 14.5 us dense, 12.7 -> 10.3 at 90 %;
+    // 14336 x 4096 int8, 2 tokens: 22.4 -> 19.6); with a long input or a wide layer they lose.
+    if (!(cfg && cfg->lanes_per_row) && bt <= 4) {
+        const int full_tiles = (a.N + 64 * elems - 1) / (64 * elems);
+        if (full_tiles <= 4 || (bt > 1 && full_tiles <= 8 && a.K <= 8192)) lpr = 32;
+    }
     const int rc = plan_splits(a, lpr * elems, bt, kc, cfg && cfg->rows_per_group);
     if (rc != SCAP_OK) {
         // a batch's kept-channel list of a very long input does not fit the vector kernel's LDS; the

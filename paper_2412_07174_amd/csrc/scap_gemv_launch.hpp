@@ -43,6 +43,7 @@ static int launch_bt(const GemvArgs& a, int waves, int unroll, int lpr, hipStrea
         return SCAP_ERR_CONFIG;
     } else if constexpr (BT <= 4) {
         if (waves == 8 && unroll == 8 && lpr == 64) return launch_one<WDT, 8, 8, BT, 64>(a, stream);
+        if (waves == 8 && unroll == 8 && lpr == 32) return launch_one<WDT, 8, 8, BT, 32>(a, stream);
         return SCAP_ERR_CONFIG;
     } else {
         if (waves == 8 && unroll == 4 && lpr == 64) return launch_one<WDT, 8, 4, BT, 64>(a, stream);

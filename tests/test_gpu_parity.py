@@ -225,6 +225,26 @@ def test_batched_tokens_moderate(B, path):
         check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"B={B} {path} tau={tau}")
 
 
+@pytest.mark.parametrize("wdt", [F16, BF16, I8])
+@pytest.mark.parametrize("B", [2, 3, 4])
+def test_batched_tokens_half_width_tiles(B, wdt):
+    """2-4 tokens on the vector kernel with half-width column tiles: forced, and as the default for a short
+    input into a narrow layer (few full-width tiles)."""
+    K, N = 1100, 2064 if wdt != I8 else 2080
+    if wdt == I8:
+        W, scale = wl.quantize_i8(K, N, 531)
+    else:
+        W, scale = wl.weights(K, N, 531, wdt), None
+    xdt = BF16 if wdt == I8 else wdt
+    layer = Layer(W, wdt, col_scale_bits=scale, B=4)
+    X = wl.laplace(B, K, 532 + B, xdt, loc=0.1, scale=0.7)
+    bf = np.random.default_rng(533).standard_normal(N).astype(np.float32)
+    for cfg in ((8, 0, 8, 32), (8, 192, 8, 32), None):
+        for m, tau in ((0.1, 0.0), (0.1, 0.6), (0.0, 2.5)):
+            say(f"half-width tiles B={B} wdt={wdt} cfg={cfg} tau={tau}")
+            check_against_oracle(layer, X, xdt, m, tau, bf, cfg=cfg, what=f"half-width B={B} wdt={wdt} cfg={cfg} tau={tau}")
+
+
 @pytest.mark.parametrize("lanes", [16, 1])
 def test_batched_matrix_core_edge_cases(lanes):
     """Ragged list lengths (not multiples of the 16-row MFMA block), infinities, one split and many splits."""
