@@ -38,8 +38,9 @@ static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
     up.Sl = up.S;
     const size_t lds_up = lds_bytes(up.Kc, BT, (RED + (size_t)BT * TILE) * 4);
 
-    // one token and at most 4 full-width tiles of output: half-width tiles, as in the plain launch
-    const bool half = BT == 1 && (dn.N + TILE - 1) / TILE <= 4;
+    // few full-width tiles of output: half-width tiles, by the rule of the plain launch
+    const int full_tiles = (dn.N + TILE - 1) / TILE;
+    const bool half = full_tiles <= 4 || (BT > 1 && full_tiles <= 8 && dn.K <= 8192);
     const int dn_tile = half ? TILE / 2 : TILE;
     rc = plan_splits(dn, dn_tile, BT, 0, false);
     if (rc == SCAP_OK && dn.Kc > kMaxListRows) rc = plan_splits(dn, dn_tile, BT, kMaxListRows, false);
@@ -54,12 +55,10 @@ static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
 
     hipLaunchKernelGGL((swiglu_up_kernel<WDT, BT>), dim3((unsigned)(up.S * up.T)), dim3(NT), lds_up, stream, up);
     if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
-    if constexpr (BT == 1) {
-        if (half) {
-            hipLaunchKernelGGL((swiglu_down_kernel<WDT, 1, kWave / 2>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn,
-                               stream, dn);
-            return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
-        }
+    if (half) {
+        hipLaunchKernelGGL((swiglu_down_kernel<WDT, BT, kWave / 2>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn,
+                           stream, dn);
+        return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
     }
     hipLaunchKernelGGL((swiglu_down_kernel<WDT, BT, kWave>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn, stream, dn);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
