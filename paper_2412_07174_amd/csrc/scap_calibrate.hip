@@ -11,6 +11,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <utility>
 #include <vector>
 
@@ -20,23 +21,28 @@
 namespace scap {
 
 constexpr int kCodes = 65536;
-constexpr int kQuarter = 16384;     // codes counted by one workgroup (64 KB of LDS counters)
+constexpr int kHalf = 32768;        // codes counted by one workgroup: 128 KB of LDS counters (gfx950: 160 KB per workgroup)
 constexpr int kHistThreads = 1024;
-constexpr int kHistChunks = 64;     // workgroups per quarter
+constexpr int kHistChunks = 128;    // workgroups per half of the code space
 
-// Workgroup (chunk, quarter) reads its share of the sample 16 bytes per lane and counts the codes whose top
-// two bits equal `quarter` in LDS, then adds its non-zero counters to the global histogram.
+// Workgroup (chunk, half) reads its share of the sample 16 bytes per lane and counts the codes whose top bit
+// equals `half` (the sign) in LDS, then adds its non-zero counters to the global histogram.  The kernel is bound
+// by instruction issue (shift, compare, masked LDS add per code), so every code is looked at by as few
+// workgroups as LDS allows: two.
 __global__ __launch_bounds__(kHistThreads) void code_hist_kernel(const uint16_t* __restrict__ X, int64_t M,
                                                                 unsigned long long* __restrict__ hist) {
-    __shared__ uint32_t sh[kQuarter];
+    extern __shared__ uint32_t sh[];  // [kHalf]
     const int tid = threadIdx.x;
-    const uint32_t quarter = blockIdx.x & 3u;
-    const int chunk = blockIdx.x >> 2;
-    const int nchunk = gridDim.x >> 2;
-    for (int i = tid; i < kQuarter; i += kHistThreads) sh[i] = 0;
+    // The two workgroups that read the same share sit on one XCD (blockIdx % 8) and start together, so the share
+    // comes from HBM once and from that XCD's L2 the second time.
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const uint32_t half = (uint32_t)j & 1u;
+    const int chunk = xcd + 8 * (j >> 1);
+    const int nchunk = gridDim.x >> 1;
+    for (int i = tid; i < kHalf; i += kHistThreads) sh[i] = 0;
     __syncthreads();
     auto count = [&](uint32_t code) {
-        if ((code >> 14) == quarter) atomicAdd(&sh[code & (kQuarter - 1)], 1u);
+        if ((code >> 15) == half) atomicAdd(&sh[code & (kHalf - 1)], 1u);
     };
     const int64_t nvec = M / 8;
     const uint4* __restrict__ X8 = reinterpret_cast<const uint4*>(X);
@@ -54,9 +60,9 @@ __global__ __launch_bounds__(kHistThreads) void code_hist_kernel(const uint16_t*
         if (j < M) count(X[j]);
     }
     __syncthreads();
-    for (int i = tid; i < kQuarter; i += kHistThreads) {
+    for (int i = tid; i < kHalf; i += kHistThreads) {
         const uint32_t v = sh[i];
-        if (v) atomicAdd(&hist[quarter * kQuarter + i], (unsigned long long)v);
+        if (v) atomicAdd(&hist[half * kHalf + i], (unsigned long long)v);
     }
 }
 
@@ -197,7 +203,20 @@ int run_calibrate(const uint16_t* X, int64_t M, int xdt, float s, int est, float
     unsigned long long* d_hist = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kOffCodeHist);
     int rc = launch_zero_words(reinterpret_cast<int32_t*>(d_hist), 2 * (size_t)kCodes, stream);
     if (rc != SCAP_OK) return rc;
-    hipLaunchKernelGGL(code_hist_kernel, dim3(4 * kHistChunks), dim3(kHistThreads), 0, stream, X, M, d_hist);
+    {
+        // 128 KB of dynamic LDS: above the default limit, asked for once per device
+        constexpr int kMaxDevices = 64;
+        static std::atomic<bool> asked[kMaxDevices];
+        int dev = 0;
+        if (!ok(hipGetDevice(&dev)) || dev < 0 || dev >= kMaxDevices) return SCAP_ERR_HIP;
+        if (!asked[dev].load(std::memory_order_acquire)) {
+            if (!ok(hipFuncSetAttribute(reinterpret_cast<const void*>(&code_hist_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kHalf * 4)))
+                return SCAP_ERR_HIP;
+            asked[dev].store(true, std::memory_order_release);
+        }
+    }
+    hipLaunchKernelGGL(code_hist_kernel, dim3(2 * kHistChunks), dim3(kHistThreads), kHalf * 4, stream, X, M, d_hist);
     if (!ok(hipGetLastError())) return SCAP_ERR_HIP;
     std::vector<unsigned long long> hist(kCodes);
     if (!ok(hipMemcpyAsync(hist.data(), d_hist, sizeof(unsigned long long) * kCodes, hipMemcpyDeviceToHost, stream)))
