@@ -71,11 +71,12 @@ typedef enum {
 /* Optional launch shape of the kernels (for tuning sweeps and tests).  Zero fields mean "choose".
  * lanes_per_row selects the kernel: 64 or 32 = the vector kernel (column tile = lanes_per_row x 8 columns,
  * x 16 for int8; more than 4 tokens: 64 only); 16 = the single-launch matrix-core kernel and 1 = the two-launch
- * matrix-core form with its lists in the workspace (both: 2..16 tokens over bf16 or int8 weights; there
- * waves_per_group must be 0 or 8 -- the two-launch form also takes 16 with bf16 -- and rows_per_group is a
- * multiple of 64, rounded up to whole 512-channel list segments by the two-launch form, whose unroll
- * (1, 2, 4; int8: 1, 2) counts 16-row blocks in flight per wavefront).  By default batches of 5 or more tokens
- * over bf16 weights and of 3 or more over int8 weights run on the matrix cores. */
+ * matrix-core form with its lists in the workspace (both: 2..16 tokens over bf16 or int8 weights; the
+ * single-launch kernel also 5..16 tokens over fp16 weights; there waves_per_group must be 0 or 8 -- the
+ * two-launch form also takes 16 with bf16 -- and rows_per_group is a multiple of 64, rounded up to whole
+ * 512-channel list segments by the two-launch form, whose unroll (1, 2, 4; int8: 1, 2) counts 16-row blocks
+ * in flight per wavefront).  By default batches of 5 or more tokens (3 or more over int8 weights) run on
+ * the matrix cores. */
 typedef struct {
     int32_t waves_per_group; /* 4, 8 or 16 wavefronts per workgroup */
     int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */
@@ -197,9 +198,9 @@ size_t scap_swiglu_workspace_bytes(int64_t K, int64_t F, int64_t N, int64_t B);
  * its input.  z is never rounded to 16 bits.
  *   W_gu, gu_scale   DEVICE  [K, 2F] from scap_pack_gate_up (and its packed fp16 scales for int8, else NULL).
  *   W_down, down_scale DEVICE [F, N] K-major (scales for int8, else NULL); same dtype wdt as W_gu.
- *   x                DEVICE  [B, K], dtype xdt.   B <= 16 over bf16 or int8 weights (matrix cores from 5 tokens,
- *                            int8 from 3), B <= 4 over fp16 weights (beyond: SCAP_ERR_UNIMPL); each token has
- *                            its own masks, a weight row is read when any token keeps its channel (Appendix C).
+ *   x                DEVICE  [B, K], dtype xdt.   B <= 16 (matrix cores from 5 tokens, int8 from 3); each token
+ *                            has its own masks, a weight row is read when any token keeps its channel
+ *                            (Appendix C).
  *   m_x, tau_x       constants of the block input;  b_gu_fused  DEVICE fp32 [2F] packed fused bias or NULL
  *                    (scap_fold_bias on W_gu with the packed bias gives it).
  *   m_z, tau_z       constants of the gated product;  b_down_fused  DEVICE fp32 [N] or NULL.

@@ -212,7 +212,6 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
     if (!x || !y) return SCAP_ERR_NULL;
     if (!act_dtype_ok(xdt)) return SCAP_ERR_DTYPE;
     if (B < 1 || B > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
-    if (B > kBlockVectorTokens && wdt == SCAP_F16) return SCAP_ERR_UNIMPL;
     if (!aligned16(x) || !aligned16(y) || (b_gu_fused && !aligned16(b_gu_fused)) ||
         (b_down_fused && !aligned16(b_down_fused)) || (z_out && !aligned16(z_out)))
         return SCAP_ERR_ALIGN;

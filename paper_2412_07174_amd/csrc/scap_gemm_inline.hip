@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_kernel(const 
     };
     auto compute = [&](const Stage& st) {
         s16x4_t a_hi, a_lo;
-        split_bf16x4(st.d, a_hi, a_lo);
+        split_operand<WDT>(st.d, a_hi, a_lo);
         mfma_block<WDT>(acc, a_hi, a_lo, st.r);
     };
 
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_raw_kernel(co
     };
     auto compute = [&](const Stage& st) {
         s16x4_t a_hi, a_lo;
-        split_bf16x4(st.d, a_hi, a_lo);
+        split_operand<WDT>(st.d, a_hi, a_lo);
         mfma_block<WDT>(acc, a_hi, a_lo, st.r);
     };
 
@@ -482,12 +482,16 @@ static int launch_inline_wdt(const GemvArgs& a, int bt, bool raw, size_t lds, hi
     if constexpr (FUSE != kFuseList) {
         if (raw) return launch_inline_raw<WDT, FUSE>(a, lds, stream);
     }
-    return bt == 4 ? launch_inline<WDT, 4, FUSE>(a, lds, stream) : launch_inline<WDT, 16, FUSE>(a, lds, stream);
+    if constexpr (WDT == kF16)  // fp16 weights: 16 token slots only (2-4 tokens stay on the vector kernel)
+        return launch_inline<WDT, 16, FUSE>(a, lds, stream);
+    else
+        return bt == 4 ? launch_inline<WDT, 4, FUSE>(a, lds, stream) : launch_inline<WDT, 16, FUSE>(a, lds, stream);
 }
 
 template <int FUSE>
 static int launch_inline_any(const GemvArgs& a, int wdt, int bt, bool raw, size_t lds, hipStream_t stream) {
     if (wdt == kBF16) return launch_inline_wdt<kBF16, FUSE>(a, bt, raw, lds, stream);
+    if (wdt == kF16) return bt == kMfmaTokens ? launch_inline_wdt<kF16, FUSE>(a, bt, raw, lds, stream) : SCAP_ERR_CONFIG;
     if (wdt == kI8) return launch_inline_wdt<kI8, FUSE>(a, bt, raw, lds, stream);
     return SCAP_ERR_CONFIG;
 }
@@ -496,9 +500,10 @@ static int launch_inline_any(const GemvArgs& a, int wdt, int bt, bool raw, size_
 // registers that hold a wavefront's chunks), LDS bytes.
 static int plan_inline(GemvArgs& a, int wdt, int kc, bool kc_forced, int fuse, int* bt_out, size_t* lds_out,
                        bool* raw_out = nullptr) {
-    if (wdt != kBF16 && wdt != kI8) return SCAP_ERR_CONFIG;
+    if (wdt != kBF16 && wdt != kI8 && wdt != kF16) return SCAP_ERR_CONFIG;
     if (a.B < 1 || a.B > kMfmaTokens) return SCAP_ERR_CONFIG;
     const int bt = a.B <= 4 ? 4 : 16;
+    if (wdt == kF16 && bt != kMfmaTokens) return SCAP_ERR_CONFIG;  // fp16: the 16-slot kernels only
     const int tile_cols = wdt == kI8 ? 2 * kMfmaTile : kMfmaTile;
     size_t budget = kInlineLdsBudget;
     int kc_cap = kMaxSplits * kWave * 1024;  // no cap

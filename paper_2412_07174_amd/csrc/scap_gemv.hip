@@ -81,14 +81,17 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     while (bt < a.B) bt <<= 1;
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
-    // Several tokens over bf16 or int8 weights: the gathered rows form a dense sub-GEMM -> matrix cores.
+    // Several tokens: the gathered rows form a dense sub-GEMM -> matrix cores (bf16 and int8 weights from 2
+    // tokens; fp16 weights from 5, on the single-launch kernel only).
     // lanes_per_row = 16 asks for the single-launch matrix-core kernel (its lane layout), 1 for the
     // two-launch form whose lists live in the workspace, 64 or 32 for the vector kernel.  By default the
     // single-launch kernel runs from kMfmaAutoTokens (bf16) / kMfmaAutoTokensI8 (int8) tokens on, the
     // two-launch form when the input is too long for LDS-sized pieces, the vector kernel otherwise.
     const int lanes = cfg ? cfg->lanes_per_row : 0;
-    const bool mfma_ok = a.B >= kMfmaMinTokens && (wdt == kBF16 || wdt == kI8) && a.mode != kModeFold;
+    const bool mfma_ok = a.mode != kModeFold &&
+                         ((a.B >= kMfmaMinTokens && (wdt == kBF16 || wdt == kI8)) || (a.B > 4 && wdt == kF16));
     if ((lanes == 16 || lanes == 1) && !mfma_ok) return SCAP_ERR_CONFIG;
+    if (lanes == 1 && wdt == kF16) return SCAP_ERR_CONFIG;
     if (lanes == 16) {
         const int rc = launch_gemm_inline(a, wdt, cfg, stream);
         return rc == SCAP_ERR_SHAPE ? SCAP_ERR_CONFIG : rc;
@@ -98,7 +101,7 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     if (mfma_auto) {
         // one launch; the two-launch form takes over where the input is too long for LDS-sized pieces
         int rc = launch_gemm_inline(a, wdt, cfg, stream);
-        if (rc == SCAP_ERR_SHAPE) rc = launch_gemm_mfma(a, wdt, cfg, stream);
+        if (rc == SCAP_ERR_SHAPE && wdt != kF16) rc = launch_gemm_mfma(a, wdt, cfg, stream);
         // more narrow tiles than there are arrival counters: the vector kernel's tiles are four times wider
         if (rc != SCAP_ERR_SHAPE) return rc;
     }
@@ -129,7 +132,7 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         // matrix-core path keeps its lists in the workspace
         if (rc == SCAP_ERR_SHAPE && mfma_ok && lanes == 0 && !(cfg && cfg->rows_per_group)) {
             const int rc2 = launch_gemm_inline(a_in, wdt, cfg, stream);
-            return rc2 == SCAP_ERR_SHAPE ? launch_gemm_mfma(a_in, wdt, cfg, stream) : rc2;
+            return (rc2 == SCAP_ERR_SHAPE && wdt != kF16) ? launch_gemm_mfma(a_in, wdt, cfg, stream) : rc2;
         }
         return (rc == SCAP_ERR_SHAPE && cfg && cfg->lanes_per_row) ? SCAP_ERR_CONFIG : rc;
     }

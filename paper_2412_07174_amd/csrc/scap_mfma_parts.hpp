@@ -10,7 +10,8 @@
 // produces columns {ELEMS*n + e}.  The C registers of lane l then hold tokens 4*(l/16)+i and ELEMS
 // consecutive columns.  The A operand (centred values of token l%16 at rows 4*(l/16)+j) is split into a
 // bf16 head and a bf16 tail (d = hi + lo) and fed through two MFMAs, so the bf16 rounding of d costs about
-// 2^-17 relative instead of 2^-9.  int8 weights are widened exactly to bf16 in registers.
+// 2^-17 relative instead of 2^-9.  int8 weights are widened exactly to bf16 in registers.  fp16 weights use
+// v_mfma_f32_16x16x16_f16 (same lane layout) with the A operand split into an fp16 head and tail.
 #pragma once
 
 #include "scap_gemv_parts.hpp"
@@ -18,6 +19,7 @@
 namespace scap {
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaTile = 128;    // columns per workgroup with bf16 weights (16 lanes x 8); int8: 256
@@ -43,6 +45,35 @@ __device__ __forceinline__ void split_bf16x4(const float4& d, s16x4_t& hi, s16x4
     }
 }
 
+// 4 centred values -> fp16 head and tail operands (as raw 16-bit patterns).  The head is clamped to the largest
+// finite fp16 so that a finite value never turns into an infinite head; the tail then carries the rest (the
+// activations are fp16 or bf16 values minus a small mode, so the rest is small).  Values below fp16's
+// subnormal step (6e-8) lose their tail, an absolute error far inside the output tolerance.
+__device__ __forceinline__ void split_f16x4(const float4& d, s16x4_t& hi, s16x4_t& lo) {
+    const float v[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool inf = fabsf(v[j]) == __builtin_huge_valf();
+        const float c = inf ? v[j] : fminf(fmaxf(v[j], -65504.f), 65504.f);
+        const _Float16 h = (_Float16)c;
+        const _Float16 l = (_Float16)(inf ? 0.f : v[j] - (float)h);
+        union { _Float16 f; short s; } a, b;
+        a.f = h;
+        b.f = l;
+        hi[j] = a.s;
+        lo[j] = b.s;
+    }
+}
+
+// head / tail split of the A operand in the format the weights' MFMA takes
+template <int WDT>
+__device__ __forceinline__ void split_operand(const float4& d, s16x4_t& hi, s16x4_t& lo) {
+    if constexpr (WDT == kF16)
+        split_f16x4(d, hi, lo);
+    else
+        split_bf16x4(d, hi, lo);
+}
+
 // One 16-row block: r[j] = this lane's 16 bytes of list row 4*(l/16)+j (zeros for a slot past the list),
 // a_hi / a_lo = its A operand.  acc[e] += A * B_e for the ELEMS column elements.
 template <int WDT>
@@ -55,7 +86,7 @@ __device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_
 #pragma unroll
     for (int e = 0; e < ELEMS; ++e) {
         uint32_t lo01, lo23;  // rows (0,1) and (2,3) of column element e, packed as two bf16
-        if constexpr (WDT == kBF16) {
+        if constexpr (WDT == kBF16 || WDT == kF16) {
             const int q = e >> 1;
             if ((e & 1) == 0) {
                 lo01 = (q0[q] & 0xFFFFu) | (q1[q] << 16);
@@ -77,8 +108,17 @@ __device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_
         union { uint32_t u32[2]; s16x4_t v; } bop;
         bop.u32[0] = lo01;
         bop.u32[1] = lo23;
-        acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bop.v, acc[e], 0, 0, 0);
-        acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop.v, acc[e], 0, 0, 0);
+        if constexpr (WDT == kF16) {
+            union { s16x4_t s; f16x4_t h; } ah, al, bh;
+            ah.s = a_hi;
+            al.s = a_lo;
+            bh.s = bop.v;
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(ah.h, bh.h, acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(al.h, bh.h, acc[e], 0, 0, 0);
+        } else {
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bop.v, acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop.v, acc[e], 0, 0, 0);
+        }
     }
 }
 

@@ -73,10 +73,10 @@ static int launch_block_wdt(const GemvArgs& up, const GemvArgs& down, hipStream_
 }
 
 int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream) {
-    // Matrix cores: more than 4 tokens (bf16, int8), and int8 from 3 tokens on, where the vector kernel is
-    // bound by its per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
+    // Matrix cores: more than 4 tokens, and int8 from 3 tokens on, where the vector kernel is bound by its
+    // per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
     // 3-4 tokens, so the choice only has to be the same for both launches.
-    const bool matrix = (wdt == kBF16 || wdt == kI8) && (up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3));
+    const bool matrix = up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3);
     if (matrix) {
         const int rc = launch_swiglu_block_inline(up, down, wdt, stream);
         if (rc != SCAP_ERR_SHAPE || up.B > kBlockVectorTokens) return rc == SCAP_ERR_SHAPE ? SCAP_ERR_UNIMPL : rc;

@@ -128,7 +128,6 @@ def test_swiglu_block_entry_points_validate(lib):
     assert _blk(lib, xdt=2) == -3
     assert _blk(lib, B=0) == -2
     assert _blk(lib, B=17) == -2
-    assert _blk(lib, B=5, wdt=0) == -8              # fp16 weights: at most 4 tokens
     assert _blk(lib, x=ODD) == -4
     assert _blk(lib, z=ODD) == -4
     assert _blk(lib, tx=-0.5) == -5

@@ -269,6 +269,7 @@ STAGED = [
     (8, 128, 5, BF16, BF16), (16, 136, 16, BF16, BF16), (56, 264, 7, BF16, F16), (64, 128, 16, I8, BF16),
     (72, 272, 9, I8, F16), (120, 520, 5, BF16, BF16), (512, 1032, 16, BF16, F16), (2048, 264, 11, I8, BF16),
     (2568, 136, 16, BF16, BF16), (4104, 528, 6, I8, BF16), (6000, 128, 13, BF16, BF16),
+    (8, 128, 5, F16, F16), (72, 272, 16, F16, BF16), (1000, 520, 7, F16, F16), (4104, 136, 16, F16, F16),
 ]
 
 

@@ -204,19 +204,20 @@ def test_small_blocks_int8(K, F, N):
 
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
-@pytest.mark.parametrize("dt", [BF16, I8])
+@pytest.mark.parametrize("dt", [BF16, I8, F16])
 @pytest.mark.parametrize("B", [2, 3, 4, 5, 8, 13, 16])
 def test_batched_blocks(B, dt):
     K, F, N = 1000, 2056, 1040
     blk = Block(K, F, N, dt, seed=840 + B, B=B)
-    X = wl.laplace(B, K, 850 + B, BF16, loc=0.1, scale=0.8)
+    xdt = F16 if dt == F16 else BF16
+    X = wl.laplace(B, K, 850 + B, xdt, loc=0.1, scale=0.8)
     rng = np.random.default_rng(860 + B)
     bg, bu, bd = (rng.standard_normal(n).astype(np.float32) * 0.05 for n in (F, F, N))
-    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.1, 0.5, 0.0, 0.0, dt, BF16, b_gate=bg, b_up=bu,
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.1, 0.5, 0.0, 0.0, dt, xdt, b_gate=bg, b_up=bu,
                                     gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd)["z"])
     for tau_x, tau_z in ((0.0, 0.0), (0.5, float(np.median(zs))), (1.1, float(np.quantile(zs, 0.9))), (0.5, 1e9)):
         say(f"batched block B={B} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
-        blk.check_batch(X, BF16, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"B={B} dt={dt} tau_z={tau_z}")
+        blk.check_batch(X, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"B={B} dt={dt} tau_z={tau_z}")
 
 
 # ------------------------------------------------------------------ degenerate cases
@@ -258,13 +259,6 @@ def test_block_is_bit_reproducible_and_workspace_is_reusable():
 
 def test_block_argument_errors():
     K, F, N = 64, 64, 16
-    blk16 = Block(K, F, N, F16, seed=919)
-    x16 = to_dev(wl.laplace(5, K, 921, F16), F16)
-    y = torch.empty((5, N), dtype=torch.float32, device="cuda")
-    big = scap.Workspace(K, N, 5, F=F)
-    with pytest.raises(scap.ScapError) as e:
-        scap.swiglu_block(blk16.W_gu, blk16.W_down, x16, 0.0, 0.1, None, 0.0, 0.1, None, y=y, workspace=big)
-    assert e.value.status == -8      # five tokens over fp16 weights: not implemented (no matrix-core form)
     blk = Block(K, F, N, BF16, seed=920)
     x = to_dev(wl.laplace(5, K, 921, BF16), BF16)
     with pytest.raises(scap.ScapError) as e:
@@ -366,7 +360,7 @@ def test_blocks_on_two_streams_with_their_own_workspaces():
 
 
 def test_random_blocks():
-    """Seeded sweep over odd block shapes, 1-4 tokens, every weight dtype."""
+    """Seeded sweep over odd block shapes, 1-16 tokens, every weight dtype."""
     rng = np.random.default_rng(20241208)
     for case in range(24):
         dt = (F16, BF16, I8)[case % 3]
@@ -374,7 +368,7 @@ def test_random_blocks():
         K = int(rng.integers(8, 3000))
         F = (8 if dt == I8 else 4) * int(rng.integers(1, 600))
         N = (16 if dt == I8 else 8) * int(rng.integers(1, 300))
-        B = int(rng.choice([1, 1, 2, 3, 4]))
+        B = int(rng.choice([1, 1, 2, 3, 4, 6, 16]))
         blk = Block(K, F, N, dt, seed=5000 + case, B=B)
         X = wl.laplace(B, K, 6000 + case, xdt, loc=0.05, scale=0.9)
         zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.05, 0.3, 0.0, 0.0, dt, xdt, gate_scale=blk.sg,
