@@ -219,6 +219,7 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
                 uint64_t any_ok = 0;
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
+                    if (r == 1 && a.B <= 8) break;  // at most 8 tokens: the second token of every lane does not exist
                     const bool ok = oct_ok && (tg + 8 * r) < a.B;
                     any_ok |= __ballot(ok);
                     // an element that does not exist becomes a NaN: the strict compare drops it
