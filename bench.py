@@ -476,6 +476,18 @@ def main() -> int:
             sweep.append({"target_sparsity": s, "density": round(nn / K, 4), "us": round(e_ms * 1e3, 3),
                           "GBps": round(ab / (e_ms * 1e-3) / 1e9, 1),
                           "frac_of_8TBps": round(ab / (e_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+        # one launch on its own: event pair around a single eager launch of the headline call, GPU idle before
+        fn = launcher(s_head)
+        lat = []
+        for i in range(60):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1) * 1e3)
+        single_launch_us = round(float(np.median(lat[10:])), 2)
         # streaming-read ceiling of this machine: read the R weight copies once per launch
         chk = torch.zeros(2048, dtype=torch.int32, device=dev)
         w_ms, e_ms = time_steps(lambda i: scap.read_probe(Ws[i % R], chk), sub_steps, 50)
@@ -490,6 +502,7 @@ def main() -> int:
         fit = {"t0_us": round(float(coef[0]), 3), "t1_us": round(float(coef[1]), 3), "r2": round(r2, 5)}
     else:
         fit = None
+        single_launch_us = None
 
     # ---- CPU oracle on the host cores (baseline, not the target)
     cpu = None
@@ -538,6 +551,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "sweep": sweep,
         "read_ceiling_GBps": read_ceiling,
+        "single_eager_launch_us": single_launch_us,
         "latency_vs_density_fit": fit,
     }
     print(json.dumps(out))
