@@ -115,7 +115,29 @@ __device__ __forceinline__ void gemv_body(const GemvArgs& a) {
         // the end of the list are masked off for the load and the accumulation alike.
         const int n_blocks = (cnt + RPI - 1) / RPI;
         const int n_w = (n_blocks > w) ? (n_blocks - w + WAVES - 1) / WAVES : 0;
-        for (int i0 = 0; i0 < n_w; i0 += UNROLL) {
+        // Whole groups of UNROLL complete blocks first, without a predicate anywhere (a conditional load keeps
+        // the compiler from issuing a group's loads together); the ragged rest goes through the masked form.
+        const int n_complete = cnt / RPI;  // blocks whose RPI entries all exist
+        const int n_cw = (n_complete > w) ? (n_complete - w + WAVES - 1) / WAVES : 0;
+        const int n_main = n_cw - n_cw % UNROLL;
+        for (int i0 = 0; i0 < n_main; i0 += UNROLL) {
+            uint4 r[UNROLL];
+            float dv[UNROLL][BT];
+#pragma unroll
+            for (int q = 0; q < UNROLL; ++q) {
+                const int e = (w + WAVES * (i0 + q)) * RPI + sub_row;
+                const uint32_t row = (uint32_t)s_idx[e];
+                r[q] = load_weights16(wbase + (uint64_t)row * row_bytes + lane_off);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) dv[q][b] = s_d[b * a.Kc + e];
+            }
+#pragma unroll
+            for (int q = 0; q < UNROLL; ++q) {
+#pragma unroll
+                for (int b = 0; b < BT; ++b) fma_vec<WDT>(acc[b], r[q], dv[q][b]);
+            }
+        }
+        for (int i0 = n_main; i0 < n_w; i0 += UNROLL) {
             uint4 r[UNROLL];
             float dv[UNROLL][BT];
             bool ok[UNROLL];
