@@ -500,10 +500,10 @@ static int launch_inline_any(const GemvArgs& a, int wdt, int bt, bool raw, size_
 // Plan one launch: token slots, rows per workgroup (bounded by LDS and, for the input prologue, by the
 // registers that hold a wavefront's chunks), LDS bytes.
 static int plan_inline(GemvArgs& a, int wdt, int kc, bool kc_forced, int fuse, int* bt_out, size_t* lds_out,
-                       bool* raw_out = nullptr) {
+                       bool* raw_out = nullptr, bool slots16 = false) {
     if (wdt != kBF16 && wdt != kI8 && wdt != kF16) return SCAP_ERR_CONFIG;
     if (a.B < 1 || a.B > kMfmaTokens) return SCAP_ERR_CONFIG;
-    const int bt = a.B <= 4 ? 4 : 16;
+    const int bt = (a.B <= 4 && !slots16) ? 4 : 16;
     if (wdt == kF16 && bt != kMfmaTokens) return SCAP_ERR_CONFIG;  // fp16: the 16-slot kernels only
     const int tile_cols = wdt == kI8 ? 2 * kMfmaTile : kMfmaTile;
     size_t budget = kInlineLdsBudget;
@@ -533,7 +533,8 @@ static int plan_inline(GemvArgs& a, int wdt, int kc, bool kc_forced, int fuse, i
     return SCAP_OK;
 }
 
-int launch_gemm_inline(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipStream_t stream) {
+// slots16: run 2-4 tokens in the 16-slot kernels (the staged-tile form when the shape allows it)
+int launch_gemm_inline(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipStream_t stream, bool slots16) {
     GemvArgs a = a_in;
     if (a.B < kMfmaMinTokens) return SCAP_ERR_CONFIG;
     int kc = 0;
@@ -545,7 +546,7 @@ int launch_gemm_inline(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg
     int bt = 0;
     size_t lds = 0;
     bool raw = false;
-    const int rc = plan_inline(a, wdt, kc, kc != 0, kFusePlain, &bt, &lds, &raw);
+    const int rc = plan_inline(a, wdt, kc, kc != 0, kFusePlain, &bt, &lds, &raw, slots16);
     if (rc != SCAP_OK) return rc;
     a.Kl = a.Kc;
     a.Sl = a.S;

@@ -97,6 +97,14 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         return rc == SCAP_ERR_SHAPE ? SCAP_ERR_CONFIG : rc;
     }
     if (lanes == 1) return launch_gemm_mfma(a, wdt, cfg, stream);
+    // 3-4 tokens in the 16-slot staged-tile kernel: faster than the 4-slot forms for int8 weights unless the layer
+    // is very wide (its narrow tiles repeat the prologue), and than the vector kernel for a long input into a
+    // narrow bf16 layer (14336 x 4096, 4 tokens: 28.7 -> 27.3 us dense, 22.2 -> 20.0 at 90 %).
+    if (mfma_ok && lanes == 0 && a.B >= 3 && a.B <= 4 && a.K % 8 == 0 &&
+        ((wdt == kI8 && (int64_t)a.N <= 4 * (int64_t)a.K) || (wdt == kBF16 && (int64_t)a.K >= 2 * (int64_t)a.N))) {
+        const int rc = launch_gemm_inline(a, wdt, cfg, stream, true);
+        if (rc != SCAP_ERR_SHAPE) return rc;
+    }
     const bool mfma_auto = mfma_ok && lanes == 0 && a.B >= (wdt == kI8 ? kMfmaAutoTokensI8 : kMfmaAutoTokens);
     if (mfma_auto) {
         // one launch; the two-launch form takes over where the input is too long for LDS-sized pieces

@@ -108,7 +108,7 @@ constexpr int kMfmaAutoTokensI8 = 3;
 int launch_gemm_mfma(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
 // The same in one launch: each workgroup compacts its own inputs into LDS (up to 160 KB on gfx950).
 // SCAP_ERR_SHAPE when the input is too long to split into LDS-sized pieces.
-int launch_gemm_inline(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+int launch_gemm_inline(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream, bool slots16 = false);
 // The fused block's two launches on the same kernel (bf16 / int8, up to 16 tokens).
 int launch_swiglu_block_inline(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
 
