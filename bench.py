@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # size), keyed by workload; filled in from the summaries under profiles/.  None = not measured.
 MEASURED_TRAFFIC = {
     # profiles/gemv_kernel_bf16_mistral_down_hbm_traffic.txt
-    "mistral7b_down_14336x4096_bf16_b1_s50": 60188648,
+    "mistral7b_down_14336x4096_bf16_b1_s50": 60188739,
 }
 
 
