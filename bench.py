@@ -34,6 +34,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC = {
     # profiles/gemv_kernel_bf16_mistral_down_hbm_traffic.txt
     "mistral7b_down_14336x4096_bf16_b1_s50": 60188739,
+    # profiles/gemm_inline_raw_kernel_bf16_mistral_down_b16_s90_hbm_traffic.txt
+    "mistral7b_down_14336x4096_bf16_b16_s90": 104156846,
 }
 
 
@@ -346,6 +348,10 @@ def main() -> int:
     ap.add_argument("--suite", action="store_true",
                     help="time every benchmark configuration (layers of configs 1-5, batches, sparsities) instead "
                          "of the headline run")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="tokens per call on the headline layer (default 1 = the headline workload; other values "
+                         "time that batch alone, without the sweep and the CPU leg)")
+    ap.add_argument("--target", type=float, default=0.5, help="target sparsity of the timed point: 0.5, 0.7 or 0.9")
     ap.add_argument("--counter-pass", action="store_true",
                     help="for rocprofv3 --pmc runs: a few eager launches of a copy of known size, the headline "
                          "sparse FC and the dense FC, then exit (no timing, no JSON)")
@@ -384,10 +390,22 @@ def main() -> int:
     Ws = [W0] + [W0.clone() for _ in range(R - 1)]
     X = dev16(X_host)
     calib = dev16(calib_host)
-    ws = scap.Workspace(K, N, 1)
+    B = args.batch
+    if B < 1 or B > 16 or args.target not in site.targets:
+        print(f"bench.py: --batch 1..16, --target one of {site.targets}", file=sys.stderr)
+        return 2
+    if B > 1 or args.target != 0.5:
+        args.no_sweep = args.no_cpu = True
+    ws = scap.Workspace(K, N, B)
     ws_cal = scap.Workspace(K, 0, calib.shape[0])
-    y = torch.empty((1, N), dtype=torch.float32, device=dev)
+    y = torch.empty((B, N), dtype=torch.float32, device=dev)
     nnz_buf = torch.zeros(64, dtype=torch.int32, device=dev)
+
+    def xin(i):  # input of launch i: one test vector, or B consecutive ones
+        if B == 1:
+            return X[i % 64]
+        j = (i * B) % (64 - B + 1)
+        return X[j:j + B]
 
     # offline part through the library: (m, tau) per target, fused bias
     layer = {}
@@ -399,16 +417,19 @@ def main() -> int:
 
     def measured_nnz(s):
         m, tau, bf = layer[s]
-        for i in range(64):
-            scap.sparse_fc(Ws[0], X[i], m, tau, bf, y=y, nnz_out=nnz_buf[i:i + 1], workspace=ws, cfg=cfg)
+        for i in range(64):  # rows read per launch: the token's kept channels, or the union of the batch's
+            if B == 1:
+                scap.sparse_fc(Ws[0], xin(i), m, tau, bf, y=y, nnz_out=nnz_buf[i:i + 1], workspace=ws, cfg=cfg)
+            else:
+                scap.sparse_fc(Ws[0], xin(i), m, tau, bf, y=y, union_nnz_out=nnz_buf[i:i + 1], workspace=ws, cfg=cfg)
         torch.cuda.synchronize()
         return nnz_buf.cpu().numpy().astype(np.float64)
 
     def launcher(s):
         if s is None:
-            return lambda i: scap.dense_fc(Ws[i % R], X[i % 64], None, y=y, workspace=ws, cfg=cfg)
+            return lambda i: scap.dense_fc(Ws[i % R], xin(i), None, y=y, workspace=ws, cfg=cfg)
         m, tau, bf = layer[s]
-        return lambda i: scap.sparse_fc(Ws[i % R], X[i % 64], m, tau, bf, y=y, workspace=ws, cfg=cfg)
+        return lambda i: scap.sparse_fc(Ws[i % R], xin(i), m, tau, bf, y=y, workspace=ws, cfg=cfg)
 
     if args.counter_pass:
         # reference for scaling the byte counters: torch copies W (reads and writes wbytes_total each)
@@ -416,7 +437,7 @@ def main() -> int:
         for i in range(10):
             dst.copy_(Ws[i % R])
         torch.cuda.synchronize()
-        fn_s, fn_d = launcher(0.5), launcher(None)
+        fn_s, fn_d = launcher(args.target), launcher(None)
         for i in range(50):
             fn_s(i)
         torch.cuda.synchronize()
@@ -457,12 +478,12 @@ def main() -> int:
             t1 = time.perf_counter()
         return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
-    # ---- headline: 50 % target sparsity
-    s_head = 0.5
+    # ---- headline: 50 % target sparsity (or the point asked for)
+    s_head = args.target
     nnz_head = measured_nnz(s_head)
     wall_ms, ev_ms = time_steps(launcher(s_head), args.steps, args.warmup)
     mean_nnz = float(nnz_head.mean())
-    abytes = algorithmic_bytes(mean_nnz, K, N, 1, 2)
+    abytes = algorithmic_bytes(mean_nnz, K, N, B, 2)
     gbs = abytes / (ev_ms * 1e-3) / 1e9
 
     sweep = []
@@ -527,11 +548,13 @@ def main() -> int:
                          f"single thread: {round(us_1, 1)} us/token over {n1} tokens",
                "single_thread_us": round(us_1, 1)}
 
-    workload = "mistral7b_down_14336x4096_bf16_b1_s50"
+    workload = f"mistral7b_down_14336x4096_bf16_b{B}_s{int(round(s_head * 100))}"
+    kernel = ("scap::gemv_kernel<bf16>" if B <= 2 else
+              "scap::gemm_inline_raw_kernel<bf16> (matrix cores)")
     out = {
-        "metric": "sparse_fc_us_per_token",
+        "metric": "sparse_fc_us_per_token" if B == 1 else "sparse_fc_us_per_call",
         "value": round(wall_ms * 1e3, 3),
-        "unit": "us/token",
+        "unit": "us/token" if B == 1 else f"us/call of {B} tokens",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -541,12 +564,12 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": workload, "K": K, "N": N, "batch": 1, "target_sparsity": s_head,
+        "config": {"workload": workload, "K": K, "N": N, "batch": B, "target_sparsity": s_head,
                    "measured_density": round(mean_nnz / K, 4), "weight_copies_rotated": R,
                    "launch": "eager" if args.eager else "hipgraph", "launch_cfg": args.cfg or "default"},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(workload),
-                     "kernel": "scap::gemv_kernel<bf16>", "us_per_launch": round(ev_ms * 1e3, 3),
+                     "kernel": kernel, "us_per_launch": round(ev_ms * 1e3, 3),
                      "algorithmic_bytes_per_launch": int(abytes)},
         "cpu_baseline": cpu,
         "sweep": sweep,
