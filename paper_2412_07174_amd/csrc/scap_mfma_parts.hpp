@@ -123,24 +123,65 @@ __device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_
 }
 
 // Every wavefront holds a full [16 tokens x TILE columns] tile of sums in the same lane layout
-// (acc[e][i] = token 4*(l/16) + i, column ELEMS*(l%16) + e of the tile), so they are added as a binary tree over
-// the wavefronts through LDS (32 KB at s_tree), CH accumulators at a time: the upper half of the surviving
-// wavefronts writes, the lower half adds lane by lane (conflict-free 16-byte accesses, every lane busy, fixed
-// order), until wavefront 0 holds the workgroup's sums; those go through LDS to all threads, which store them.
-// Ends with a barrier.
+// (acc[e][i] = token 4*(l/16) + i, column ELEMS*(l%16) + e of the tile).  They are added through LDS (32 KB at
+// s_tree) in a fixed order and emitted by one thread per (token, 4-column group).  Ends with a barrier.
 // (FUSE / s_fin: see finish_columns -- with one split the sums are final and may go to the gating step)
-template <int WDT, int WAVES, int FUSE = kFusePlain>
+// ONE_LEVEL (8 wavefronts): the form described inside; otherwise a binary tree over the wavefronts.  The
+// two-launch kernel keeps the tree: the one-level form costs it registers it needs for two workgroups per CU.
+template <int WDT, int WAVES, int FUSE = kFusePlain, bool ONE_LEVEL = false>
 __device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgpu_buffer_rsrc_t pbuf, int tile, int split,
                                                       f32x4_t* __restrict__ acc, float* s_red, float* s_fin = nullptr) {
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr int TILE = 16 * ELEMS;
-    constexpr int CH = (WAVES <= 8) ? 8 : 4;  // (WAVES/2) * CH * 64 lanes * 16 bytes = 32 KB of LDS
-    static_assert(ELEMS % CH == 0, "accumulators are handed over in whole chunks");
     const int tid = threadIdx.x;
     const int w = uniform(tid >> 6);
     const int lane = tid & 63;
     const int cg = lane & 15, kg = lane >> 4;
     f32x4_t* s_tree = reinterpret_cast<f32x4_t*>(s_red);
+    static_assert(!ONE_LEVEL || WAVES == 8, "the one-level form is written for 8 wavefronts");
+    if constexpr (ONE_LEVEL) {
+        // One level, eight columns per lane at a time, the wavefronts in two halves: four wavefronts write their
+        // [16 tokens x 32 groups of 4 columns] (4 x 512 items x 16 bytes = 32 KB), every thread adds the four
+        // values of its (token, group) in wavefront order, then the other four -- a fixed association -- and
+        // emits the sum: consecutive threads hold consecutive groups, so a wavefront's stores are one contiguous
+        // KB (write-through stores of half-filled 32-byte sectors cost visibly more).  Four barriers per 8
+        // columns instead of seven with a tree plus a hand-over to the storing threads (1.3 -> 0.6 us at 16 tokens).
+        constexpr int ITEMS = kMfmaTokens * 32;
+        constexpr int H = WAVES / 2;
+        static_assert(H * ITEMS * 16 <= 32 * 1024 && ITEMS == WAVES * kWave, "reduction buffer, one item per thread");
+        static_assert(ELEMS % 8 == 0, "accumulators are handed over eight columns at a time");
+#pragma unroll
+        for (int c0 = 0; c0 < ELEMS; c0 += 8) {
+            f32x4_t t = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int hw = 0; hw < 2; ++hw) {
+                __syncthreads();  // the buffer is free (the list, or the previous values, have been read)
+                if (w / H == hw) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                        for (int v = 0; v < 2; ++v)
+                            s_tree[(w % H) * ITEMS + (4 * kg + i) * 32 + 2 * cg + v] =
+                                f32x4_t{acc[c0 + 4 * v][i], acc[c0 + 4 * v + 1][i], acc[c0 + 4 * v + 2][i], acc[c0 + 4 * v + 3][i]};
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int ww = 0; ww < H; ++ww) t += s_tree[ww * ITEMS + tid];
+            }
+            const int b = tid >> 5, gi = tid & 31;
+            if (b < a.B) {
+                const int g = ((gi >> 1) * ELEMS + c0) / 4 + (gi & 1);
+                // one split: this is the finished value, and the group's constants are loaded here
+                emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, make_float4(t[0], t[1], t[2], t[3]), s_fin,
+                                            a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
+            }
+        }
+        __syncthreads();
+        return;
+    }
+    constexpr int CH = (WAVES <= 8) ? 8 : 4;  // binary tree: (WAVES/2) * CH * 64 lanes * 16 bytes = 32 KB of LDS
+    static_assert(ELEMS % CH == 0, "accumulators are handed over in whole chunks");
 #pragma unroll
     for (int c0 = 0; c0 < ELEMS; c0 += CH) {
 #pragma unroll
@@ -157,8 +198,8 @@ __device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgp
             }
         }
         // Wavefront 0 holds the chunk's sums (lane = column group x row group).  They pass through LDS once more
-        // so that every thread emits one 4-column group of one token and a wavefront's 64 stores are contiguous
-        // (straight from wavefront 0's registers they were 8 strided stores per lane, ~2 us of the kernel).
+        // so that every thread emits one 4-column group of one token (straight from wavefront 0's registers they
+        // were strided stores of one wavefront, ~2 us of the kernel).
         constexpr int GPC = 16 * (CH / 4);  // 4-column groups of the chunk per token
         if (w == 0) {  // the only reader of the last tree level: no barrier needed before it writes
 #pragma unroll
@@ -175,7 +216,6 @@ __device__ __forceinline__ void reduce_waves_and_emit(const GemvArgs& a, __amdgp
             if (b < a.B) {
                 const f32x4_t t = s_tree[item];
                 const int g = ((gi / (CH / 4)) * ELEMS + c0) / 4 + gi % (CH / 4);
-                // one split: this is the finished value, and the group's constants are loaded here
                 emit_group<WDT, TILE, FUSE>(a, pbuf, tile, split, b, g, make_float4(t[0], t[1], t[2], t[3]), s_fin,
                                             a.S == 1 ? load_col_const<WDT, TILE>(a, tile, g) : ColConst{});
             }
