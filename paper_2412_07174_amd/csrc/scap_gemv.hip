@@ -18,7 +18,7 @@
 namespace scap {
 
 // ---------------------------------------------------------------------------------------------- launch
-int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced, size_t lds_budget) {
+int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced, size_t lds_budget, int granule) {
     a.T = (int)((a.N + tile - 1) / tile);
     if (a.T > kMaxTiles) return SCAP_ERR_SHAPE;
     // bounds from the workspace (at most kMaxSplits splits and partial_capacity floats per token) and from
@@ -29,19 +29,21 @@ int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_for
     if (s_cap < 1) s_cap = 1;
     const int kc_lds = (int)((lds_budget - kHdrBytes) / (4 * (1 + floats_per_entry)) / kWave * kWave);
     if (kc == 0) {
-        // Rows per workgroup, a multiple of 64.  Workgroups are spread over the 256 compute units, so the
+        // Rows per workgroup, a multiple of `granule`.  Workgroups are spread over the 256 compute units, so the
         // launch takes about as long as the busiest unit: ceil(workgroups / 256) workgroups, each costing
         // its kc rows plus a fixed part (prologue, reduction, hand-over) worth about kFixedRows rows.
         // Slightly more than 256 workgroups is the worst case (on 4096 x 28672, 280 workgroups of 832 rows
         // took 50.8 us, 224 of 1024 rows 38.2 us); more splits than needed only lengthen the final
         // reduction, so ties go to the larger kc.
+        // Candidates: for every split count the smallest kc (a multiple of `granule`) that gives it; any other
+        // kc with the same split count only costs more.
         constexpr int kFixedRows = 128;
-        int kc_max = (int)align_up((size_t)a.K, kWave);
-        if (kc_max > kc_lds) kc_max = kc_lds;
         long best_cost = -1;
-        for (int c = kc_max; c >= kWave; c -= kWave) {
+        const long s_max = (long)((a.K + granule - 1) / granule);
+        for (long sp = 1; sp <= s_max && (size_t)sp <= s_cap; ++sp) {
+            const int c = (int)align_up((size_t)((a.K + sp - 1) / sp), (size_t)granule);
+            if (c > kc_lds) continue;
             const long splits = (a.K + c - 1) / c;
-            if ((size_t)splits > s_cap) break;  // smaller c only means more splits
             const long cost = ((splits * a.T + 255) / 256) * (c + kFixedRows);
             if (best_cost < 0 || cost < best_cost) {
                 best_cost = cost;
@@ -134,6 +136,8 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         const int full_tiles = (a.N + 64 * elems - 1) / (64 * elems);
         if (full_tiles <= 4 || (bt > 1 && full_tiles <= 8 && a.K <= 8192)) lpr = 32;
     }
+    // (The vector kernel would take any multiple of 8 rows per workgroup -- 11008 rows as 32 x 344 instead of
+    // 29 x 384 -- but that measured faster only at medium sparsity and slower dense and on small layers.)
     const int rc = plan_splits(a, lpr * elems, bt, kc, cfg && cfg->rows_per_group);
     if (rc != SCAP_OK) {
         // a batch's kept-channel list of a very long input does not fit the vector kernel's LDS; the

@@ -786,6 +786,7 @@ inline size_t lds_bytes(int Kc, int floats_per_entry, size_t red_bytes) {
 // Choose the K split of a launch: fills a.T, a.Kc, a.S.  `tile` = columns per workgroup, `kc` = requested
 // rows per workgroup (0 = about one workgroup per compute unit).  Returns a scap_status.
 // `lds_budget` = LDS bytes one workgroup may use for its list.
-int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced, size_t lds_budget = 64 * 1024);
+int plan_splits(GemvArgs& a, int tile, int floats_per_entry, int kc, bool kc_forced, size_t lds_budget = 64 * 1024,
+                int granule = kWave);
 
 }  // namespace scap
