@@ -1,4 +1,7 @@
-// Batched sparse FC on the matrix cores in ONE launch (gfx950 MFMA), bf16 or int8 weights, 2..16 tokens.
+// Batched sparse FC on the matrix cores in ONE launch (gfx950 MFMA): bf16 or int8 weights from 2 tokens, fp16
+// weights from 5, up to 16 tokens.  Two kernels: gemm_inline_kernel (below) keeps per-token value lists in LDS;
+// gemm_inline_raw_kernel (further down, the default whenever K is a multiple of 8 and 16 token slots are used)
+// stages the raw input tile instead and forms the centred values when the MFMA operand is assembled.
 //
 // Workgroup (K split, column tile of 16 lanes x 16 bytes) centres, thresholds and compacts its Kc input
 // channels of every token into LDS exactly as the one-token kernel does (SCAP Alg. 3 steps 1-2; per-token
