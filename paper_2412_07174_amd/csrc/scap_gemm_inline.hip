@@ -210,13 +210,32 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
     // ---- stage, test, union mask per chunk
     uint64_t um[MAXC];
     int ucount = 0;
+    // The list only decides which rows are READ: what a token contributes is decided again, exactly, when the
+    // operand is assembled.  So the list may be a superset of the union.  With many tokens the union is nearly
+    // everything (Appendix C: 1 - s^B), and testing 16 tokens per channel to find that out is the larger part
+    // of this prologue.  Each wavefront therefore tests its first chunk; if at most 2 of its 64 channels are
+    // dropped by every token, it lists its other chunks whole (a few rows read for nothing against three
+    // quarters of the tests).  Dense mode lists everything without a test (there that is the exact union).
+    // The decision depends on the inputs only, so every column tile of a split takes the same one.  Column
+    // tile 0 tests everything when the caller asked for the size of the union, which has to be exact.
+    const bool exact_only = tile == 0 && a.union_nnz_out != nullptr;
     auto test_chunks = [&](auto bf16x) {
         constexpr bool BF16X = decltype(bf16x)::value;
+        bool assume_full = dense;  // wave-uniform
 #pragma unroll
         for (int j = 0; j < MAXC; ++j) {
             const int c = c_begin + j;
             um[j] = 0;
-            if (c < c_end) {  // wave-uniform
+            if (c < c_end && assume_full) {  // wave-uniform: stage the chunk, list all its channels
+                const int nval = min((int)kWave, kend - (k0 + c * kWave));
+#pragma unroll
+                for (int r = 0; r < 2; ++r) {
+                    if (r == 1 && a.B <= 8) break;
+                    *reinterpret_cast<uint4*>(xs + (size_t)(tg + 8 * r) * xrow + (size_t)(c * kWave + 8 * o) * 2) = xv[j][r];
+                }
+                um[j] = nval >= kWave ? ~0ull : ((1ull << nval) - 1ull);
+                ucount += nval;
+            } else if (c < c_end) {  // wave-uniform
                 const bool oct_ok = (k0 + c * kWave + 8 * o) < kend;  // K and Kc are multiples of 8: whole octets
                 uint64_t kp[8];  // lane masks (bit tg + 8*o): channel 8*o+e kept by token tg or tg+8
                 uint64_t any_ok = 0;
@@ -248,6 +267,7 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
                 }
                 um[j] = u;  // bit i: channel i of the chunk is kept by some token
                 ucount += __popcll(u);
+                if (j == 0 && !exact_only && __popcll(u) + 2 >= min((int)kWave, kend - (k0 + c * kWave))) assume_full = true;
             }
         }
     };
