@@ -176,7 +176,7 @@ __device__ __forceinline__ float word_half_to_f32(uint32_t wd, int half) {
 // a nonzero-byte test.  Everything in the test is straight-line: the instruction count per element is what the
 // prologue costs, repeated by every column tile.  Per-token lists and counts (column tile 0, on request) are
 // read back from the staged tile with one channel per lane.  Returns the list length; ends with a barrier.
-template <int WAVES, int MAXC>
+template <int WAVES, int MAXC, bool SUPERSET>
 __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile, int split, const Lds& L, char* xs,
                                                      uint32_t xrow) {
     constexpr int BT = kMfmaTokens;
@@ -221,12 +221,11 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
     const bool exact_only = tile == 0 && a.union_nnz_out != nullptr;
     auto test_chunks = [&](auto bf16x) {
         constexpr bool BF16X = decltype(bf16x)::value;
-        bool assume_full = dense;  // wave-uniform
-#pragma unroll
-        for (int j = 0; j < MAXC; ++j) {
+        // stage chunk slot j and list all its channels (wave-uniform)
+        auto list_whole = [&](int j) {
             const int c = c_begin + j;
             um[j] = 0;
-            if (c < c_end && assume_full) {  // wave-uniform: stage the chunk, list all its channels
+            if (c < c_end) {
                 const int nval = min((int)kWave, kend - (k0 + c * kWave));
 #pragma unroll
                 for (int r = 0; r < 2; ++r) {
@@ -235,7 +234,13 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
                 }
                 um[j] = nval >= kWave ? ~0ull : ((1ull << nval) - 1ull);
                 ucount += nval;
-            } else if (c < c_end) {  // wave-uniform
+            }
+        };
+        // stage chunk slot j and list the channels kept by at least one token
+        auto test_slot = [&](int j) {
+            const int c = c_begin + j;
+            um[j] = 0;
+            if (c < c_end) {  // wave-uniform
                 const bool oct_ok = (k0 + c * kWave + 8 * o) < kend;  // K and Kc are multiples of 8: whole octets
                 uint64_t kp[8];  // lane masks (bit tg + 8*o): channel 8*o+e kept by token tg or tg+8
                 uint64_t any_ok = 0;
@@ -267,8 +272,26 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
                 }
                 um[j] = u;  // bit i: channel i of the chunk is kept by some token
                 ucount += __popcll(u);
-                if (j == 0 && !exact_only && __popcll(u) + 2 >= min((int)kWave, kend - (k0 + c * kWave))) assume_full = true;
             }
+        };
+        if constexpr (SUPERSET) {
+            if (dense) {  // every element that exists is kept: the list is all valid channels, exactly
+#pragma unroll
+                for (int j = 0; j < MAXC; ++j) list_whole(j);
+                return;
+            }
+            test_slot(0);
+            const int nval0 = c_begin < c_end ? min((int)kWave, kend - (k0 + c_begin * kWave)) : 0;
+            if (!exact_only && __popcll(um[0]) + 2 >= nval0) {  // wave-uniform
+#pragma unroll
+                for (int j = 1; j < MAXC; ++j) list_whole(j);
+            } else {
+#pragma unroll
+                for (int j = 1; j < MAXC; ++j) test_slot(j);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < MAXC; ++j) test_slot(j);
         }
     };
     if (a.xdt == kBF16)
@@ -360,7 +383,9 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_raw_kernel(co
     const ColConst mine = load_col_const<WDT, TILE>(a, tile, tid % (TILE / 4));
 
     // ------------------------------------------------------------------ 1. stage the inputs, list the union
-    const int cnt = stage_inputs_and_list<WAVES, kRawChunks>(a, tile, split, L, xs, xrow);
+    // int8 weights: 256-column tiles, so half as many workgroups repeat a split's prologue and a wavefront has
+    // two chunks; listing supersets measured no gain there (and 0.14 us lost to the extra code)
+    const int cnt = stage_inputs_and_list<WAVES, kRawChunks, WDT != kI8>(a, tile, split, L, xs, xrow);
     const int n_blocks = (cnt + kMfmaBlock - 1) / kMfmaBlock;
 
     // ------------------------------------------------------------------ 2. stream the kept rows
