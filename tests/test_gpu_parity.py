@@ -294,6 +294,31 @@ def test_staged_tile_kernel_shapes(K, N, B, wdt, xdt):
     assert_y_close(y.cpu().numpy(), oracle.dense_fc(W, X, bias, wdt, xdt, col_scale=scale), "staged dense")
 
 
+@pytest.mark.parametrize("wdt", [BF16, F16])
+def test_staged_tile_kernel_lists_a_superset_of_the_union(wdt):
+    """A wavefront whose first 64-channel chunk is kept entirely lists its other chunks without testing them.
+    Here every fourth chunk holds large values and the three after it values that every token drops, with 1792
+    channels per workgroup (4 chunks per wavefront): the lists are four times the union, and y, the per-token
+    lists and the size of the union (column tile 0 tests everything when they are asked for) must not change."""
+    K, N, B = 7168, 392, 16
+    W = wl.weights(K, N, 541, wdt)
+    layer = Layer(W, wdt, B=16)
+    rng = np.random.default_rng(542)
+    big = rng.choice([-1.0, 1.0], size=(B, K)) * rng.uniform(1.0, 2.0, size=(B, K))
+    small = rng.uniform(-0.05, 0.05, size=(B, K))
+    chunk = (np.arange(K) // 64) % 4
+    Xf = np.where(chunk[None, :] == 0, big, small)
+    Xf[3, 64 * 4 * 5 + 7] = 0.01     # one token drops a channel of a "large" chunk; the others keep it
+    Xf[:, 64 * 4 * 9 + 11] = 0.02    # a channel of a "large" chunk dropped by every token (still at most 2 of 64)
+    Xf[5, 64 * 13 + 3] = 1.5         # one token keeps a channel inside a "small" chunk
+    X = wl.encode(Xf, wdt)
+    bias = rng.standard_normal(N).astype(np.float32)
+    for cfg in ((0, 1792, 0, 16), None):
+        say(f"superset lists wdt={wdt} cfg={cfg}")
+        got, want = check_against_oracle(layer, X, wdt, 0.0, 0.5, bias, cfg=cfg, what=f"superset cfg={cfg}")
+        assert want["union_nnz"] == (K // 256) * 64 - 1 + 1
+
+
 @pytest.mark.parametrize("B", [4, 16])
 def test_batched_tokens_fp16_weights(B):
     K, N = 1500, 1032
