@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_kernel(const 
 
     // ------------------------------------------------------------------ 3. add the wavefronts' sums
     const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
-    reduce_waves_and_emit<WDT, WAVES, FUSE, true>(a, pbuf, tile, split, acc, L.red, L.fin);  // starts with a barrier: the list is done with
+    reduce_waves_and_emit<WDT, WAVES, FUSE, WDT != kI8>(a, pbuf, tile, split, acc, L.red, L.fin);  // starts with a barrier: the list is done with
 
     // ------------------------------------------------------------------ 4. last arrival finishes the tile
     finish_tile<WDT, WAVES, TILE, BT, FUSE>(a, pbuf, tile, L, mine);
@@ -479,7 +479,7 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_raw_kernel(co
 
     // ------------------------------------------------------------------ 3. add the wavefronts' sums
     const __amdgpu_buffer_rsrc_t pbuf = partial_buffer<TILE>(a);
-    reduce_waves_and_emit<WDT, WAVES, FUSE, true>(a, pbuf, tile, split, acc, L.red, L.fin);  // starts with a barrier: the tile is done with
+    reduce_waves_and_emit<WDT, WAVES, FUSE, WDT != kI8>(a, pbuf, tile, split, acc, L.red, L.fin);  // starts with a barrier: the tile is done with
 
     // ------------------------------------------------------------------ 4. last arrival finishes the tile
     finish_tile<WDT, WAVES, TILE, BT, FUSE>(a, pbuf, tile, L, mine);
