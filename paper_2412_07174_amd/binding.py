@@ -122,6 +122,64 @@ def _code(t: torch.Tensor, what: str) -> int:
         raise TypeError(f"{what}: dtype {t.dtype} is not float16, bfloat16 or int8") from None
 
 
+_ACT = (torch.float16, torch.bfloat16)
+_WGT = (torch.float16, torch.bfloat16, torch.int8)
+
+
+class _Args:
+    """Validation of one call's tensors.  The binding hands raw pointers to the kernels, so a tensor of the wrong
+    dtype, layout or shape would be read or written out of bounds on the device: refuse it here."""
+
+    def __init__(self):
+        self.seen = []
+
+    def want(self, t: Optional[torch.Tensor], what: str, shape=None, dtype=None, optional: bool = False) -> None:
+        if t is None:
+            if optional:
+                return
+            raise TypeError(f"{what}: a tensor is required")
+        if not isinstance(t, torch.Tensor):
+            raise TypeError(f"{what}: expected a torch.Tensor, got {type(t).__name__}")
+        if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+            raise TypeError(f"{what}: dtype {t.dtype}, expected {dtype}")
+        if not t.is_contiguous():
+            raise ValueError(f"{what}: must be contiguous (shape {tuple(t.shape)}, strides {t.stride()})")
+        if shape is not None and tuple(t.shape) not in (shape if isinstance(shape, list) else [shape]):
+            raise ValueError(f"{what}: shape {tuple(t.shape)}, expected {shape}")
+        self.seen.append((what, t))   # where it lives is checked last, by on_one_gpu()
+
+    def on_one_gpu(self, workspace=None) -> None:
+        """Every tensor of the call, and the workspace, on one GPU."""
+        seen = list(self.seen)
+        if isinstance(workspace, Workspace):
+            seen.append(("workspace", workspace.buf))
+        first = None
+        for what, t in seen:
+            if not t.is_cuda:
+                raise ValueError(f"{what}: must live on the GPU, is on {t.device}")
+            if first is None:
+                first = (what, t.device)
+            elif t.device != first[1]:
+                raise ValueError(f"{what}: on {t.device}, but {first[0]} is on {first[1]}")
+        if workspace is not None and not isinstance(workspace, Workspace):
+            raise TypeError("workspace: expected a Workspace")
+
+    def weights(self, W: torch.Tensor, col_scale, what: str = "W") -> None:
+        self.want(W, what, dtype=_WGT)
+        if W.dim() != 2:
+            raise ValueError(f"{what}: expected a [K, N] matrix, got shape {tuple(W.shape)}")
+        if W.dtype == torch.int8:
+            self.want(col_scale, f"{what} column scales", shape=(W.shape[1],), dtype=torch.float16)
+        elif col_scale is not None:
+            raise TypeError(f"{what}: column scales go with int8 weights only")
+
+    def tokens(self, x: torch.Tensor, K: int, what: str = "x") -> int:
+        self.want(x, what, dtype=_ACT)
+        if x.dim() not in (1, 2) or x.shape[-1] != K:
+            raise ValueError(f"{what}: shape {tuple(x.shape)}, expected [{K}] or [B, {K}]")
+        return 1 if x.dim() == 1 else x.shape[0]
+
+
 def _cfg(cfg):
     if cfg is None:
         return None
@@ -152,6 +210,11 @@ def calibrate(X_calib: torch.Tensor, target_sparsity: float, est: int = MODE_MED
               stream=None) -> Tuple[float, float]:
     """(m, tau) of one layer from its calibration activations [n, K] (device tensor, fp16/bf16)."""
     lib = load_library()
+    a = _Args()
+    a.want(X_calib, "X_calib", dtype=_ACT)
+    if X_calib.dim() != 2:
+        raise ValueError(f"X_calib: expected [n, K], got shape {tuple(X_calib.shape)}")
+    a.on_one_gpu(workspace)
     n, K = X_calib.shape
     m, tau = ctypes.c_float(0), ctypes.c_float(0)
     rc = lib.scap_calibrate(_ptr(X_calib), n, K, _code(X_calib, "X_calib"), float(target_sparsity), int(est),
@@ -163,7 +226,12 @@ def calibrate(X_calib: torch.Tensor, target_sparsity: float, est: int = MODE_MED
 def fold_bias(W: torch.Tensor, m: float, bias: Optional[torch.Tensor] = None, *, col_scale=None,
               out: Optional[torch.Tensor] = None, workspace: Workspace, stream=None) -> torch.Tensor:
     lib = load_library()
+    a = _Args()
+    a.weights(W, col_scale)
     K, N = W.shape
+    a.want(bias, "bias", shape=(N,), dtype=torch.float32, optional=True)
+    a.want(out, "out", shape=(N,), dtype=torch.float32, optional=True)
+    a.on_one_gpu(workspace)
     if out is None:
         out = torch.empty(N, dtype=torch.float32, device=W.device)
     rc = lib.scap_fold_bias(_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(bias), float(m), _ptr(out),
@@ -177,10 +245,23 @@ def sparse_fc(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_fused: O
               workspace: Workspace, cfg=None, stream=None) -> torch.Tensor:
     """y[B,N] = ((x - m) masked by |x - m| > tau) @ W + b_fused.  x is [K] or [B, K]."""
     lib = load_library()
+    a = _Args()
+    a.weights(W, col_scale)
     K, N = W.shape
-    B = 1 if x.dim() == 1 else x.shape[0]
+    B = a.tokens(x, K, W.device)
+    a.want(b_fused, "b_fused", shape=(N,), dtype=torch.float32, optional=True)
+    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32, optional=True)
+    a.want(idx_out, "idx_out", shape=[(B, K)] + ([(K,)] if B == 1 else []), dtype=torch.int32,
+          optional=True)
+    for t, what in ((nnz_out, "nnz_out"), (union_nnz_out, "union_nnz_out")):
+        a.want(t, what, dtype=torch.int32, optional=True)
+    if nnz_out is not None and nnz_out.numel() < B:
+        raise ValueError(f"nnz_out: {nnz_out.numel()} entries for {B} tokens")
+    if union_nnz_out is not None and union_nnz_out.numel() < 1:
+        raise ValueError("union_nnz_out: needs one entry")
+    a.on_one_gpu(workspace)
     if y is None:
-        y = torch.empty((B, N), dtype=torch.float32, device=W.device)
+        y = torch.empty((B, N), dtype=torch.float32, device=x.device)
     args = [_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(x), _code(x, "x"), B, float(m), float(tau),
             _ptr(b_fused), _ptr(y), _ptr(idx_out), _ptr(nnz_out), _ptr(union_nnz_out), _ptr(workspace.buf),
             workspace.nbytes, _stream(stream)]
@@ -195,10 +276,15 @@ def sparse_fc(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_fused: O
 def dense_fc(W: torch.Tensor, x: torch.Tensor, bias: Optional[torch.Tensor] = None, *, col_scale=None,
              y: Optional[torch.Tensor] = None, workspace: Workspace, cfg=None, stream=None) -> torch.Tensor:
     lib = load_library()
+    a = _Args()
+    a.weights(W, col_scale)
     K, N = W.shape
-    B = 1 if x.dim() == 1 else x.shape[0]
+    B = a.tokens(x, K, W.device)
+    a.want(bias, "bias", shape=(N,), dtype=torch.float32, optional=True)
+    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32, optional=True)
+    a.on_one_gpu(workspace)
     if y is None:
-        y = torch.empty((B, N), dtype=torch.float32, device=W.device)
+        y = torch.empty((B, N), dtype=torch.float32, device=x.device)
     rc = lib.scap_dense_fc(_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(x), _code(x, "x"), B, _ptr(bias),
                            _ptr(y), _ptr(workspace.buf), workspace.nbytes, _stream(stream), _cfg(cfg))
     _check(rc, "scap_dense_fc")
@@ -207,7 +293,12 @@ def dense_fc(W: torch.Tensor, x: torch.Tensor, bias: Optional[torch.Tensor] = No
 
 def pack_gate_up(gate: torch.Tensor, up: torch.Tensor, stream=None) -> torch.Tensor:
     """[rows, 2F] (or [2F]) interleaving of two [rows, F] (or [F]) tensors in groups of 4 columns."""
-    assert gate.shape == up.shape and gate.dtype == up.dtype and gate.is_contiguous() and up.is_contiguous()
+    a = _Args()
+    a.want(gate, "gate")
+    a.want(up, "up", shape=tuple(gate.shape), dtype=gate.dtype)
+    if gate.dim() not in (1, 2):
+        raise ValueError(f"gate: expected [F] or [rows, F], got shape {tuple(gate.shape)}")
+    a.on_one_gpu()
     rows = 1 if gate.dim() == 1 else gate.shape[0]
     F = gate.shape[-1]
     out = torch.empty(gate.shape[:-1] + (2 * F,), dtype=gate.dtype, device=gate.device)
@@ -222,13 +313,27 @@ def swiglu_block(W_gu: torch.Tensor, W_down: torch.Tensor, x: torch.Tensor, m_x:
                  nnz_z_out=None, workspace: Workspace, stream=None) -> torch.Tensor:
     """y[N] of the SwiGLU block: W_gu is the packed [K, 2F] gate|up matrix, W_down is [F, N]."""
     lib = load_library()
+    a = _Args()
+    a.weights(W_gu, gu_scale, "W_gu")
+    a.weights(W_down, down_scale, "W_down")
     K, F2 = W_gu.shape
     F, N = W_down.shape
     if F2 != 2 * F:
         raise ValueError(f"W_gu has {F2} columns, W_down has {F} rows")
-    B = 1 if x.dim() == 1 else x.shape[0]
+    B = a.tokens(x, K, W_gu.device)
+    dev = W_gu.device
+    a.want(b_gu_fused, "b_gu_fused", shape=(2 * F,), dtype=torch.float32, optional=True)
+    a.want(b_down_fused, "b_down_fused", shape=(N,), dtype=torch.float32, optional=True)
+    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32, optional=True)
+    one = [(F,)] if B == 1 else []
+    a.want(z_out, "z_out", shape=[(B, F)] + one, dtype=torch.float32, optional=True)
+    a.want(idx_z_out, "idx_z_out", shape=[(B, F)] + one, dtype=torch.int32, optional=True)
+    a.want(nnz_z_out, "nnz_z_out", dtype=torch.int32, optional=True)
+    if nnz_z_out is not None and nnz_z_out.numel() < B:
+        raise ValueError(f"nnz_z_out: {nnz_z_out.numel()} entries for {B} tokens")
+    a.on_one_gpu(workspace)
     if y is None:
-        y = torch.empty((B, N), dtype=torch.float32, device=W_gu.device)
+        y = torch.empty((B, N), dtype=torch.float32, device=x.device)
     if _code(W_gu, "W_gu") != _code(W_down, "W_down"):
         raise TypeError("W_gu and W_down must have one dtype")
     rc = lib.scap_swiglu_block(_ptr(W_gu), _ptr(gu_scale), _ptr(W_down), _ptr(down_scale), K, F, N, _code(W_gu, "W_gu"),
@@ -240,5 +345,11 @@ def swiglu_block(W_gu: torch.Tensor, W_down: torch.Tensor, x: torch.Tensor, m_x:
 
 
 def read_probe(src: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    a = _Args()
+    a.want(src, "src")
+    a.want(out, "out", dtype=(torch.int32, torch.uint32))
+    if out.numel() < 2048:
+        raise ValueError("out: needs 2048 entries (SCAP_PROBE_SLOTS)")
+    a.on_one_gpu()
     rc = load_library().scap_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(out), _stream(stream))
     _check(rc, "scap_read_probe")

@@ -8,6 +8,7 @@
 // subtraction): order statistics by walking the counts in value order -- exact, no float error -- the mean
 // as an fp64 sum of count x value, the histogram mode from fp64 bin arithmetic.
 #include <math.h>
+#include <cmath>
 #include <string.h>
 
 #include <algorithm>
@@ -188,11 +189,44 @@ float select_centred(const Table& t, float m, unsigned long long k) {
     return quiet_nan();
 }
 
-int64_t rank_of(double q, int64_t M) {
-    int64_t k = (int64_t)ceil(q * (double)M);
-    if (k < 0) k = 0;
-    if (k > M) k = M;
-    return k;
+// 1-based rank of the q-quantile among M pooled values: the smallest integer >= q*M (product formed in fp64),
+// kept inside [0, M]
+int64_t quantile_rank(double q, int64_t M) {
+    return std::min<int64_t>(M, std::max<int64_t>(0, (int64_t)std::ceil(q * (double)M)));
+}
+
+// Histogram estimate of the mode from the (value, count) table: kHistBins equal bins between the 0.001 and
+// 0.999 order statistics (a value equal to the upper one belongs to the last bin), each bin scored by the
+// number of samples in the five bins centred on it (fewer at the edges), the centre of the first bin with the
+// top score.  The bins are filled as a running total, so a score is the difference of two totals.
+float histogram_mode(const Table& t, int64_t M) {
+#pragma clang fp contract(off)  // (b + 1/2) * w and lo + ... each round once, in fp64
+    const float lo = select_raw(t, (unsigned long long)std::max<int64_t>(1, quantile_rank(0.001, M)));
+    const float hi = select_raw(t, (unsigned long long)std::max<int64_t>(1, quantile_rank(0.999, M)));
+    if (!(hi > lo)) return lo;
+    const double width = ((double)hi - (double)lo) / (double)kHistBins;
+    // upto[b] = samples in bins 0 .. b-1; the table is ascending, so bins are met in order
+    std::vector<unsigned long long> upto(kHistBins + 1, 0);
+    for (size_t i = 0; i < t.val.size(); ++i) {
+        const float v = t.val[i];
+        if (v < lo || v > hi) continue;
+        const double pos = std::floor(((double)v - (double)lo) / width);
+        const int bin = pos >= (double)kHistBins ? kHistBins - 1 : (int)pos;
+        upto[bin + 1] += t.cnt[i];
+    }
+    for (int b = 0; b < kHistBins; ++b) upto[b + 1] += upto[b];
+    int top_bin = 0;
+    unsigned long long top = 0;
+    for (int b = 0; b < kHistBins; ++b) {
+        const unsigned long long score = upto[std::min(b + 3, kHistBins)] - upto[std::max(b - 2, 0)];
+        if (b == 0 || score > top) {
+            top = score;
+            top_bin = b;
+        }
+    }
+    const double offset = ((double)top_bin + 0.5) * width;
+    const double centre = (double)lo + offset;
+    return (float)centre;
 }
 
 }  // namespace
@@ -238,43 +272,11 @@ int run_calibrate(const uint16_t* X, int64_t M, int xdt, float s, int est, float
             m = (float)(((double)a + (double)b) / 2.0);
         }
     } else if (est == SCAP_MODE_HIST) {
-        int64_t klo = rank_of(0.001, M), khi = rank_of(0.999, M);
-        if (klo < 1) klo = 1;
-        if (khi < 1) khi = 1;
-        const float lo = select_raw(t, (unsigned long long)klo), hi = select_raw(t, (unsigned long long)khi);
-        if (!(hi > lo)) {
-            m = lo;
-        } else {
-            // 2048 equal bins between lo and hi (inclusive), bin = floor((v - lo) / w) in fp64
-            const double w = ((double)hi - (double)lo) / (double)kHistBins;
-            std::vector<long long> cnt(kHistBins, 0);
-            for (size_t i = 0; i < t.val.size(); ++i) {
-                const float v = t.val[i];
-                if (!(v >= lo && v <= hi)) continue;
-                long long b = (long long)floor(((double)v - (double)lo) / w);
-                if (b > kHistBins - 1) b = kHistBins - 1;
-                if (b < 0) b = 0;
-                cnt[b] += (long long)t.cnt[i];
-            }
-            long long best = -1;
-            int bestb = 0;
-            for (int b = 0; b < kHistBins; ++b) {
-                long long sum = 0;
-                for (int q = b - 2; q <= b + 2; ++q)
-                    if (q >= 0 && q < kHistBins) sum += cnt[q];
-                if (sum > best) {
-                    best = sum;
-                    bestb = b;
-                }
-            }
-            volatile double centre = ((double)bestb + 0.5) * w;
-            volatile double mode = (double)lo + centre;
-            m = (float)mode;
-        }
+        m = histogram_mode(t, M);
     }
 
     float tau = 0.f;
-    const int64_t k = rank_of((double)s, M);
+    const int64_t k = quantile_rank((double)s, M);
     if (k > 0) tau = select_centred(t, m, (unsigned long long)k);
     *m_out = m;
     *tau_out = tau;

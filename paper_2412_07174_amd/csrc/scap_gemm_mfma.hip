@@ -351,12 +351,18 @@ int launch_gemm_mfma(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, 
     a.S = (a.K + a.Kc - 1) / a.Kc;
     if ((size_t)a.S * a.T * tile_cols > partial_capacity(a.N)) return SCAP_ERR_SHAPE;
 
-    hipLaunchKernelGGL(batch_union_kernel, dim3((unsigned)a.Sl), dim3(kCompactWaves * kWave), 0, stream, a);
-    if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
-
+    // Everything that can refuse the call comes before the first launch: the union kernel already writes the
+    // caller's lists and counts.
+    const bool instantiated = (wdt == kBF16 && (waves == 16 || waves == 8) && (ub == 1 || ub == 2 || ub == 4)) ||
+                              (wdt == kI8 && waves == 8 && (ub == 1 || ub == 2));
+    if (!instantiated) return SCAP_ERR_CONFIG;
     // tree reduction buffer: 32 KB (the final reduction needs less)
     const size_t lds = lds_bytes(0, 0, (size_t)32 * 1024);
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
+
+    hipLaunchKernelGGL(batch_union_kernel, dim3((unsigned)a.Sl), dim3(kCompactWaves * kWave), 0, stream, a);
+    if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
+
     const dim3 grid((unsigned)(a.S * a.T));
     const dim3 block(waves * kWave);
 #define SCAP_MFMA_CASE(WD, WV, UBV)                                                                 \
@@ -368,7 +374,7 @@ int launch_gemm_mfma(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, 
     SCAP_MFMA_CASE(kBF16, 8, 1) SCAP_MFMA_CASE(kBF16, 8, 2) SCAP_MFMA_CASE(kBF16, 8, 4)
     SCAP_MFMA_CASE(kI8, 8, 1) SCAP_MFMA_CASE(kI8, 8, 2)
 #undef SCAP_MFMA_CASE
-    return SCAP_ERR_CONFIG;
+    return SCAP_ERR_CONFIG;  // not reached: `instantiated` lists the same table
 }
 
 }  // namespace scap

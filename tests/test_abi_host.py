@@ -150,3 +150,44 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "scap_oracle" not in text, f
+
+
+def test_binding_refuses_tensors_the_kernels_would_overrun(lib):
+    """The binding hands raw pointers to the kernels, so it checks dtype, layout, shape and device of every tensor
+    first (CPU tensors suffice here: the device check comes last and nothing is launched)."""
+    import torch
+
+    class FakeWs:
+        pass
+
+    K, N = 64, 32
+    W = torch.zeros((K, N), dtype=torch.bfloat16)
+    x = torch.zeros(K, dtype=torch.bfloat16)
+    ws = FakeWs()
+    with pytest.raises(ValueError, match="contiguous"):        # a torch Linear weight viewed as [K, N]
+        scap.sparse_fc(torch.zeros((N, K), dtype=torch.bfloat16).t(), x, 0.0, 0.1, workspace=ws)
+    with pytest.raises(ValueError, match="shape"):             # input shorter than K
+        scap.sparse_fc(W, x[:-8], 0.0, 0.1, workspace=ws)
+    with pytest.raises(TypeError, match="dtype"):
+        scap.sparse_fc(W, x.float(), 0.0, 0.1, workspace=ws)
+    with pytest.raises(TypeError, match="dtype"):
+        scap.sparse_fc(W.float(), x, 0.0, 0.1, workspace=ws)
+    with pytest.raises(TypeError, match="required"):           # int8 weights without their scales
+        scap.sparse_fc(W.to(torch.int8), x, 0.0, 0.1, workspace=ws)
+    with pytest.raises(ValueError, match="shape"):             # undersized output
+        scap.sparse_fc(W, x, 0.0, 0.1, y=torch.zeros((1, N - 8)), workspace=ws)
+    with pytest.raises(ValueError, match="shape"):             # undersized index list
+        scap.sparse_fc(W, x, 0.0, 0.1, idx_out=torch.zeros((1, K - 1), dtype=torch.int32),
+                       nnz_out=torch.zeros(1, dtype=torch.int32), workspace=ws)
+    with pytest.raises(ValueError, match="shape"):
+        scap.sparse_fc(W, x, 0.0, 0.1, torch.zeros(N + 8), workspace=ws)
+    with pytest.raises(ValueError, match="shape"):
+        scap.dense_fc(W, torch.zeros((3, K + 1), dtype=torch.bfloat16), workspace=ws)
+    with pytest.raises(ValueError, match="shape"):
+        scap.fold_bias(W, 0.1, torch.zeros(N - 1), workspace=ws)
+    with pytest.raises(ValueError, match="expected"):
+        scap.calibrate(x, 0.5, workspace=ws)                    # a vector, not [n, K]
+    with pytest.raises(ValueError, match="W_down has"):
+        scap.swiglu_block(W, torch.zeros((N, 8), dtype=torch.bfloat16), x, 0.0, 0.1, None, 0.0, 0.1, None, workspace=ws)
+    with pytest.raises(ValueError, match="GPU"):               # everything right except where it lives
+        scap.sparse_fc(W, x, 0.0, 0.1, workspace=ws)

@@ -330,13 +330,15 @@ def test_batched_tokens_fp16_weights(B):
         check_against_oracle(layer, X, F16, 0.1, tau, None, what=f"fp16 B={B} tau={tau}")
 
 
-@pytest.mark.parametrize("which,B", [(0, 4), (1, 4), (1, 16)])
+@pytest.mark.parametrize("which,B", [(0, 4), (0, 16), (1, 4), (1, 16)])
 def test_config4_batched_full_size(which, B):
+    """Both layers of the batched configuration at full size, 4 tokens (vector kernel / 16-slot staged tile) and 16
+    tokens (staged-tile kernel: 112 narrow column tiles on 4096 -> 14336), at the three per-token targets."""
     site = wl.sites(4)[which]
     layer = Layer(site.make_weights(), site.wdt, B=16)
     calib = site.calib()
     X = site.draw(B, site.seed_test + 77)
-    for s in (0.7, 0.9):
+    for s in (0.5, 0.7, 0.9):
         _, tau = oracle.calibrate(calib, site.xdt, s, oracle.MODE_ZERO)
         say(f"config4 {site.name} B={B} s={s}")
         got, want = check_against_oracle(layer, X, site.xdt, 0.0, tau, None, what=f"{site.name} B={B} s={s}")
@@ -464,6 +466,55 @@ def test_calibrate_paper_sized_sample():
     v = np.abs(wl.decode(X, BF16).astype(np.float32)).ravel()
     k = int(np.ceil(np.float64(np.float32(0.9)) * v.size))
     assert tau == float(np.partition(v, k - 1)[k - 1])
+
+
+def test_calibrate_paper_sized_sample_of_the_widest_input():
+    """16384 tokens of the 14336-wide down-projection input: 235 million pooled values.  Sorting that many on the
+    host takes minutes, so the order statistics are checked against numpy's selection (the routine the oracle's
+    sort is pinned to) on the same fp32 values: the threshold uncentred and centred on the median."""
+    n, K = 16384, 14336
+    rng = np.random.default_rng(953)
+    X = np.empty((n, K), dtype=np.uint16)
+    for r0 in range(0, n, 2048):   # SiLU(g) * u drawn in slabs to bound host memory
+        g = rng.standard_normal((2048, K), dtype=np.float32)
+        u = rng.standard_normal((2048, K), dtype=np.float32)
+        X[r0:r0 + 2048] = wl.encode(g / (1 + np.exp(-g)) * u + np.float32(0.05), BF16)
+    Xd = to_dev(X, BF16)
+    ws = scap.Workspace(K, 0, n)
+    v = wl.decode(X, BF16).astype(np.float32).ravel()
+    del X
+    M = v.size
+    say("calibrate 16384 x 14336 median s=0.7")
+    m, tau = scap.calibrate(Xd, 0.7, scap.MODE_MEDIAN, workspace=ws)
+    mid = np.partition(v, [M // 2 - 1, M // 2])[[M // 2 - 1, M // 2]]
+    assert m == float(np.float32((np.float64(mid[0]) + np.float64(mid[1])) / 2))
+    k = int(np.ceil(np.float64(np.float32(0.7)) * M))
+    imp = np.abs(v - np.float32(m))     # one fp32 subtraction, as the pruner forms it
+    assert tau == float(np.partition(imp, k - 1)[k - 1])
+    say("calibrate 16384 x 14336 zero s=0.5")
+    _, tau0 = scap.calibrate(Xd, 0.5, scap.MODE_ZERO, workspace=ws)
+    k = int(np.ceil(np.float64(np.float32(0.5)) * M))
+    np.abs(v, out=imp)
+    assert tau0 == float(np.partition(imp, k - 1)[k - 1])
+
+
+def test_calibrate_histogram_mode_on_hand_built_samples():
+    """The histogram estimator against values worked out by hand from its definition (the samples and their
+    derivations are in test_oracle_hist_pins.py): peaks that separate the definition from its near misses, a
+    value equal to the upper end of the range, a window cut at the lower edge with a three-way tie."""
+    import test_oracle_hist_pins as hp
+    from fractions import Fraction
+    cases = [(hp._case1(), 100.5 / 64),
+             (hp._grid_sample({}, Fraction(0), hi_copies=60), 2045.5 / 64),
+             (hp._grid_sample({}, Fraction(0), hi_copies=6, lo_copies=40, empty=range(1, 7)), 0.5 / 64)]
+    for X, want in cases:
+        ws = scap.Workspace(X.shape[1], 0, 1)
+        say(f"calibrate hist hand-built M={X.size} want={want}")
+        m, tau = scap.calibrate(to_dev(X, F16), 0.5, scap.MODE_HIST, workspace=ws)
+        assert m == want
+        assert (m, tau) == oracle.calibrate(X, F16, 0.5, oracle.MODE_HIST)
+    Xc = np.full((3, 50), 2.5, dtype=np.float16).view(np.uint16)
+    assert scap.calibrate(to_dev(Xc, F16), 0.3, scap.MODE_HIST, workspace=scap.Workspace(50, 0, 3)) == (2.5, 0.0)
 
 
 @pytest.mark.parametrize("dt", [F16, BF16])
