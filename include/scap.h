@@ -160,6 +160,26 @@ int scap_sparse_fc(const void* W, const void* col_scale, int64_t K, int64_t N, i
                    int32_t* nnz_out, int32_t* union_nnz_out, void* workspace, size_t workspace_bytes,
                    void* stream);
 
+/*
+ * ASYNC.  scap_sparse_fc for callers that cannot allocate device memory or pass a workspace: code recorded into a
+ * HIP graph, tight serving loops, harnesses that forbid allocation.  Arguments and results as scap_sparse_fc
+ * (same kernels, bit-identical outputs); the scratch is an array of SCAP_STATIC_SCRATCH_BYTES bytes inside the
+ * library's code object, one copy per GPU, held until the process ends.  The call allocates and frees nothing.
+ *   - Refused with SCAP_ERR_WORKSPACE when scap_workspace_bytes(K, N, B) exceeds SCAP_STATIC_SCRATCH_BYTES
+ *     (one token: any layer up to about 300 000 output columns; four tokens: up to 65536 columns and about
+ *     50 000 input channels; 16 tokens never fit).  Nothing is launched then.
+ *   - The device that is current when the call is made must be the stream's device.  The first call on a
+ *     device (and the first after a call that failed with SCAP_ERR_HIP) looks up the array's address and clears
+ *     its header with a fill kernel on `stream`.
+ *   - All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in time on one GPU
+ *     race and give wrong results.  Serialise them (one stream, or events), or use scap_sparse_fc with one
+ *     workspace per stream.
+ */
+#define SCAP_STATIC_SCRATCH_BYTES (24 * 1024 * 1024)
+int scap_sparse_fc_static(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x,
+                          int xdt, int64_t B, float m, float tau, const float* b_fused, float* y,
+                          int32_t* idx_out, int32_t* nnz_out, int32_t* union_nnz_out, void* stream);
+
 /* Same as scap_sparse_fc with an explicit launch shape (cfg may be NULL). */
 int scap_sparse_fc_ex(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x,
                       int xdt, int64_t B, float m, float tau, const float* b_fused, float* y, int32_t* idx_out,

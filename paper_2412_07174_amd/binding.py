@@ -18,7 +18,7 @@ _TORCH_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8}
 
 EXPORTS = (
     "scap_status_string", "scap_version", "scap_workspace_bytes", "scap_workspace_init", "scap_calibrate",
-    "scap_fold_bias", "scap_sparse_fc", "scap_sparse_fc_ex", "scap_dense_fc", "scap_read_probe",
+    "scap_fold_bias", "scap_sparse_fc", "scap_sparse_fc_ex", "scap_sparse_fc_static", "scap_dense_fc", "scap_read_probe",
     "scap_pack_gate_up", "scap_swiglu_workspace_bytes", "scap_swiglu_block",
 )
 
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.scap_sparse_fc.argtypes = fc
     lib.scap_sparse_fc_ex.restype = i32
     lib.scap_sparse_fc_ex.argtypes = fc + [ctypes.POINTER(LaunchCfg)]
+    lib.scap_sparse_fc_static.restype = i32
+    lib.scap_sparse_fc_static.argtypes = fc[:-3] + [vp]
     lib.scap_dense_fc.restype = i32
     lib.scap_dense_fc.argtypes = [vp, vp, i64, i64, i32, vp, i32, i64, vp, vp, vp, sz, vp, ctypes.POINTER(LaunchCfg)]
     lib.scap_pack_gate_up.restype = i32
@@ -270,6 +272,36 @@ def sparse_fc(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_fused: O
     else:
         rc = lib.scap_sparse_fc_ex(*args, _cfg(cfg))
     _check(rc, "scap_sparse_fc")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 24 * 1024 * 1024
+
+
+def sparse_fc_static(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_fused: Optional[torch.Tensor] = None, *,
+                     col_scale=None, y: torch.Tensor, idx_out=None, nnz_out=None, union_nnz_out=None,
+                     stream=None) -> torch.Tensor:
+    """sparse_fc without a workspace and without any allocation (the output tensor is required): the scratch is a
+    fixed array inside the library, one per GPU, shared by every call on that GPU."""
+    lib = load_library()
+    a = _Args()
+    a.weights(W, col_scale)
+    K, N = W.shape
+    B = a.tokens(x, K)
+    a.want(b_fused, "b_fused", shape=(N,), dtype=torch.float32, optional=True)
+    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32)
+    a.want(idx_out, "idx_out", shape=[(B, K)] + ([(K,)] if B == 1 else []), dtype=torch.int32, optional=True)
+    for t, what in ((nnz_out, "nnz_out"), (union_nnz_out, "union_nnz_out")):
+        a.want(t, what, dtype=torch.int32, optional=True)
+    if nnz_out is not None and nnz_out.numel() < B:
+        raise ValueError(f"nnz_out: {nnz_out.numel()} entries for {B} tokens")
+    if union_nnz_out is not None and union_nnz_out.numel() < 1:
+        raise ValueError("union_nnz_out: needs one entry")
+    a.on_one_gpu()
+    rc = lib.scap_sparse_fc_static(_ptr(W), _ptr(col_scale), K, N, _code(W, "W"), _ptr(x), _code(x, "x"), B, float(m),
+                                   float(tau), _ptr(b_fused), _ptr(y), _ptr(idx_out), _ptr(nnz_out),
+                                   _ptr(union_nnz_out), _stream(stream))
+    _check(rc, "scap_sparse_fc_static")
     return y
 
 

@@ -1,6 +1,8 @@
 // extern "C" entry points of libscap: argument validation and dispatch.  See include/scap.h.
 #include <math.h>
 
+#include <mutex>
+
 #include "scap_internal.hpp"
 
 using namespace scap;
@@ -50,10 +52,11 @@ void fill_workspace_ptrs(GemvArgs& a, void* ws, int64_t K, int64_t N, int64_t B)
     }
 }
 
-int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
-              int64_t B, float m, float tau, const float* bias, float* y, int32_t* idx_out, int32_t* nnz_out,
-              int32_t* union_nnz_out, void* workspace, size_t workspace_bytes, void* stream, const scap_launch_cfg* cfg) {
-    int rc = check_layer(W, col_scale, K, N, wdt);
+// argument checks of an FC call, workspace apart
+int check_fc_args(int mode, const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                  int64_t B, float m, float tau, const float* bias, const float* y, const int32_t* idx_out,
+                  const int32_t* nnz_out) {
+    const int rc = check_layer(W, col_scale, K, N, wdt);
     if (rc != SCAP_OK) return rc;
     if (!y) return SCAP_ERR_NULL;
     if (mode != kModeFold) {
@@ -69,6 +72,14 @@ int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t
     } else if (mode == kModeFold) {
         if (!isfinite(m)) return SCAP_ERR_VALUE;
     }
+    return SCAP_OK;
+}
+
+int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+              int64_t B, float m, float tau, const float* bias, float* y, int32_t* idx_out, int32_t* nnz_out,
+              int32_t* union_nnz_out, void* workspace, size_t workspace_bytes, void* stream, const scap_launch_cfg* cfg) {
+    int rc = check_fc_args(mode, W, col_scale, K, N, wdt, x, xdt, B, m, tau, bias, y, idx_out, nnz_out);
+    if (rc != SCAP_OK) return rc;
     rc = check_workspace(workspace, workspace_bytes, K, N, B);
     if (rc != SCAP_OK) return rc;
 
@@ -90,6 +101,48 @@ int fc_common(int mode, const void* W, const void* col_scale, int64_t K, int64_t
     a.tau = tau;
     fill_workspace_ptrs(a, workspace, K, N, B);
     return launch_gemv(a, wdt, cfg, static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Scratch of scap_sparse_fc_static: the workspace of a call, held in the code object instead of a caller's
+// allocation.  Each GPU that loads the library has its own copy at its own address; host code never uses the
+// array's name as an address, only what hipGetSymbolAddress returned for the current device.
+static __device__ __align__(256) unsigned char scratch[SCAP_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+    void* ptr = nullptr;   // device address of `scratch` on this GPU
+    bool clean = false;    // header (arrival counters, segment counts) known to be zero
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// Address of the current device's scratch, its header cleared if it may be dirty.  SCAP_ERR_HIP on failure.
+int static_scratch(hipStream_t stream, void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SCAP_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticScratch& st = g_static[dev];
+    if (st.ptr == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SCAP_ERR_HIP;
+        st.ptr = p;
+    }
+    if (!st.clean) {
+        // a fill kernel, not hipMemsetAsync: the call may be recorded into a HIP graph
+        const int rc = launch_workspace_init(st.ptr, SCAP_STATIC_SCRATCH_BYTES, stream);
+        if (rc != SCAP_OK) return rc;
+        st.clean = true;
+    }
+    *out = st.ptr;
+    return SCAP_OK;
+}
+
+void static_scratch_failed() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    g_static[dev].clean = false;
 }
 
 constexpr int64_t kMaxGated = 262144;  // channels of the gated product: 4096 segments of 64
@@ -168,6 +221,24 @@ int scap_sparse_fc(const void* W, const void* col_scale, int64_t K, int64_t N, i
                    int32_t* union_nnz_out, void* workspace, size_t workspace_bytes, void* stream) {
     return fc_common(kModeSparse, W, col_scale, K, N, wdt, x, xdt, B, m, tau, b_fused, y, idx_out, nnz_out,
                      union_nnz_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int scap_sparse_fc_static(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
+                          int64_t B, float m, float tau, const float* b_fused, float* y, int32_t* idx_out,
+                          int32_t* nnz_out, int32_t* union_nnz_out, void* stream) {
+    int rc = check_fc_args(kModeSparse, W, col_scale, K, N, wdt, x, xdt, B, m, tau, b_fused, y, idx_out, nnz_out);
+    if (rc != SCAP_OK) return rc;
+    // a layer and batch whose workspace would not fit the static scratch is refused before anything is touched
+    const size_t need = scap_workspace_bytes(K, N, B);
+    if (need == 0) return SCAP_ERR_SHAPE;
+    if (need > (size_t)SCAP_STATIC_SCRATCH_BYTES) return SCAP_ERR_WORKSPACE;
+    void* ws = nullptr;
+    rc = static_scratch(static_cast<hipStream_t>(stream), &ws);
+    if (rc != SCAP_OK) return rc;
+    rc = fc_common(kModeSparse, W, col_scale, K, N, wdt, x, xdt, B, m, tau, b_fused, y, idx_out, nnz_out,
+                   union_nnz_out, ws, SCAP_STATIC_SCRATCH_BYTES, stream, nullptr);
+    if (rc == SCAP_ERR_HIP) static_scratch_failed();
+    return rc;
 }
 
 int scap_dense_fc(const void* W, const void* col_scale, int64_t K, int64_t N, int wdt, const void* x, int xdt,
