@@ -70,7 +70,8 @@ typedef enum {
 
 /* Optional launch shape of the kernels (for tuning sweeps and tests).  Zero fields mean "choose".
  * lanes_per_row selects the kernel: 64 or 32 = the vector kernel (column tile = lanes_per_row x 8 columns,
- * x 16 for int8; more than 4 tokens: 64 only); 16 = the single-launch matrix-core kernel and 1 = the two-launch
+ * x 16 for int8; more than 4 tokens: 64 only; one token with 8 wavefronts and 64 lanes per row, the default, runs
+ * the one-token kernel unless flags says otherwise or a workgroup would own more than 2048 channels); 16 = the single-launch matrix-core kernel and 1 = the two-launch
  * matrix-core form with its lists in the workspace (both: 2..16 tokens over bf16 or int8 weights; the
  * single-launch kernel also 5..16 tokens over fp16 weights; there waves_per_group must be 0 or 8 -- the
  * two-launch form also takes 16 with bf16 -- and rows_per_group is a multiple of 64, rounded up to whole
@@ -82,7 +83,14 @@ typedef struct {
     int32_t rows_per_group;  /* input channels owned by one workgroup; multiple of 64 */
     int32_t unroll;          /* weight rows in flight per wavefront: 4, 8 or 16 */
     int32_t lanes_per_row;   /* 64, 32, 16 or 1: see above */
+    int32_t flags;           /* bit 0 (SCAP_CFG_DEVICE_SCOPE_LOADS): the one-token kernel fetches split-K partial sums
+                                with device-coherent loads even when all their writers ran on the reader's own
+                                accelerator die (results are identical; for tests and measurements);
+                                bit 1 (SCAP_CFG_GENERAL_KERNEL): one token through the general vector kernel
+                                instead of the one-token kernel */
 } scap_launch_cfg;
+#define SCAP_CFG_DEVICE_SCOPE_LOADS 1
+#define SCAP_CFG_GENERAL_KERNEL 2
 
 /* Static, NUL-terminated description of a status code.  Never freed. */
 const char* scap_status_string(int status);

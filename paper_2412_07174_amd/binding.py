@@ -13,6 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libscap.so")
 F16, BF16, I8 = 0, 1, 2
 MODE_ZERO, MODE_MEAN, MODE_MEDIAN, MODE_HIST = 0, 1, 2, 3
 MAX_TOKENS = 16
+CFG_DEVICE_SCOPE_LOADS, CFG_GENERAL_KERNEL = 1, 2
 
 _TORCH_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8}
 
@@ -31,7 +32,7 @@ class ScapError(RuntimeError):
 
 class LaunchCfg(ctypes.Structure):
     _fields_ = [("waves_per_group", ctypes.c_int32), ("rows_per_group", ctypes.c_int32),
-                ("unroll", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32)]
+                ("unroll", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 _lib = None
@@ -188,7 +189,8 @@ def _cfg(cfg):
     if isinstance(cfg, LaunchCfg):
         return ctypes.byref(cfg)
     waves, rows, unroll, *rest = cfg
-    return ctypes.byref(LaunchCfg(int(waves), int(rows), int(unroll), int(rest[0]) if rest else 0))
+    return ctypes.byref(LaunchCfg(int(waves), int(rows), int(unroll), int(rest[0]) if rest else 0,
+                                  int(rest[1]) if len(rest) > 1 else 0))
 
 
 class Workspace:

@@ -1,0 +1,438 @@
+// One-token column-gathered GEMV (SCAP Alg. 3; Eq. 2, 3, 6) for gfx950: the decode-time hot path in one launch,
+// built around what a launch costs when no weight is streaming.
+//
+// The K input channels are cut into S ranges of Kc channels and the N columns into T tiles of one 16-byte vector
+// per lane (512 columns of 16-bit weights, 1024 of int8).  Workgroup (split, tile), 8 wavefronts:
+//   1. EVERY wavefront tests all Kc inputs of the workgroup itself: one 16-byte load per lane covers 512
+//      channels, eight subtract-compare-ballot steps give the keep masks (Alg. 3 steps 1-2, strict compare of
+//      Eq. 2).  A kept channel's position in the workgroup's list follows from the ballots; wavefront w takes
+//      the positions p with p % 8 == w.  No count is exchanged, so there is no barrier before the first weight
+//      load, and the kept rows are spread evenly over the wavefronts whatever the mask looks like.
+//   2. a wavefront streams its rows with UNROLL 16-byte loads per lane in flight, re-issuing a load as soon as
+//      its predecessor in the ring has been consumed (Eq. 3: only kept rows are ever addressed).
+//   3. one barrier; wavefront w then adds the eight wavefronts' sums of ITS slice of the tile (1/8 of the
+//      columns), stores the slice's split-K partial and takes the slice's arrival ticket.  The last arrival of a
+//      (tile, slice) adds the S partials in split order -- a fixed order, so y is bit-reproducible -- applies
+//      the int8 scale and the fused bias (Eq. 6) and writes y.  Eight tickets per tile instead of one: the
+//      final sums of a tile are collected by up to eight compute units in parallel, each pulling S x 256 bytes,
+//      and no wavefront waits for another after the barrier.
+//
+// Hand-over of the partials between workgroups.  The stores are device-coherent write-through stores and the
+// ticket is a device-scope atomic, so a reader anywhere on the device may fetch them with device-coherent
+// loads once it holds the last ticket.  Those loads go to the device's coherence point, past the L2 of the
+// reader's accelerator die (XCD).  When every contributor of a (tile, slice) ran on the reader's own XCD -- the
+// usual placement, workgroups being dealt round-robin to the 8 XCDs and a tile's workgroups being 8 apart --
+// their stores all went through the L2 the reader uses, which therefore holds the current data or nothing;
+// the reader then invalidates its compute unit's vector L1 and uses ordinary loads.  Whether that holds is
+// decided at run time from the hardware's XCC id: each arrival adds (1, id, id^2) to the ticket word, and the
+// last arrival takes the short way only if count * sum(id^2) == sum(id)^2, i.e. all ids are equal.  Where the
+// dispatcher puts a workgroup thus decides speed only, never correctness.
+#pragma once
+
+#include "scap_gemv_body.hpp"
+
+namespace scap {
+
+constexpr int kG1Waves = 8;
+constexpr int kG1Threads = kG1Waves * kWave;
+constexpr int kG1Chunk = 8 * kWave;  // channels a wavefront tests per 16-byte load per lane
+constexpr int kG1MaxChunks = 4;      // Kc <= 2048
+constexpr int kG1HdrBytes = 2048;    // offsets and counts of up to 256 splits (closing the caller's lists)
+constexpr int kG1TicketWords = 32;   // int32 words between the tickets of a tile's slices (128 bytes)
+
+constexpr int kG1FlagDeviceScope = 1;  // always fetch the partials with device-coherent loads
+
+struct Gemv1Args {
+    const void* W;
+    const uint16_t* x;
+    const uint16_t* col_scale;
+    const float* bias;
+    float* y;
+    float* partial;      // [S][T][TILE] fp32
+    int32_t* counters;   // ticket of (tile, slice) at word tile*kCounterStride + slice*kG1TicketWords (64-bit)
+    int32_t* idx_out;
+    int32_t* nnz_out;
+    int32_t* union_nnz_out;
+    int32_t* seg_cnt;    // [S] kept channels per split (only when the caller wants lists)
+    int K, N, Kc, S, T, mode, xdt, flags;
+    float m, tau;
+};
+
+// id of the accelerator die (XCD) this wavefront runs on: hardware register XCC_ID (20), bits 3:0
+__device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg(((4 - 1) << 11) | (0 << 6) | 20) & 0xFu; }
+
+// what an arrival adds to the 64-bit ticket: count in bits 0-15, sum of ids in 16-31, sum of squares in 32-63
+__device__ __forceinline__ unsigned long long ticket_increment(uint32_t id) {
+    return 1ull | ((unsigned long long)id << 16) | ((unsigned long long)(id * id) << 32);
+}
+__device__ __forceinline__ bool ticket_all_one_xcd(unsigned long long t) {
+    const unsigned long long n = t & 0xFFFFull, sum = (t >> 16) & 0xFFFFull, sq = t >> 32;
+    return n * sq == sum * sum;  // zero variance of the ids
+}
+
+template <int CPL> struct SliceVec;
+template <> struct SliceVec<1> {
+    float v[1];
+    __device__ __forceinline__ static SliceVec load_coherent(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        SliceVec s;
+        s.v[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, kAuxDeviceCoherent));
+        return s;
+    }
+    __device__ __forceinline__ static SliceVec load_plain(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        SliceVec s;
+        s.v[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+        return s;
+    }
+    __device__ __forceinline__ void store_coherent(__amdgpu_buffer_rsrc_t r, uint32_t off) const {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[0]), r, (int)off, 0, kAuxDeviceCoherent);
+    }
+};
+template <> struct SliceVec<2> {
+    float v[2];
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    __device__ __forceinline__ static SliceVec load_coherent(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, kAuxDeviceCoherent);
+        SliceVec s;
+        s.v[0] = __uint_as_float(t[0]);
+        s.v[1] = __uint_as_float(t[1]);
+        return s;
+    }
+    __device__ __forceinline__ static SliceVec load_plain(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+        SliceVec s;
+        s.v[0] = __uint_as_float(t[0]);
+        s.v[1] = __uint_as_float(t[1]);
+        return s;
+    }
+    __device__ __forceinline__ void store_coherent(__amdgpu_buffer_rsrc_t r, uint32_t off) const {
+        const u32x2_t t = {__float_as_uint(v[0]), __float_as_uint(v[1])};
+        __builtin_amdgcn_raw_buffer_store_b64(t, r, (int)off, 0, kAuxDeviceCoherent);
+    }
+};
+
+// exclusive prefix sum across the 64 lanes of a wave
+__device__ __forceinline__ int wave_exclusive_scan(int v) { return wave_inclusive_scan(v) - v; }
+
+// Last arrival of (tile 0, slice 0): every split's ascending list sits at idx_out[split*Kc ...] with its count in
+// seg_cnt; write the total and close the gaps.  One wavefront; entries only move left, and a block of source
+// positions is read completely before any of it is written, so nothing is overwritten before it has been read.
+__device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off, int* s_cnt) {
+    const int lane = lane_id();
+    int run = 0;
+    for (int s0 = 0; s0 < a.S; s0 += kWave) {
+        const int sp = s0 + lane;
+        const int v = sp < a.S ? load_dev(&a.seg_cnt[sp]) : 0;
+        const int inc = wave_inclusive_scan(v);
+        if (sp < a.S) {
+            s_off[sp] = run + inc - v;
+            s_cnt[sp] = v;
+        }
+        run += __shfl(inc, kWave - 1, kWave);
+    }
+    if (lane == 0) {
+        if (a.nnz_out) a.nnz_out[0] = run;
+        if (a.union_nnz_out) a.union_nnz_out[0] = run;
+    }
+    if (a.idx_out == nullptr || a.S == 1) return;
+    __builtin_amdgcn_wave_barrier();
+    constexpr int PER = 16;
+    for (int c0 = 0; c0 < a.K; c0 += kWave * PER) {
+        int vals[PER], dsts[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int p = c0 + j * kWave + lane;
+            dsts[j] = -1;
+            vals[j] = 0;
+            if (p < a.K) {
+                const int seg = p / a.Kc;
+                const int r = p - seg * a.Kc;
+                if (r < s_cnt[seg]) {
+                    vals[j] = load_dev(&a.idx_out[p]);
+                    dsts[j] = s_off[seg] + r;
+                }
+            }
+        }
+        wait_memory_ops();
+#pragma unroll
+        for (int j = 0; j < PER; ++j)
+            if (dsts[j] >= 0) a.idx_out[dsts[j]] = vals[j];
+        wait_memory_ops();
+    }
+}
+
+template <int WDT, int UNROLL, int NCH>
+__global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const Gemv1Args a) {
+    constexpr int ELEMS = Vec<WDT>::kElems;
+    constexpr int TILE = kWave * ELEMS;
+    constexpr int CPL = ELEMS / 8;      // columns per lane of a wavefront's slice
+    constexpr int SLICE = kWave * CPL;  // columns per slice: 1/8 of the tile
+    typedef SliceVec<CPL> slice_t;
+
+    extern __shared__ uint4 smem_raw[];
+    char* smem = reinterpret_cast<char*>(smem_raw);
+    int* s_off = reinterpret_cast<int*>(smem);
+    int* s_cnt = s_off + kMaxSplits;
+    float* s_red = reinterpret_cast<float*>(smem + kG1HdrBytes);                           // [8][TILE]
+    int2* s_list = reinterpret_cast<int2*>(smem + kG1HdrBytes + kG1Waves * TILE * 4);      // [8][slots]
+    const int slots = a.Kc / kG1Waves + 1;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = uniform(tid >> 6);
+    const int tile = blockIdx.x % a.T;
+    const int split = blockIdx.x / a.T;
+    const int k0 = split * a.Kc;
+    const int kend = min(k0 + a.Kc, a.K);
+
+    // ------------------------------------------------------------------ 1. inputs: every wavefront, all Kc
+    uint4 xv[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        xv[c] = make_uint4(0u, 0u, 0u, 0u);
+        const int kb = k0 + c * kG1Chunk + 8 * lane;
+        if (a.mode != kModeFold && kb < kend) {
+            if (kb + 8 <= a.K) {
+                xv[c] = *reinterpret_cast<const uint4*>(a.x + kb);
+            } else {  // the last octet of an input whose length is not a multiple of 8: element by element
+                uint32_t h[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) h[j] = kb + j < a.K ? (uint32_t)a.x[kb + j] : 0u;
+                xv[c] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            }
+        }
+    }
+    // constants of the columns this lane finishes, needed only at the very end: loaded now, behind the inputs
+    const int fcol = tile * TILE + w * SLICE + lane * CPL;
+    float cbias[CPL], cscale[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        cbias[c] = 0.f;
+        cscale[c] = 1.f;
+        if (fcol + c < a.N) {
+            if (a.bias) cbias[c] = a.bias[fcol + c];
+            if (WDT == kI8) cscale[c] = f16_bits_to_f32(a.col_scale[fcol + c]);
+        }
+    }
+
+    const bool want_lists = tile == 0 && w == 0 && (a.nnz_out != nullptr || a.union_nnz_out != nullptr);
+    int2* mylist = s_list + w * slots;
+    int cnt = 0;    // kept channels so far, in (chunk, element, lane) order -- wave-uniform
+    int lcnt = 0;   // the same in ascending channel order (caller's list)
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        if (k0 + c * kG1Chunk < kend) {  // wave-uniform
+            const int kb = k0 + c * kG1Chunk + 8 * lane;
+            const int nvalid = kend - kb;  // elements j < nvalid of this lane exist
+            const uint32_t wd[4] = {xv[c].x, xv[c].y, xv[c].z, xv[c].w};
+            float xf[8];
+            if (a.xdt == kBF16) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) xf[j] = __uint_as_float((j & 1) ? (wd[j >> 1] & 0xFFFF0000u) : (wd[j >> 1] << 16));
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) xf[j] = f16_bits_to_f32((j & 1) ? (wd[j >> 1] >> 16) : (wd[j >> 1] & 0xFFFFu));
+            }
+            uint64_t bal[8];
+            // position of a kept channel in the workgroup's list, and the entries this wavefront owns
+            auto place = [&](int j, float dv) {
+                const int pos = cnt + lanes_below(bal[j]);
+                if (((bal[j] >> lane) & 1) && (pos & (kG1Waves - 1)) == w) mylist[pos >> 3] = make_int2(kb + j, __float_as_int(dv));
+                cnt += __popcll(bal[j]);
+            };
+            if (a.mode == kModeSparse) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float dv = xf[j] - a.m;                          // one fp32 subtraction
+                    bal[j] = __ballot(fabsf(dv) > a.tau && j < nvalid);    // strict; NaN is pruned
+                    place(j, dv);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    bal[j] = __ballot(j < nvalid);  // dense (Eq. 1) and bias folding (Eq. 6): every channel
+                    place(j, a.mode == kModeFold ? a.m : xf[j]);
+                }
+            }
+            if (want_lists) {
+                uint32_t kbits = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) kbits |= (uint32_t)((bal[j] >> lane) & 1) << j;
+                const int mine = __popc(kbits);
+                const int inc = wave_inclusive_scan(mine);
+                if (a.idx_out) {
+                    int p = k0 + lcnt + inc - mine;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if ((kbits >> j) & 1u) store_dev(&a.idx_out[p++], kb + j);
+                }
+                lcnt += __shfl(inc, kWave - 1, kWave);
+            }
+        }
+    }
+    cnt = uniform(cnt);
+    if (want_lists && lane == 0) {
+        if (a.S == 1) {
+            if (a.nnz_out) a.nnz_out[0] = cnt;
+            if (a.union_nnz_out) a.union_nnz_out[0] = cnt;
+        } else {
+            store_dev(&a.seg_cnt[split], cnt);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();  // the list is this wavefront's own: written above, read below, in order
+
+    // ------------------------------------------------------------------ 2. stream the kept rows
+    float acc[ELEMS];
+#pragma unroll
+    for (int j = 0; j < ELEMS; ++j) acc[j] = 0.f;
+    const int col0 = tile * TILE + lane * ELEMS;
+    const uint32_t lane_off = col0 < a.N ? (uint32_t)col0 * Vec<WDT>::kBytes : 0u;  // lanes past N re-read column 0
+    const uint32_t row_bytes = (uint32_t)a.N * Vec<WDT>::kBytes;
+    const char* wbase = reinterpret_cast<const char*>(a.W);
+    const int n_w = cnt > w ? (cnt - w + kG1Waves - 1) / kG1Waves : 0;  // positions w, w+8, ...
+
+    for (int i0 = 0; i0 < n_w; i0 += kWave) {
+        const int e = i0 + lane;
+        const int2 ent = e < n_w ? mylist[e] : make_int2(0, 0);
+        const int vidx = ent.x;
+        const float vd = __int_as_float(ent.y);
+        const int nb = min((int)kWave, n_w - i0);
+        auto row_load = [&](int i) {
+            return load_row_vec(wbase, (uint32_t)__builtin_amdgcn_readlane(vidx, i), row_bytes, lane_off);
+        };
+        uint4 r[UNROLL];
+        if (nb < UNROLL) {
+#pragma unroll
+            for (int q = 0; q < UNROLL - 1; ++q)
+                if (q < nb) r[q] = row_load(q);
+#pragma unroll
+            for (int q = 0; q < UNROLL - 1; ++q)
+                if (q < nb) fma_vec<WDT>(acc, r[q], read_lane_f(vd, q));
+        } else {
+#pragma unroll
+            for (int q = 0; q < UNROLL; ++q) r[q] = row_load(q);
+            int u = 0;
+            for (; u + 2 * UNROLL <= nb; u += UNROLL) {
+#pragma unroll
+                for (int q = 0; q < UNROLL; ++q) {
+                    fma_vec<WDT>(acc, r[q], read_lane_f(vd, u + q));
+                    r[q] = row_load(u + UNROLL + q);
+                    __builtin_amdgcn_sched_barrier(0);  // keep each load where it is: right behind the row it replaces
+                }
+            }
+            // rows u .. u+UNROLL-1 are in flight; fewer than UNROLL further rows are left to issue
+            const int rest = nb - u - UNROLL;
+#pragma unroll
+            for (int q = 0; q < UNROLL; ++q) {
+                fma_vec<WDT>(acc, r[q], read_lane_f(vd, u + q));
+                if (q < rest) r[q] = row_load(u + UNROLL + q);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int q = 0; q < UNROLL - 1; ++q)
+                if (q < rest) fma_vec<WDT>(acc, r[q], read_lane_f(vd, u + UNROLL + q));
+        }
+    }
+
+    // ------------------------------------------------------------------ 3. add the wavefronts' sums, slice by slice
+    {
+        float4* dst = reinterpret_cast<float4*>(s_red + w * TILE + lane * ELEMS);
+#pragma unroll
+        for (int j = 0; j < ELEMS / 4; ++j) dst[j] = make_float4(acc[4 * j], acc[4 * j + 1], acc[4 * j + 2], acc[4 * j + 3]);
+    }
+    __syncthreads();
+    slice_t sum;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) sum.v[c] = 0.f;
+#pragma unroll
+    for (int i = 0; i < kG1Waves; ++i) {
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) sum.v[c] += s_red[i * TILE + w * SLICE + lane * CPL + c];
+    }
+
+    auto finish = [&](const slice_t& s) {
+#pragma unroll
+        for (int c = 0; c < CPL; ++c)
+            if (fcol + c < a.N) a.y[fcol + c] = (WDT == kI8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
+    };
+    if (a.S == 1) {
+        finish(sum);
+        return;
+    }
+
+    // ------------------------------------------------------------------ 4. split-K hand-over per (tile, slice)
+    const __amdgpu_buffer_rsrc_t pbuf = make_raw_buffer(a.partial, (uint32_t)a.S * a.T * TILE * 4u);
+    const uint32_t pstride = (uint32_t)a.T * TILE * 4u;  // bytes between consecutive splits
+    const uint32_t pmine = (uint32_t)((tile * TILE + w * SLICE + lane * CPL) * 4);
+    sum.store_coherent(pbuf, split * pstride + pmine);
+    wait_memory_ops();  // the wavefront's stores have been acknowledged
+    unsigned long long* ticket =
+        reinterpret_cast<unsigned long long*>(a.counters + tile * kCounterStride + w * kG1TicketWords);
+    unsigned long long seen = 0;
+    if (lane == 0)
+        seen = __hip_atomic_fetch_add(ticket, ticket_increment(xcc_id()), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
+               ticket_increment(xcc_id());
+    const uint32_t seen_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)seen);
+    const uint32_t seen_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(seen >> 32));
+    seen = ((unsigned long long)seen_hi << 32) | seen_lo;
+    if ((int)(seen & 0xFFFFull) != a.S) return;  // not the last arrival of this slice
+
+    const bool near = ticket_all_one_xcd(seen) && !(a.flags & kG1FlagDeviceScope);
+    if (near) asm volatile("buffer_inv sc0" ::: "memory");  // this compute unit's vector L1 holds nothing older
+    slice_t total;
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) total.v[c] = 0.f;
+    constexpr int FLY = 32;  // partial loads in flight
+    for (int sp0 = 0; sp0 < a.S; sp0 += FLY) {
+        slice_t v[FLY];
+        if (near) {
+#pragma unroll
+            for (int j = 0; j < FLY; ++j) v[j] = slice_t::load_plain(pbuf, min(sp0 + j, a.S - 1) * pstride + pmine);
+        } else {
+#pragma unroll
+            for (int j = 0; j < FLY; ++j) v[j] = slice_t::load_coherent(pbuf, min(sp0 + j, a.S - 1) * pstride + pmine);
+        }
+#pragma unroll
+        for (int j = 0; j < FLY; ++j) {
+            const bool in = sp0 + j < a.S;  // a slot past the last split re-read it: not added
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) total.v[c] += in ? v[j].v[c] : 0.f;
+        }
+    }
+    finish(total);
+    if (lane == 0) store_dev(ticket, 0ull);  // ready for the next call
+    if (want_lists) close_lists_wave(a, s_off, s_cnt);
+}
+
+// ---------------------------------------------------------------------------------------------- launch
+inline size_t gemv1_lds_bytes(int tile_cols, int Kc) {
+    return (size_t)kG1HdrBytes + (size_t)kG1Waves * tile_cols * 4 + (size_t)kG1Waves * (Kc / kG1Waves + 1) * 8;
+}
+
+template <int WDT, int UNROLL>
+static int launch_gemv1_nch(const Gemv1Args& a, hipStream_t stream) {
+    constexpr int TILE = kWave * Vec<WDT>::kElems;
+    const size_t lds = gemv1_lds_bytes(TILE, a.Kc);
+    if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
+    const dim3 grid((unsigned)(a.S * a.T)), block(kG1Threads);
+    if (a.Kc <= kG1Chunk)
+        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 1>), grid, block, lds, stream, a);
+    else if (a.Kc <= 2 * kG1Chunk)
+        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 2>), grid, block, lds, stream, a);
+    else if (a.Kc <= 4 * kG1Chunk)
+        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 4>), grid, block, lds, stream, a);
+    else
+        return SCAP_ERR_CONFIG;
+    return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
+}
+
+template <int WDT>
+int launch_gemv1_wdt(const Gemv1Args& a, int unroll, hipStream_t stream) {
+    switch (unroll) {
+        case 4: return launch_gemv1_nch<WDT, 4>(a, stream);
+        case 8: return launch_gemv1_nch<WDT, 8>(a, stream);
+        case 16: return launch_gemv1_nch<WDT, 16>(a, stream);
+    }
+    return SCAP_ERR_CONFIG;
+}
+
+}  // namespace scap

@@ -1,0 +1,6 @@
+// Instantiations of the one-token GEMV kernel for f16 weights.
+#include "scap_gemv1.hpp"
+
+namespace scap {
+template int launch_gemv1_wdt<kF16>(const Gemv1Args&, int, hipStream_t);
+}  // namespace scap

@@ -85,6 +85,11 @@ struct GemvArgs {
 // Enqueue one GEMV (sparse / dense / fold mode).  Returns a scap_status.
 int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
 
+// One token (B == 1) through the one-token kernel.  Returns a scap_status, or kG1NotApplicable (positive) when a
+// workgroup would own more channels than that kernel tests per wavefront: the caller takes launch_gemv's kernel.
+constexpr int kG1NotApplicable = 1;
+int launch_gemv1(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+
 // Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
 // `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.
 constexpr int kBlockVectorTokens = 4;  // tokens per fused-block call on the vector kernel (any weight dtype)

@@ -62,6 +62,68 @@ def test_every_launch_shape(waves, unroll, lanes):
                                  what=f"{waves}/{rows}/{unroll}/{lanes}")
 
 
+# ------------------------------------------------------------------ the one-token kernel and the general kernel
+ONE_TOKEN = [
+    # K, N, dtype, rows per workgroup (0 = planner): one / two / four 512-channel chunks per wavefront, ragged
+    # last chunk, an input whose length is not a multiple of 8, column tiles that are not a multiple of the 8
+    # accelerator dies (so that a tile's workgroups sit on different dies), ragged last column tile
+    (4099, 1544, BF16, 0), (4099, 1544, BF16, 1024), (4099, 1544, BF16, 2048), (777, 4096, F16, 0),
+    (5000, 6144, BF16, 0), (2048, 11008, F16, 1024), (333, 8, BF16, 0), (6000, 2064, I8, 0), (3000, 5136, I8, 1536),
+]
+
+
+@pytest.mark.parametrize("K,N,dt,rows", ONE_TOKEN)
+def test_one_token_kernel_shapes_and_both_hand_overs(K, N, dt, rows):
+    """The one-token kernel against the oracle, and its two ways of fetching the split-K partial sums (ordinary
+    loads when all writers ran on the reader's own accelerator die, device-coherent loads otherwise or when
+    asked for) against each other and against the general vector kernel's masks: y bit-identical between the
+    two hand-overs, on repeated calls with changing inputs through one workspace."""
+    if dt == I8:
+        Wq, sc = wl.quantize_i8(K, N, 331 + K)
+        layer = Layer(Wq, I8, col_scale_bits=sc, B=1)
+        xdt = BF16
+    else:
+        layer = Layer(wl.weights(K, N, 331 + K, dt), dt, B=1)
+        xdt = dt
+    X = wl.laplace(6, K, 332 + K, xdt, loc=0.1, scale=0.5)
+    bf = np.random.default_rng(K + N).standard_normal(N).astype(np.float32)
+    for rep, tau in enumerate((0.0, 0.3, 0.35, 0.9, 2.5, 1e6)):
+        x = X[rep]
+        say(f"one-token K={K} N={N} dt={dt} rows={rows} tau={tau}")
+        for unroll in (8, 16, 4):
+            near, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, 0),
+                                           what=f"one-token K={K} N={N} rows={rows} unroll={unroll} tau={tau}")
+            far = gpu_sparse_fc(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, scap.CFG_DEVICE_SCOPE_LOADS))
+            assert np.array_equal(near["y"].view(np.uint32), far["y"].view(np.uint32)), "hand-over paths differ"
+            assert np.array_equal(near["idx"][0], far["idx"][0])
+        check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(8, 0 if rows > 1024 else rows, 8, 64, scap.CFG_GENERAL_KERNEL),
+                             what=f"general kernel K={K} N={N} tau={tau}")
+
+
+def test_one_token_kernel_many_calls_in_a_row_both_hand_overs():
+    """Back-to-back launches on one workspace with rotating weights and inputs (what the benchmark does): the
+    ordinary-load hand-over must never see a partial sum of an earlier launch.  Every y is compared bit for bit
+    with the same call made with device-coherent loads."""
+    K, N = 14336, 4096
+    Ws = [to_dev(wl.weights(K, N, 341 + i, BF16), BF16) for i in range(3)]
+    X = to_dev(wl.swiglu(16, K, 345, BF16), BF16)
+    ws = scap.Workspace(K, N, 1)
+    calls = [(i % 3, i % 16, (0.05, 0.3, 0.8, 0.0)[i % 4]) for i in range(48)]
+    ys = {}
+    for flags in (0, scap.CFG_DEVICE_SCOPE_LOADS):
+        out = torch.empty((len(calls), N), dtype=torch.float32, device="cuda")
+        say(f"48 launches in a row, flags={flags}")
+        for n, (wi, xi, tau) in enumerate(calls):
+            scap.sparse_fc(Ws[wi], X[xi], 0.0, tau, None, y=out[n:n + 1], workspace=ws, cfg=(8, 0, 8, 64, flags))
+        torch.cuda.synchronize()
+        ys[flags] = out.cpu().numpy()
+    assert np.array_equal(ys[0].view(np.uint32), ys[scap.CFG_DEVICE_SCOPE_LOADS].view(np.uint32))
+    # and one of them against the oracle
+    want = oracle.sparse_fc(wl.weights(K, N, 341 + 2, BF16), wl.swiglu(16, K, 345, BF16)[5], 0.0, 0.3, None, BF16, BF16)
+    n = calls.index((2, 5, 0.3))
+    assert_y_close(ys[0][n], want["y"][0], "launch in the middle of the series")
+
+
 @pytest.mark.parametrize("dt", [F16, I8])
 @pytest.mark.parametrize("lanes", [32])
 def test_narrow_tiles_other_dtypes(dt, lanes):
