@@ -17,6 +17,8 @@ HIPCC_FLAGS = [
     # keep the compiler from forming packed-fp32 instructions out of scalar float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
+    # leading scalar kernel arguments arrive in registers instead of being fetched by the kernel's first loads
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
 ]
 
 

@@ -14,7 +14,7 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
     if (g.B != 1) return kG1NotApplicable;
     const int elems = wdt == kI8 ? 16 : 8;
     const int tile = kWave * elems;
-    int kc = 0, unroll = 8, flags = 0;
+    int kc = 0, unroll = 4, flags = 0;
     if (cfg) {
         if (cfg->rows_per_group) kc = cfg->rows_per_group;
         if (cfg->unroll) unroll = cfg->unroll;

@@ -160,8 +160,19 @@ __device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off,
     }
 }
 
+// The arguments are passed one by one, the ones the prologue needs first: the leading 16 dwords of a kernel's
+// scalar arguments can be placed in registers by the dispatcher (kernel-argument preload), which takes the
+// argument fetch -- one memory round trip -- off the path to the first input load.
 template <int WDT, int UNROLL, int NCH>
-__global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const Gemv1Args a) {
+__global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, const void* W, int K, int N, int Kc, int S,
+                                                           int T, int mode, int xdt, int flags, float m, float tau,
+                                                           const float* bias, float* y, float* partial,
+                                                           int32_t* counters, const uint16_t* col_scale, int32_t* idx_out,
+                                                           int32_t* nnz_out, int32_t* union_nnz_out, int32_t* seg_cnt) {
+    Gemv1Args a;
+    a.W = W; a.x = x; a.col_scale = col_scale; a.bias = bias; a.y = y; a.partial = partial; a.counters = counters;
+    a.idx_out = idx_out; a.nnz_out = nnz_out; a.union_nnz_out = union_nnz_out; a.seg_cnt = seg_cnt;
+    a.K = K; a.N = N; a.Kc = Kc; a.S = S; a.T = T; a.mode = mode; a.xdt = xdt; a.flags = flags; a.m = m; a.tau = tau;
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr int TILE = kWave * ELEMS;
     constexpr int CPL = ELEMS / 8;      // columns per lane of a wavefront's slice
@@ -408,6 +419,9 @@ inline size_t gemv1_lds_bytes(int tile_cols, int Kc) {
     return (size_t)kG1HdrBytes + (size_t)kG1Waves * tile_cols * 4 + (size_t)kG1Waves * (Kc / kG1Waves + 1) * 8;
 }
 
+#define G1_ARGS                                                                                                    \
+    a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, a.mode, a.xdt, a.flags, a.m, a.tau, a.bias, a.y, a.partial, a.counters, \
+        a.col_scale, a.idx_out, a.nnz_out, a.union_nnz_out, a.seg_cnt
 template <int WDT, int UNROLL>
 static int launch_gemv1_nch(const Gemv1Args& a, hipStream_t stream) {
     constexpr int TILE = kWave * Vec<WDT>::kElems;
@@ -415,20 +429,25 @@ static int launch_gemv1_nch(const Gemv1Args& a, hipStream_t stream) {
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
     const dim3 grid((unsigned)(a.S * a.T)), block(kG1Threads);
     if (a.Kc <= kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 1>), grid, block, lds, stream, a);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 1>), grid, block, lds, stream, G1_ARGS);
     else if (a.Kc <= 2 * kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 2>), grid, block, lds, stream, a);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 2>), grid, block, lds, stream, G1_ARGS);
     else if (a.Kc <= 4 * kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 4>), grid, block, lds, stream, a);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 4>), grid, block, lds, stream, G1_ARGS);
     else
         return SCAP_ERR_CONFIG;
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
+#undef G1_ARGS
+
 template <int WDT>
 int launch_gemv1_wdt(const Gemv1Args& a, int unroll, hipStream_t stream) {
     switch (unroll) {
+        case 2: return launch_gemv1_nch<WDT, 2>(a, stream);
+        case 3: return launch_gemv1_nch<WDT, 3>(a, stream);
         case 4: return launch_gemv1_nch<WDT, 4>(a, stream);
+        case 6: return launch_gemv1_nch<WDT, 6>(a, stream);
         case 8: return launch_gemv1_nch<WDT, 8>(a, stream);
         case 16: return launch_gemv1_nch<WDT, 16>(a, stream);
     }
