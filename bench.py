@@ -29,13 +29,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known
-# size), keyed by workload; filled in from the summaries under profiles/.  None = not measured.
+# HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel of known size),
+# keyed by workload.  These are RECORDED values, copied from the profile summaries named beside them (each of
+# which gives the command that produced it); they are not measured in the run that prints them, since hardware
+# counters need the profiler.  Absent = not profiled.
 MEASURED_TRAFFIC = {
-    # profiles/gemv_kernel_bf16_mistral_down_hbm_traffic.txt
-    "mistral7b_down_14336x4096_bf16_b1_s50": 60188739,
-    # profiles/gemm_inline_raw_kernel_bf16_mistral_down_b16_s90_hbm_traffic.txt
-    "mistral7b_down_14336x4096_bf16_b16_s90": 104156846,
+    "mistral7b_down_14336x4096_bf16_b1_s50":
+        (60188739, "recorded: profiles/gemv_kernel_bf16_mistral_down_hbm_traffic.txt"),
+    "mistral7b_down_14336x4096_bf16_b16_s90":
+        (104156846, "recorded: profiles/gemm_inline_raw_kernel_bf16_mistral_down_b16_s90_hbm_traffic.txt"),
 }
 
 
@@ -45,10 +47,107 @@ def algorithmic_bytes(nnz_rows: float, K: int, N: int, B: int, wbytes: int) -> f
     return nnz_rows * N * wbytes + B * K * 2 + N * 4 + B * N * 4
 
 
+def graph_timed(torch, fn, n, repeats=1):
+    """us per call of fn(i), i = 0..n-1, captured once into a HIP graph and replayed (best of `repeats`)."""
+    for i in range(10):
+        fn(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(n):
+            fn(i)
+    g.replay()
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / n * 1e3)
+    return best
+
+
+def bench_site(torch, scap, wl, dev, rows, cfg_no, site, batches, targets, est, steps, library_gemm=False):
+    """One layer of a benchmark configuration: dense and sparse launches for every batch size and target, appended
+    to `rows` as dicts (us per launch, GB/s on the bytes actually needed).  Weights are random on the device
+    (their values do not matter for timing) and rotate over >= 1 GiB of copies; inputs come from the seeded
+    generators, thresholds from scap_calibrate."""
+    def dev16(bits, dt):
+        t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+        return t.view(torch.float16 if dt == wl.F16 else torch.bfloat16).to(dev)
+
+    K, N = site.K, site.N
+    wbytes = 1 if site.wdt == wl.I8 else 2
+    if site.wdt == wl.I8:
+        W0 = torch.randint(-127, 128, (K, N), dtype=torch.int8, device=dev)
+        scale = (torch.rand(N, device=dev) * 1e-3 + 1e-4).to(torch.float16)
+    else:
+        W0 = (torch.randn(K, N, device=dev) * 0.02).to(torch.float16 if site.wdt == wl.F16 else torch.bfloat16)
+        scale = None
+    R = max(2, -(-(1 << 30) // (K * N * wbytes)))
+    Ws = [W0] + [W0.clone() for _ in range(R - 1)]
+    X = dev16(site.draw(64, site.seed_test), site.xdt)
+    calib = dev16(site.draw(128, site.seed_calib), site.xdt)
+    ws = scap.Workspace(K, N, max(batches))
+    unz = torch.zeros(1, dtype=torch.int32, device=dev)
+    taus = {s: scap.calibrate(calib, s, est, workspace=ws) for s in targets}
+    for B in batches:
+        y = torch.empty((B, N), dtype=torch.float32, device=dev)
+
+        def xs(i):
+            o = (i * B) % (64 - B + 1)
+            return X[o] if B == 1 else X[o:o + B]
+
+        t_dense = graph_timed(torch, lambda i: scap.dense_fc(Ws[i % R], xs(i), None, col_scale=scale, y=y, workspace=ws), steps)
+        rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
+                     "target": None, "density": 1.0, "us": round(t_dense, 2),
+                     "GBps": round(algorithmic_bytes(K, K, N, B, wbytes) / t_dense / 1e3, 1)})
+        if library_gemm and site.wdt != wl.I8:
+            # the vendor library's dense GEMM on the same operands, for the crossover against a dense batch
+            yl = torch.empty((B, N), dtype=W0.dtype, device=dev)
+            t_lib = graph_timed(torch, lambda i: torch.matmul(xs(i).reshape(B, K), Ws[i % R], out=yl), steps)
+            rows[-1]["library_dense_gemm_us"] = round(t_lib, 2)
+        for s in targets:
+            m, tau = taus[s]
+            dens = 0.0
+            for i in range(8):
+                scap.sparse_fc(Ws[0], xs(i), m, tau, None, col_scale=scale, y=y, union_nnz_out=unz, workspace=ws)
+                dens += unz.item() / K / 8
+            t = graph_timed(torch, lambda i: scap.sparse_fc(Ws[i % R], xs(i), m, tau, None, col_scale=scale, y=y, workspace=ws), steps)
+            rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
+                         "target": s, "density": round(dens, 4), "us": round(t, 2),
+                         "GBps": round(algorithmic_bytes(dens * K, K, N, B, wbytes) / t / 1e3, 1),
+                         "frac_of_8TBps": round(algorithmic_bytes(dens * K, K, N, B, wbytes) / t / 1e3 / HBM_PEAK_GBS, 4),
+                         "vs_dense": round(t_dense / t, 3)})
+    del Ws, W0
+    torch.cuda.empty_cache()
+
+
+def suite_summary(torch, scap, wl, dev, steps=200):
+    """A few points of the other benchmark configurations for the default run's JSON line: the Mistral layer's FC
+    set (config 3) dense and at 50 %, 16-token batches on both feed-forward layers (config 4), and the int8 expert
+    down projection at 70 % with 1 and 8 tokens (config 5)."""
+    rows = []
+    for st in wl.sites(3):
+        bench_site(torch, scap, wl, dev, rows, 3, st, (1,), (0.5,), scap.MODE_MEDIAN, steps)
+    for st in wl.sites(4):
+        bench_site(torch, scap, wl, dev, rows, 4, st, (16,), (0.5, 0.7, 0.9), scap.MODE_ZERO, steps, library_gemm=True)
+    bench_site(torch, scap, wl, dev, rows, 5, wl.sites(5)[1], (1, 8), (0.7,), scap.MODE_MEDIAN, steps)
+    layer3 = [r for r in rows if r["cfg"] == 3]
+    out = {"mistral_layer_fc_set_dense_us": round(sum(r["us"] for r in layer3 if r["target"] is None), 2),
+           "mistral_layer_fc_set_s50_us": round(sum(r["us"] for r in layer3 if r["target"] == 0.5), 2),
+           "launches_per_point": steps, "points": []}
+    for r in rows:
+        out["points"].append({k: r[k] for k in ("cfg", "layer", "w", "B", "target", "density", "us", "GBps") if k in r}
+                             | ({"library_dense_gemm_us": r["library_dense_gemm_us"]} if "library_dense_gemm_us" in r else {}))
+    return out
+
+
 def run_suite(args, torch, scap, wl, dev):
     """Every benchmark configuration, one line per (layer, batch, target sparsity): us per launch and GB/s
-    on the bytes actually needed.  Weights are random on the device (values do not matter for timing),
-    inputs come from the seeded generators, thresholds from scap_calibrate.  Prints ONE JSON line."""
+    on the bytes actually needed.  Prints ONE JSON line."""
     steps = max(100, args.steps // 10)
     steps_box = [steps]
 
@@ -57,70 +156,12 @@ def run_suite(args, torch, scap, wl, dev):
         return t.view(torch.float16 if dt == wl.F16 else torch.bfloat16).to(dev)
 
     def timed(fn):
-        for i in range(10):
-            fn(i)
-        torch.cuda.synchronize()
-        n = steps_box[0]
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            for i in range(n):
-                fn(i)
-        g.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        g.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n * 1e3  # us
+        return graph_timed(torch, fn, steps_box[0])
 
     rows = []
 
     def run_site(cfg_no, site, batches, targets, est):
-        K, N = site.K, site.N
-        wbytes = 1 if site.wdt == wl.I8 else 2
-        if site.wdt == wl.I8:
-            W0 = torch.randint(-127, 128, (K, N), dtype=torch.int8, device=dev)
-            scale = (torch.rand(N, device=dev) * 1e-3 + 1e-4).to(torch.float16)
-        else:
-            W0 = (torch.randn(K, N, device=dev) * 0.02).to(torch.float16 if site.wdt == wl.F16 else torch.bfloat16)
-            scale = None
-        R = max(2, -(-(1 << 30) // (K * N * wbytes)))
-        Ws = [W0] + [W0.clone() for _ in range(R - 1)]
-        X = dev16(site.draw(64, site.seed_test), site.xdt)
-        calib = dev16(site.draw(128, site.seed_calib), site.xdt)
-        ws = scap.Workspace(K, N, max(batches))
-        unz = torch.zeros(1, dtype=torch.int32, device=dev)
-        taus = {s: scap.calibrate(calib, s, est, workspace=ws) for s in targets}
-        for B in batches:
-            y = torch.empty((B, N), dtype=torch.float32, device=dev)
-
-            def xs(i):
-                o = (i * B) % (64 - B + 1)
-                return X[o] if B == 1 else X[o:o + B]
-
-            t_dense = timed(lambda i: scap.dense_fc(Ws[i % R], xs(i), None, col_scale=scale, y=y, workspace=ws))
-            rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
-                         "target": None, "density": 1.0, "us": round(t_dense, 2),
-                         "GBps": round(algorithmic_bytes(K, K, N, B, wbytes) / t_dense / 1e3, 1)})
-            if site.wdt != wl.I8 and cfg_no == 4:
-                # the vendor library's dense GEMM on the same operands, for the crossover against a dense batch
-                yl = torch.empty((B, N), dtype=W0.dtype, device=dev)
-                t_lib = timed(lambda i: torch.matmul(xs(i).reshape(B, K), Ws[i % R], out=yl))
-                rows[-1]["library_dense_gemm_us"] = round(t_lib, 2)
-            for s in targets:
-                m, tau = taus[s]
-                dens = 0.0
-                for i in range(8):
-                    scap.sparse_fc(Ws[0], xs(i), m, tau, None, col_scale=scale, y=y, union_nnz_out=unz, workspace=ws)
-                    dens += unz.item() / K / 8
-                t = timed(lambda i: scap.sparse_fc(Ws[i % R], xs(i), m, tau, None, col_scale=scale, y=y, workspace=ws))
-                rows.append({"cfg": cfg_no, "layer": site.name, "K": K, "N": N, "w": wl.DTYPE_NAME[site.wdt], "B": B,
-                             "target": s, "density": round(dens, 4), "us": round(t, 2),
-                             "GBps": round(algorithmic_bytes(dens * K, K, N, B, wbytes) / t / 1e3, 1),
-                             "vs_dense": round(t_dense / t, 3)})
-        del Ws, W0
-        torch.cuda.empty_cache()
+        bench_site(torch, scap, wl, dev, rows, cfg_no, site, batches, targets, est, steps, library_gemm=(cfg_no == 4))
 
     run_site(1, wl.sites(1)[0], (1,), (0.5,), scap.MODE_MEDIAN)
     for st in wl.sites(2):
@@ -344,6 +385,8 @@ def main() -> int:
     ap.add_argument("--eager", action="store_true", help="time direct calls instead of a HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-sweep", action="store_true", help="only the headline point")
+    ap.add_argument("--no-summary", action="store_true",
+                    help="skip the few points of the other configurations that the default run appends")
     ap.add_argument("--cfg", type=str, default="", help="launch shape waves,rows,unroll (tuning)")
     ap.add_argument("--suite", action="store_true",
                     help="time every benchmark configuration (layers of configs 1-5, batches, sparsities) instead "
@@ -395,7 +438,7 @@ def main() -> int:
         print(f"bench.py: --batch 1..16, --target one of {site.targets}", file=sys.stderr)
         return 2
     if B > 1 or args.target != 0.5:
-        args.no_sweep = args.no_cpu = True
+        args.no_sweep = args.no_cpu = args.no_summary = True
     ws = scap.Workspace(K, N, B)
     ws_cal = scap.Workspace(K, 0, calib.shape[0])
     y = torch.empty((B, N), dtype=torch.float32, device=dev)
@@ -520,10 +563,27 @@ def main() -> int:
         coef, res, *_ = np.linalg.lstsq(A, tt, rcond=None)
         ss_tot = float(((tt - tt.mean()) ** 2).sum())
         r2 = 1.0 - float(((A @ coef - tt) ** 2).sum()) / ss_tot if ss_tot > 0 else 1.0
-        fit = {"t0_us": round(float(coef[0]), 3), "t1_us": round(float(coef[1]), 3), "r2": round(r2, 5)}
+        fit = {"t0_us": round(float(coef[0]), 3), "t1_us": round(float(coef[1]), 3), "r2": round(r2, 5),
+               "t0_over_dense": round(float(coef[0]) / sweep[0]["us"], 4)}
+        # The machine's floor for one dependent launch, to read the fixed part against: the back-to-back period
+        # of a kernel that does next to nothing (the 1-workgroup fill of a 4 KB workspace header), and of the
+        # headline call with a threshold that keeps no channel (every phase of the kernel except the row stream).
+        import ctypes
+        lib = scap.load_library()
+        tiny = torch.zeros(4096, dtype=torch.uint8, device=dev)
+
+        def tiny_launch(i):
+            lib.scap_workspace_init(ctypes.c_void_p(tiny.data_ptr()), 4096,
+                                    ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+
+        m, _, bf = layer[s_head]
+        floor = {"empty_kernel_period_us": round(graph_timed(torch, tiny_launch, sub_steps), 3),
+                 "nothing_kept_us": round(graph_timed(
+                     torch, lambda i: scap.sparse_fc(Ws[i % R], xin(i), m, 3.0e38, bf, y=y, workspace=ws, cfg=cfg), sub_steps), 3)}
     else:
         fit = None
         single_launch_us = None
+        floor = None
 
     # ---- CPU oracle on the host cores (baseline, not the target)
     cpu = None
@@ -543,14 +603,25 @@ def main() -> int:
             oracle.sparse_fc(W_host, X_host[nm % 64], m, tau, bf_host, site.wdt, site.xdt, nthreads=cores)
             nm += 1
         us_m = (time.perf_counter() - t0) / nm * 1e6
+        model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                for line in f:
+                    if line.startswith("model name"):
+                        model = line.split(":", 1)[1].strip()
+                        break
+        except OSError:
+            pass
         cpu = {"value": round(us_m, 1), "unit": "us/token", "cores": cores, "kind": "oracle",
+               "cpu_model": model, "nproc": os.cpu_count(),
                "sample": f"{nm} tokens of the headline workload, output columns split over {cores} threads; "
                          f"single thread: {round(us_1, 1)} us/token over {n1} tokens",
                "single_thread_us": round(us_1, 1)}
 
     workload = f"mistral7b_down_14336x4096_bf16_b{B}_s{int(round(s_head * 100))}"
-    kernel = ("scap::gemv_kernel<bf16>" if B <= 2 else
+    kernel = ("scap::gemv1_kernel<bf16>" if B == 1 else "scap::gemv_kernel<bf16>" if B == 2 else
               "scap::gemm_inline_raw_kernel<bf16> (matrix cores)")
+    summary = None if args.no_summary else suite_summary(torch, scap, wl, dev)
     out = {
         "metric": "sparse_fc_us_per_token" if B == 1 else "sparse_fc_us_per_call",
         "value": round(wall_ms * 1e3, 3),
@@ -568,7 +639,8 @@ def main() -> int:
                    "measured_density": round(mean_nnz / K, 4), "weight_copies_rotated": R,
                    "launch": "eager" if args.eager else "hipgraph", "launch_cfg": args.cfg or "default"},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(workload),
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(workload, (None, None))[0],
+                     "traffic_source": MEASURED_TRAFFIC.get(workload, (None, None))[1],
                      "kernel": kernel, "us_per_launch": round(ev_ms * 1e3, 3),
                      "algorithmic_bytes_per_launch": int(abytes)},
         "cpu_baseline": cpu,
@@ -576,6 +648,8 @@ def main() -> int:
         "read_ceiling_GBps": read_ceiling,
         "single_eager_launch_us": single_launch_us,
         "latency_vs_density_fit": fit,
+        "launch_floor": floor,
+        "suite_summary": summary,
     }
     print(json.dumps(out))
     return 0

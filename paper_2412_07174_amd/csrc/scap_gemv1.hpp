@@ -42,6 +42,48 @@ constexpr int kG1TicketWords = 32;   // int32 words between the tickets of a til
 
 constexpr int kG1FlagDeviceScope = 1;  // always fetch the partials with device-coherent loads
 
+// int8 weights read 8 bytes per lane instead of 16 (internal to this kernel): the column tile is 512 columns
+// instead of 1024, so a layer with few columns gets twice the tiles and half the K splits.  With 4096 columns
+// that is 8 tiles of 32 splits instead of 4 of 64: half as many partial sums per finished slice.
+constexpr int kI8Half = 3;
+template <> struct Vec<kI8Half> { static constexpr int kElems = 8; static constexpr int kBytes = 1; };
+
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(1))) const u32x2_t global_u32x2_t;
+
+// this lane's vector of weight row `row` (wave-uniform): scalar row base plus the lane's byte offset
+template <int WDT>
+__device__ __forceinline__ uint4 load_row(const char* __restrict__ wbase, uint32_t row, uint32_t row_bytes, uint32_t lane_off) {
+    if constexpr (WDT == kI8Half) {
+        const uint64_t base = reinterpret_cast<uint64_t>(wbase) + (uint64_t)row * (uint64_t)row_bytes;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base >> 32));
+        typedef __attribute__((address_space(1))) const char gchar_t;
+        gchar_t* p = (gchar_t*)(((uint64_t)hi << 32) | lo);
+        const u32x2_t v = __builtin_nontemporal_load((global_u32x2_t*)(p + lane_off));
+        return make_uint4(v.x, v.y, 0u, 0u);
+    } else {
+        return load_row_vec(wbase, row, row_bytes, lane_off);
+    }
+}
+
+template <int WDT>
+__device__ __forceinline__ void fma_row(float* __restrict__ acc, const uint4& r, float d) {
+    if constexpr (WDT == kI8Half) {
+        const uint32_t w[2] = {r.x, r.y};
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int v = ((int)(w[q] << (24 - 8 * j))) >> 24;
+                acc[4 * q + j] = fmaf((float)v, d, acc[4 * q + j]);
+            }
+        }
+    } else {
+        fma_vec<WDT>(acc, r, d);
+    }
+}
+
 struct Gemv1Args {
     const void* W;
     const uint16_t* x;
@@ -174,6 +216,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
     a.idx_out = idx_out; a.nnz_out = nnz_out; a.union_nnz_out = union_nnz_out; a.seg_cnt = seg_cnt;
     a.K = K; a.N = N; a.Kc = Kc; a.S = S; a.T = T; a.mode = mode; a.xdt = xdt; a.flags = flags; a.m = m; a.tau = tau;
     constexpr int ELEMS = Vec<WDT>::kElems;
+    constexpr bool IS_I8 = WDT == kI8 || WDT == kI8Half;
     constexpr int TILE = kWave * ELEMS;
     constexpr int CPL = ELEMS / 8;      // columns per lane of a wavefront's slice
     constexpr int SLICE = kWave * CPL;  // columns per slice: 1/8 of the tile
@@ -221,7 +264,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
         cscale[c] = 1.f;
         if (fcol + c < a.N) {
             if (a.bias) cbias[c] = a.bias[fcol + c];
-            if (WDT == kI8) cscale[c] = f16_bits_to_f32(a.col_scale[fcol + c]);
+            if (IS_I8) cscale[c] = f16_bits_to_f32(a.col_scale[fcol + c]);
         }
     }
 
@@ -308,7 +351,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
         const float vd = __int_as_float(ent.y);
         const int nb = min((int)kWave, n_w - i0);
         auto row_load = [&](int i) {
-            return load_row_vec(wbase, (uint32_t)__builtin_amdgcn_readlane(vidx, i), row_bytes, lane_off);
+            return load_row<WDT>(wbase, (uint32_t)__builtin_amdgcn_readlane(vidx, i), row_bytes, lane_off);
         };
         uint4 r[UNROLL];
         if (nb < UNROLL) {
@@ -317,7 +360,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
                 if (q < nb) r[q] = row_load(q);
 #pragma unroll
             for (int q = 0; q < UNROLL - 1; ++q)
-                if (q < nb) fma_vec<WDT>(acc, r[q], read_lane_f(vd, q));
+                if (q < nb) fma_row<WDT>(acc, r[q], read_lane_f(vd, q));
         } else {
 #pragma unroll
             for (int q = 0; q < UNROLL; ++q) r[q] = row_load(q);
@@ -325,7 +368,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
             for (; u + 2 * UNROLL <= nb; u += UNROLL) {
 #pragma unroll
                 for (int q = 0; q < UNROLL; ++q) {
-                    fma_vec<WDT>(acc, r[q], read_lane_f(vd, u + q));
+                    fma_row<WDT>(acc, r[q], read_lane_f(vd, u + q));
                     r[q] = row_load(u + UNROLL + q);
                     __builtin_amdgcn_sched_barrier(0);  // keep each load where it is: right behind the row it replaces
                 }
@@ -334,13 +377,13 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
             const int rest = nb - u - UNROLL;
 #pragma unroll
             for (int q = 0; q < UNROLL; ++q) {
-                fma_vec<WDT>(acc, r[q], read_lane_f(vd, u + q));
+                fma_row<WDT>(acc, r[q], read_lane_f(vd, u + q));
                 if (q < rest) r[q] = row_load(u + UNROLL + q);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int q = 0; q < UNROLL - 1; ++q)
-                if (q < rest) fma_vec<WDT>(acc, r[q], read_lane_f(vd, u + UNROLL + q));
+                if (q < rest) fma_row<WDT>(acc, r[q], read_lane_f(vd, u + UNROLL + q));
         }
     }
 
@@ -363,7 +406,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
     auto finish = [&](const slice_t& s) {
 #pragma unroll
         for (int c = 0; c < CPL; ++c)
-            if (fcol + c < a.N) a.y[fcol + c] = (WDT == kI8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
+            if (fcol + c < a.N) a.y[fcol + c] = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
     };
     if (a.S == 1) {
         finish(sum);
