@@ -117,7 +117,7 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     }
 
     // One token: the one-token kernel, unless the caller asks for another workgroup shape or the general kernel.
-    if (a.B == 1 && !(cfg && ((cfg->flags & SCAP_CFG_GENERAL_KERNEL) || (cfg->waves_per_group && cfg->waves_per_group != 8) ||
+    if (a.B == 1 && !(cfg && ((cfg->flags & SCAP_CFG_GENERAL_KERNEL) || (cfg->waves_per_group && cfg->waves_per_group != 8 && cfg->waves_per_group != 4) ||
                               (cfg->lanes_per_row && cfg->lanes_per_row != 64)))) {
         const int rc = launch_gemv1(a, wdt, cfg, stream);
         if (rc != kG1NotApplicable) return rc;

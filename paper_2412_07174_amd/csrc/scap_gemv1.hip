@@ -3,10 +3,10 @@
 
 namespace scap {
 
-extern template int launch_gemv1_wdt<kF16>(const Gemv1Args&, int, hipStream_t);
-extern template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, hipStream_t);
-extern template int launch_gemv1_wdt<kI8>(const Gemv1Args&, int, hipStream_t);
-extern template int launch_gemv1_wdt<kI8Half>(const Gemv1Args&, int, hipStream_t);
+extern template int launch_gemv1_wdt<kF16>(const Gemv1Args&, int, int, hipStream_t);
+extern template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, int, hipStream_t);
+extern template int launch_gemv1_wdt<kI8>(const Gemv1Args&, int, int, hipStream_t);
+extern template int launch_gemv1_wdt<kI8Half>(const Gemv1Args&, int, int, hipStream_t);
 
 // One token through a K x N layer (sparse, dense or bias-folding mode).  Returns a scap_status, or
 // kG1NotApplicable when the shape needs more than 2048 channels per workgroup (the caller then takes the
@@ -18,17 +18,18 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
     const bool i8_half = wdt == kI8 && g.N <= 4 * 1024;
     const int elems = wdt == kI8 && !i8_half ? 16 : 8;
     const int tile = kWave * elems;
-    int kc = 0, unroll = 0, flags = 0;
+    int kc = 0, unroll = 0, flags = 0, waves = 8;
     if (cfg) {
         if (cfg->rows_per_group) kc = cfg->rows_per_group;
         if (cfg->unroll) unroll = cfg->unroll;
+        if (cfg->waves_per_group) waves = cfg->waves_per_group;
         flags = cfg->flags;
         if (kc < 0 || (kc % 8) != 0) return SCAP_ERR_CONFIG;  // whole octets of channels per workgroup
         if (kc > kG1MaxChunks * kG1Chunk) return kG1NotApplicable;
     }
     GemvArgs p = g;
     // LDS: header, the eight wavefronts' sums, then 8 bytes per listed channel
-    const size_t lds_budget = 64 * 1024 - (size_t)kG1Waves * tile * 4 - 64 + (kHdrBytes - kG1HdrBytes);
+    const size_t lds_budget = 64 * 1024 - (size_t)waves * tile * 4 - 64 + (kHdrBytes - kG1HdrBytes);
     // Rows per workgroup in multiples of 64, unless the input is so short that 64-row pieces would leave compute
     // units without a workgroup (1024 x 4096: 16 splits x 8 tiles; with 32-row pieces 8.5 -> 6.5 us dense)
     p.T = (p.N + tile - 1) / tile;
@@ -62,9 +63,9 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
     a.m = g.m;
     a.tau = g.tau;
     switch (wdt) {
-        case kF16: return launch_gemv1_wdt<kF16>(a, unroll, stream);
-        case kBF16: return launch_gemv1_wdt<kBF16>(a, unroll, stream);
-        case kI8: return i8_half ? launch_gemv1_wdt<kI8Half>(a, unroll, stream) : launch_gemv1_wdt<kI8>(a, unroll, stream);
+        case kF16: return launch_gemv1_wdt<kF16>(a, waves, unroll, stream);
+        case kBF16: return launch_gemv1_wdt<kBF16>(a, waves, unroll, stream);
+        case kI8: return i8_half ? launch_gemv1_wdt<kI8Half>(a, waves, unroll, stream) : launch_gemv1_wdt<kI8>(a, waves, unroll, stream);
     }
     return SCAP_ERR_DTYPE;
 }

@@ -2,19 +2,19 @@
 // built around what a launch costs when no weight is streaming.
 //
 // The K input channels are cut into S ranges of Kc channels and the N columns into T tiles of one 16-byte vector
-// per lane (512 columns of 16-bit weights, 1024 of int8).  Workgroup (split, tile), 8 wavefronts:
+// per lane (512 columns of 16-bit weights, 1024 of int8).  Workgroup (split, tile), WAVES = 8 (or 4) wavefronts:
 //   1. EVERY wavefront tests all Kc inputs of the workgroup itself: one 16-byte load per lane covers 512
 //      channels, eight subtract-compare-ballot steps give the keep masks (Alg. 3 steps 1-2, strict compare of
 //      Eq. 2).  A kept channel's position in the workgroup's list follows from the ballots; wavefront w takes
-//      the positions p with p % 8 == w.  No count is exchanged, so there is no barrier before the first weight
+//      the positions p with p % WAVES == w.  No count is exchanged, so there is no barrier before the first weight
 //      load, and the kept rows are spread evenly over the wavefronts whatever the mask looks like.
 //   2. a wavefront streams its rows with UNROLL 16-byte loads per lane in flight, re-issuing a load as soon as
 //      its predecessor in the ring has been consumed (Eq. 3: only kept rows are ever addressed).
-//   3. one barrier; wavefront w then adds the eight wavefronts' sums of ITS slice of the tile (1/8 of the
+//   3. one barrier; wavefront w then adds the wavefronts' sums of ITS slice of the tile (1/WAVES of the
 //      columns), stores the slice's split-K partial and takes the slice's arrival ticket.  The last arrival of a
 //      (tile, slice) adds the S partials in split order -- a fixed order, so y is bit-reproducible -- applies
-//      the int8 scale and the fused bias (Eq. 6) and writes y.  Eight tickets per tile instead of one: the
-//      final sums of a tile are collected by up to eight compute units in parallel, each pulling S x 256 bytes,
+//      the int8 scale and the fused bias (Eq. 6) and writes y.  WAVES tickets per tile instead of one: the
+//      final sums of a tile are collected by up to WAVES compute units in parallel, each pulling S x 256 bytes,
 //      and no wavefront waits for another after the barrier.
 //
 // Hand-over of the partials between workgroups.  The stores are device-coherent write-through stores and the
@@ -33,8 +33,7 @@
 
 namespace scap {
 
-constexpr int kG1Waves = 8;
-constexpr int kG1Threads = kG1Waves * kWave;
+constexpr int kG1MaxWaves = 8;       // wavefronts per workgroup: 4 or 8
 constexpr int kG1Chunk = 8 * kWave;  // channels a wavefront tests per 16-byte load per lane
 constexpr int kG1MaxChunks = 4;      // Kc <= 2048
 constexpr int kG1HdrBytes = 2048;    // offsets and counts of up to 256 splits (closing the caller's lists)
@@ -152,6 +151,28 @@ template <> struct SliceVec<2> {
     }
 };
 
+template <> struct SliceVec<4> {
+    float v[4];
+    __device__ __forceinline__ static SliceVec from(const float4& t) {
+        SliceVec s;
+        s.v[0] = t.x;
+        s.v[1] = t.y;
+        s.v[2] = t.z;
+        s.v[3] = t.w;
+        return s;
+    }
+    __device__ __forceinline__ static SliceVec load_coherent(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        return from(load_coherent16(r, off));
+    }
+    __device__ __forceinline__ static SliceVec load_plain(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        const auto t = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+        return from(make_float4(__uint_as_float(t[0]), __uint_as_float(t[1]), __uint_as_float(t[2]), __uint_as_float(t[3])));
+    }
+    __device__ __forceinline__ void store_coherent(__amdgpu_buffer_rsrc_t r, uint32_t off) const {
+        store_coherent16(r, off, make_float4(v[0], v[1], v[2], v[3]));
+    }
+};
+
 // exclusive prefix sum across the 64 lanes of a wave
 __device__ __forceinline__ int wave_exclusive_scan(int v) { return wave_inclusive_scan(v) - v; }
 
@@ -205,8 +226,8 @@ __device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off,
 // The arguments are passed one by one, the ones the prologue needs first: the leading 16 dwords of a kernel's
 // scalar arguments can be placed in registers by the dispatcher (kernel-argument preload), which takes the
 // argument fetch -- one memory round trip -- off the path to the first input load.
-template <int WDT, int UNROLL, int NCH>
-__global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, const void* W, int K, int N, int Kc, int S,
+template <int WDT, int WAVES, int UNROLL, int NCH>
+__global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x, const void* W, int K, int N, int Kc, int S,
                                                            int T, int mode, int xdt, int flags, float m, float tau,
                                                            const float* bias, float* y, float* partial,
                                                            int32_t* counters, const uint16_t* col_scale, int32_t* idx_out,
@@ -218,8 +239,9 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr bool IS_I8 = WDT == kI8 || WDT == kI8Half;
     constexpr int TILE = kWave * ELEMS;
-    constexpr int CPL = ELEMS / 8;      // columns per lane of a wavefront's slice
-    constexpr int SLICE = kWave * CPL;  // columns per slice: 1/8 of the tile
+    constexpr int CPL = ELEMS / WAVES;  // columns per lane of a wavefront's slice
+    constexpr int SLICE = kWave * CPL;  // columns per slice: 1/WAVES of the tile
+    static_assert(CPL == 1 || CPL == 2 || CPL == 4, "a slice is 4, 8 or 16 bytes per lane");
     typedef SliceVec<CPL> slice_t;
 
     extern __shared__ uint4 smem_raw[];
@@ -227,8 +249,8 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
     int* s_off = reinterpret_cast<int*>(smem);
     int* s_cnt = s_off + kMaxSplits;
     float* s_red = reinterpret_cast<float*>(smem + kG1HdrBytes);                           // [8][TILE]
-    int2* s_list = reinterpret_cast<int2*>(smem + kG1HdrBytes + kG1Waves * TILE * 4);      // [8][slots]
-    const int slots = a.Kc / kG1Waves + 1;
+    int2* s_list = reinterpret_cast<int2*>(smem + kG1HdrBytes + WAVES * TILE * 4);  // [WAVES][slots]
+    const int slots = a.Kc / WAVES + 1;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -290,7 +312,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
             // position of a kept channel in the workgroup's list, and the entries this wavefront owns
             auto place = [&](int j, float dv) {
                 const int pos = cnt + lanes_below(bal[j]);
-                if (((bal[j] >> lane) & 1) && (pos & (kG1Waves - 1)) == w) mylist[pos >> 3] = make_int2(kb + j, __float_as_int(dv));
+                if (((bal[j] >> lane) & 1) && (pos & (WAVES - 1)) == w) mylist[pos / WAVES] = make_int2(kb + j, __float_as_int(dv));
                 cnt += __popcll(bal[j]);
             };
             if (a.mode == kModeSparse) {
@@ -342,7 +364,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
     const uint32_t lane_off = col0 < a.N ? (uint32_t)col0 * Vec<WDT>::kBytes : 0u;  // lanes past N re-read column 0
     const uint32_t row_bytes = (uint32_t)a.N * Vec<WDT>::kBytes;
     const char* wbase = reinterpret_cast<const char*>(a.W);
-    const int n_w = cnt > w ? (cnt - w + kG1Waves - 1) / kG1Waves : 0;  // positions w, w+8, ...
+    const int n_w = cnt > w ? (cnt - w + WAVES - 1) / WAVES : 0;  // positions w, w + WAVES, ...
 
     for (int i0 = 0; i0 < n_w; i0 += kWave) {
         const int e = i0 + lane;
@@ -398,7 +420,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
 #pragma unroll
     for (int c = 0; c < CPL; ++c) sum.v[c] = 0.f;
 #pragma unroll
-    for (int i = 0; i < kG1Waves; ++i) {
+    for (int i = 0; i < WAVES; ++i) {
 #pragma unroll
         for (int c = 0; c < CPL; ++c) sum.v[c] += s_red[i * TILE + w * SLICE + lane * CPL + c];
     }
@@ -435,7 +457,7 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
     slice_t total;
 #pragma unroll
     for (int c = 0; c < CPL; ++c) total.v[c] = 0.f;
-    constexpr int FLY = 32;  // partial loads in flight
+    constexpr int FLY = CPL == 4 ? 16 : 32;  // partial loads in flight
     for (int sp0 = 0; sp0 < a.S; sp0 += FLY) {
         slice_t v[FLY];
         if (near) {
@@ -458,42 +480,45 @@ __global__ __launch_bounds__(kG1Threads) void gemv1_kernel(const uint16_t* x, co
 }
 
 // ---------------------------------------------------------------------------------------------- launch
-inline size_t gemv1_lds_bytes(int tile_cols, int Kc) {
-    return (size_t)kG1HdrBytes + (size_t)kG1Waves * tile_cols * 4 + (size_t)kG1Waves * (Kc / kG1Waves + 1) * 8;
+inline size_t gemv1_lds_bytes(int tile_cols, int Kc, int waves) {
+    return (size_t)kG1HdrBytes + (size_t)waves * tile_cols * 4 + (size_t)waves * (Kc / waves + 1) * 8;
 }
 
 #define G1_ARGS                                                                                                    \
     a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, a.mode, a.xdt, a.flags, a.m, a.tau, a.bias, a.y, a.partial, a.counters, \
         a.col_scale, a.idx_out, a.nnz_out, a.union_nnz_out, a.seg_cnt
-template <int WDT, int UNROLL>
+template <int WDT, int WAVES, int UNROLL>
 static int launch_gemv1_nch(const Gemv1Args& a, hipStream_t stream) {
     constexpr int TILE = kWave * Vec<WDT>::kElems;
-    const size_t lds = gemv1_lds_bytes(TILE, a.Kc);
+    const size_t lds = gemv1_lds_bytes(TILE, a.Kc, WAVES);
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
-    const dim3 grid((unsigned)(a.S * a.T)), block(kG1Threads);
+    const dim3 grid((unsigned)(a.S * a.T)), block(WAVES * kWave);
     if (a.Kc <= kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 1>), grid, block, lds, stream, G1_ARGS);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 1>), grid, block, lds, stream, G1_ARGS);
     else if (a.Kc <= 2 * kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 2>), grid, block, lds, stream, G1_ARGS);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 2>), grid, block, lds, stream, G1_ARGS);
     else if (a.Kc <= 4 * kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, UNROLL, 4>), grid, block, lds, stream, G1_ARGS);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 4>), grid, block, lds, stream, G1_ARGS);
     else
         return SCAP_ERR_CONFIG;
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
-
 #undef G1_ARGS
 
-template <int WDT>
-int launch_gemv1_wdt(const Gemv1Args& a, int unroll, hipStream_t stream) {
+template <int WDT, int WAVES>
+static int launch_gemv1_unroll(const Gemv1Args& a, int unroll, hipStream_t stream) {
     switch (unroll) {
-        case 2: return launch_gemv1_nch<WDT, 2>(a, stream);
-        case 3: return launch_gemv1_nch<WDT, 3>(a, stream);
-        case 4: return launch_gemv1_nch<WDT, 4>(a, stream);
-        case 6: return launch_gemv1_nch<WDT, 6>(a, stream);
-        case 8: return launch_gemv1_nch<WDT, 8>(a, stream);
-        case 16: return launch_gemv1_nch<WDT, 16>(a, stream);
+        case 4: return launch_gemv1_nch<WDT, WAVES, 4>(a, stream);
+        case 8: return launch_gemv1_nch<WDT, WAVES, 8>(a, stream);
+        case 16: return launch_gemv1_nch<WDT, WAVES, 16>(a, stream);
     }
+    return SCAP_ERR_CONFIG;
+}
+
+template <int WDT>
+int launch_gemv1_wdt(const Gemv1Args& a, int waves, int unroll, hipStream_t stream) {
+    if (waves == 8) return launch_gemv1_unroll<WDT, 8>(a, unroll, stream);
+    if (waves == 4) return launch_gemv1_unroll<WDT, 4>(a, unroll, stream);
     return SCAP_ERR_CONFIG;
 }
 

@@ -2,5 +2,5 @@
 #include "scap_gemv1.hpp"
 
 namespace scap {
-template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, hipStream_t);
+template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, int, hipStream_t);
 }  // namespace scap
