@@ -163,16 +163,20 @@ def run_suite(args, torch, scap, wl, dev):
     def run_site(cfg_no, site, batches, targets, est):
         bench_site(torch, scap, wl, dev, rows, cfg_no, site, batches, targets, est, steps, library_gemm=(cfg_no == 4))
 
-    run_site(1, wl.sites(1)[0], (1,), (0.5,), scap.MODE_MEDIAN)
-    for st in wl.sites(2):
-        run_site(2, st, (1,), (0.5, 0.7, 0.9), scap.MODE_MEDIAN)
-    for st in wl.sites(3):
-        run_site(3, st, (1,), (0.5,), scap.MODE_MEDIAN)
-    for st in wl.sites(4):
-        run_site(4, st, (1, 4, 16), (0.5, 0.7, 0.9), scap.MODE_ZERO)
-    c5 = wl.sites(5)
-    run_site(5, c5[0], (1,), (0.4,), scap.MODE_MEDIAN)
-    run_site(5, c5[1], (1, 8), (0.7,), scap.MODE_MEDIAN)
+    def want(part):
+        return not args.only or args.only == part
+
+    if want("layers"):
+        run_site(1, wl.sites(1)[0], (1,), (0.5,), scap.MODE_MEDIAN)
+        for st in wl.sites(2):
+            run_site(2, st, (1,), (0.5, 0.7, 0.9), scap.MODE_MEDIAN)
+        for st in wl.sites(3):
+            run_site(3, st, (1,), (0.5,), scap.MODE_MEDIAN)
+        for st in wl.sites(4):
+            run_site(4, st, (1, 4, 16), (0.5, 0.7, 0.9), scap.MODE_ZERO)
+        c5 = wl.sites(5)
+        run_site(5, c5[0], (1,), (0.4,), scap.MODE_MEDIAN)
+        run_site(5, c5[1], (1, 8), (0.7,), scap.MODE_MEDIAN)
 
     # Feed-forward blocks (Alg. 2): the fused two-launch block against the same work as separate calls
     # (sparse_fc on [gate | up], torch silu * up and cast to 16 bits, sparse_fc on down) and the dense block.
@@ -238,8 +242,83 @@ def run_suite(args, torch, scap, wl, dev):
         del Wcat, Wgu, Wd
         torch.cuda.empty_cache()
 
-    run_block("mistral7b_ffn", 4096, 14336, 4096, (0.5, 0.7, 0.9))
-    run_block("llama2_7b_ffn", 4096, 11008, 4096, (0.5,))
+    if want("blocks"):
+        run_block("mistral7b_ffn", 4096, 14336, 4096, (0.5, 0.7, 0.9))
+        run_block("llama2_7b_ffn", 4096, 11008, 4096, (0.5,))
+
+    # Latency of the fused block against FFN sparsity (Appendix B: the latency-scaling figure and the rule
+    # FFN sparsity = 2/3 s_x + 1/3 s_gated for three equal-sized FCs): a grid of input and gated-product targets,
+    # each point timed on its own, then one straight line through all of them.
+    grids = []
+
+    def run_block_grid(name, K, F, N, wname):
+        dt = torch.bfloat16
+        i8 = wname == "i8"
+        levels = (0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8)
+        if i8:
+            Wgu0 = torch.randint(-127, 128, (K, 2 * F), dtype=torch.int8, device=dev)
+            Wd0 = torch.randint(-127, 128, (F, N), dtype=torch.int8, device=dev)
+            sgu = (torch.rand(2 * F, device=dev) * 2e-4 + 1e-4).to(torch.float16)
+            sdn = (torch.rand(N, device=dev) * 2e-4 + 1e-4).to(torch.float16)
+        else:
+            Wgu0 = (torch.randn(K, 2 * F, device=dev) * 0.02).to(dt)
+            Wd0 = (torch.randn(F, N, device=dev) * 0.02).to(dt)
+            sgu = sdn = None
+        wb = 1 if i8 else 2
+        R = max(2, -(-(1 << 30) // (3 * K * F * wb)))
+        Wgu = [Wgu0] + [Wgu0.clone() for _ in range(R - 1)]
+        Wd = [Wd0] + [Wd0.clone() for _ in range(R - 1)]
+        site = wl.Site(name, K, 2 * F, wl.BF16, wl.BF16, "prenorm", 128, 4101, 4102, 4103)
+        X = dev16(site.draw(64, site.seed_test), wl.BF16)
+        calib = dev16(site.draw(32, site.seed_calib), wl.BF16)
+        ws = scap.Workspace(K, N, 1, F=F)
+        y = torch.empty((1, N), dtype=torch.float32, device=dev)
+        zf = torch.empty((1, F), dtype=torch.float32, device=dev)
+        nz = torch.zeros(1, dtype=torch.int32, device=dev)
+        nx = torch.zeros(1, dtype=torch.int32, device=dev)
+        ygu = torch.empty((1, 2 * F), dtype=torch.float32, device=dev)
+        n = max(50, steps // 2)
+        t_dense = graph_timed(torch, lambda i: scap.swiglu_block(Wgu[i % R], Wd[i % R], X[i % 64], 0.0, 0.0, None, 0.0, 0.0,
+                                                                 None, gu_scale=sgu, down_scale=sdn, y=y, workspace=ws), n)
+        pts = []
+        for sx in levels:
+            m_x, tau_x = scap.calibrate(calib, sx, scap.MODE_MEDIAN, workspace=ws)
+            bgu = scap.fold_bias(Wgu[0], m_x, None, col_scale=sgu, workspace=ws)
+            zc = torch.empty((32, F), dtype=dt, device=dev)
+            for j in range(32):   # the gated product the block itself forms at this input sparsity
+                scap.swiglu_block(Wgu[0], Wd[0], calib[j], m_x, tau_x, bgu, 0.0, 0.0, None, gu_scale=sgu, down_scale=sdn,
+                                  y=y, z_out=zf, workspace=ws)
+                zc[j] = zf[0].to(dt)
+            for sz in levels:
+                _, tau_z = scap.calibrate(zc, sz, scap.MODE_ZERO, workspace=ws)
+                dx = dz = 0.0
+                for i in range(4):
+                    scap.sparse_fc(Wgu[0], X[i], m_x, tau_x, bgu, col_scale=sgu, y=ygu, nnz_out=nx, workspace=ws)
+                    scap.swiglu_block(Wgu[0], Wd[0], X[i], m_x, tau_x, bgu, 0.0, tau_z, None, gu_scale=sgu, down_scale=sdn,
+                                      y=y, nnz_z_out=nz, workspace=ws)
+                    dx += nx.item() / K / 4
+                    dz += nz.item() / F / 4
+                t = graph_timed(torch, lambda i: scap.swiglu_block(Wgu[i % R], Wd[i % R], X[i % 64], m_x, tau_x, bgu, 0.0, tau_z,
+                                                                   None, gu_scale=sgu, down_scale=sdn, y=y, workspace=ws), n)
+                ffn = (2 * (1 - dx) + (1 - dz)) / 3
+                pts.append({"s_x": sx, "s_gated": sz, "sparsity_x": round(1 - dx, 4), "sparsity_gated": round(1 - dz, 4),
+                            "ffn_sparsity": round(ffn, 4), "us": round(t, 2)})
+        xs_ = np.array([0.0] + [p["ffn_sparsity"] for p in pts])
+        ts_ = np.array([t_dense] + [p["us"] for p in pts])
+        A = np.stack([np.ones_like(xs_), xs_], axis=1)
+        coef, *_ = np.linalg.lstsq(A, ts_, rcond=None)
+        r2 = 1.0 - float(((A @ coef - ts_) ** 2).sum()) / float(((ts_ - ts_.mean()) ** 2).sum())
+        grids.append({"block": name, "w": wname, "K": K, "F": F, "N": N, "nothing_pruned_us": round(t_dense, 2),
+                      "fit_us_at_ffn_sparsity_0": round(float(coef[0]), 2), "fit_us_per_unit_ffn_sparsity": round(float(coef[1]), 2),
+                      "fit_us_at_ffn_sparsity_1": round(float(coef[0] + coef[1]), 2), "r2": round(r2, 5),
+                      "max_abs_residual_us": round(float(np.abs(A @ coef - ts_).max()), 2), "launches_per_point": n,
+                      "points": pts})
+        del Wgu, Wd, Wgu0, Wd0
+        torch.cuda.empty_cache()
+
+    if want("grid"):
+        run_block_grid("mistral7b_ffn", 4096, 14336, 4096, "bf16")
+        run_block_grid("mistral7b_ffn", 4096, 14336, 4096, "i8")
 
     # Mixture-of-experts feed-forward (config 5): 8 int8 experts, top-2 routing from seeded logits, the tokens
     # of a step grouped per expert; an expert's group goes through the fused block or through separate calls.
@@ -345,13 +424,14 @@ def run_suite(args, torch, scap, wl, dev):
                              "sparse_fused_blocks_4_streams_us": round(t_streams, 1),
                              "vs_dense": round(t_dense / t_fused, 3)})
 
-    run_moe()
+    if want("moe"):
+        run_moe()
     torch.cuda.empty_cache()
 
     # Offline calibration at the paper's sample size (64 slices x 256 tokens per layer): wall time of the
     # synchronous call (one counting pass on the GPU, statistics on the host), median estimator + threshold.
     calib_rows = []
-    for K in (4096, 14336):
+    for K in ((4096, 14336) if want("calibration") else ()):
         n = 16384
         Xc = torch.randn(n, K, device=dev).to(torch.bfloat16)
         wsc = scap.Workspace(K, 0, n)
@@ -371,7 +451,7 @@ def run_suite(args, torch, scap, wl, dev):
     layer3 = [r for r in rows if r["cfg"] == 3]
     summary = {"mistral_layer_fc_set_dense_us": round(sum(r["us"] for r in layer3 if r["target"] is None), 2),
                "mistral_layer_fc_set_s50_us": round(sum(r["us"] for r in layer3 if r["target"] == 0.5), 2)}
-    print(json.dumps({"suite": rows, "blocks": blocks, "moe": moe_rows, "calibration": calib_rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
+    print(json.dumps({"suite": rows, "blocks": blocks, "block_latency_vs_ffn_sparsity": grids, "moe": moe_rows, "calibration": calib_rows, "summary": summary, "steps_per_point": steps, "launch": "hipgraph",
                       "note": "GB/s = (rows read x N x sizeof(w) + x + bias + y) / time; density = union of the "
                               "batch's masks / K"}))
     return 0
@@ -388,6 +468,9 @@ def main() -> int:
     ap.add_argument("--no-summary", action="store_true",
                     help="skip the few points of the other configurations that the default run appends")
     ap.add_argument("--cfg", type=str, default="", help="launch shape waves,rows,unroll (tuning)")
+    ap.add_argument("--only", type=str, default="",
+                    help="with --suite: only the named part: layers, blocks, grid (fused-block latency against FFN "
+                         "sparsity), moe or calibration")
     ap.add_argument("--suite", action="store_true",
                     help="time every benchmark configuration (layers of configs 1-5, batches, sparsities) instead "
                          "of the headline run")
