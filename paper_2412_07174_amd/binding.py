@@ -151,6 +151,15 @@ class _Args:
             raise ValueError(f"{what}: shape {tuple(t.shape)}, expected {shape}")
         self.seen.append((what, t))   # where it lives is checked last, by on_one_gpu()
 
+    def rows(self, t: Optional[torch.Tensor], what: str, B: int, width: int, dtype, optional: bool = True) -> None:
+        """A [rows, width] buffer with at least B rows (or a [width] vector for one token)."""
+        self.want(t, what, dtype=dtype, optional=optional)
+        if t is None:
+            return
+        ok = (t.dim() == 2 and t.shape[1] == width and t.shape[0] >= B) or (B == 1 and tuple(t.shape) == (width,))
+        if not ok:
+            raise ValueError(f"{what}: shape {tuple(t.shape)}, expected [>= {B}, {width}]")
+
     def on_one_gpu(self, workspace=None) -> None:
         """Every tensor of the call, and the workspace, on one GPU."""
         seen = list(self.seen)
@@ -254,9 +263,8 @@ def sparse_fc(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_fused: O
     K, N = W.shape
     B = a.tokens(x, K, W.device)
     a.want(b_fused, "b_fused", shape=(N,), dtype=torch.float32, optional=True)
-    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32, optional=True)
-    a.want(idx_out, "idx_out", shape=[(B, K)] + ([(K,)] if B == 1 else []), dtype=torch.int32,
-          optional=True)
+    a.rows(y, "y", B, N, torch.float32)
+    a.rows(idx_out, "idx_out", B, K, torch.int32)
     for t, what in ((nnz_out, "nnz_out"), (union_nnz_out, "union_nnz_out")):
         a.want(t, what, dtype=torch.int32, optional=True)
     if nnz_out is not None and nnz_out.numel() < B:
@@ -291,8 +299,8 @@ def sparse_fc_static(W: torch.Tensor, x: torch.Tensor, m: float, tau: float, b_f
     K, N = W.shape
     B = a.tokens(x, K)
     a.want(b_fused, "b_fused", shape=(N,), dtype=torch.float32, optional=True)
-    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32)
-    a.want(idx_out, "idx_out", shape=[(B, K)] + ([(K,)] if B == 1 else []), dtype=torch.int32, optional=True)
+    a.rows(y, "y", B, N, torch.float32, optional=False)
+    a.rows(idx_out, "idx_out", B, K, torch.int32)
     for t, what in ((nnz_out, "nnz_out"), (union_nnz_out, "union_nnz_out")):
         a.want(t, what, dtype=torch.int32, optional=True)
     if nnz_out is not None and nnz_out.numel() < B:
@@ -315,7 +323,7 @@ def dense_fc(W: torch.Tensor, x: torch.Tensor, bias: Optional[torch.Tensor] = No
     K, N = W.shape
     B = a.tokens(x, K, W.device)
     a.want(bias, "bias", shape=(N,), dtype=torch.float32, optional=True)
-    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32, optional=True)
+    a.rows(y, "y", B, N, torch.float32)
     a.on_one_gpu(workspace)
     if y is None:
         y = torch.empty((B, N), dtype=torch.float32, device=x.device)
@@ -358,10 +366,9 @@ def swiglu_block(W_gu: torch.Tensor, W_down: torch.Tensor, x: torch.Tensor, m_x:
     dev = W_gu.device
     a.want(b_gu_fused, "b_gu_fused", shape=(2 * F,), dtype=torch.float32, optional=True)
     a.want(b_down_fused, "b_down_fused", shape=(N,), dtype=torch.float32, optional=True)
-    a.want(y, "y", shape=[(B, N)] + ([(N,)] if B == 1 else []), dtype=torch.float32, optional=True)
-    one = [(F,)] if B == 1 else []
-    a.want(z_out, "z_out", shape=[(B, F)] + one, dtype=torch.float32, optional=True)
-    a.want(idx_z_out, "idx_z_out", shape=[(B, F)] + one, dtype=torch.int32, optional=True)
+    a.rows(y, "y", B, N, torch.float32)
+    a.rows(z_out, "z_out", B, F, torch.float32)
+    a.rows(idx_z_out, "idx_z_out", B, F, torch.int32)
     a.want(nnz_z_out, "nnz_z_out", dtype=torch.int32, optional=True)
     if nnz_z_out is not None and nnz_z_out.numel() < B:
         raise ValueError(f"nnz_z_out: {nnz_z_out.numel()} entries for {B} tokens")
