@@ -1,6 +1,11 @@
 // Pieces shared by the kernels that run the gathered product on the matrix cores (gfx950 MFMA):
 //
 //     Y[16 tokens, 16 columns] += D[16 tokens, 16 rows] * W[16 rows, 16 columns]     v_mfma_f32_16x16x16_bf16
+//     Y[16 tokens, 16 columns] += D[16 tokens, 32 rows] * W[32 rows, 16 columns]     v_mfma_f32_16x16x32_bf16
+//
+// (the second, gfx950's own shape, in the staged-tile kernel: mfma_block32 below -- same lane layout with 8
+// instead of 4 k-slots per lane, A[m = l%16][k = 8*(l/16) + j], B[k = 8*(l/16) + j][n = l%16], j = 0..7, fed from
+// two 16-row blocks of the list at a time; half the matrix instructions for the same rows)
 //
 // Operand layout without any transposition.  For this instruction lane l holds
 //     A[m = l%16][k = 4*(l/16) + j],   B[k = 4*(l/16) + j][n = l%16],   C[m = 4*(l/16) + i][n = l%16],  i,j = 0..3.
@@ -118,6 +123,59 @@ __device__ __forceinline__ void mfma_block(f32x4_t* __restrict__ acc, s16x4_t a_
         } else {
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_hi, bop.v, acc[e], 0, 0, 0);
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a_lo, bop.v, acc[e], 0, 0, 0);
+        }
+    }
+}
+
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+// Two 16-row blocks at once on the 32-deep instruction: r[0..3] = this lane's 16 bytes of rows 4*(l/16)+j of the
+// first block, r[4..7] of the second (zeros for slots past the list); a_hi / a_lo = heads and tails of the eight
+// matching centred values.  Which list row sits in which of the lane's 8 k-slots is free as long as A and B
+// agree.  acc[e] += A * B_e for the ELEMS column elements.
+template <int WDT>
+__device__ __forceinline__ void mfma_block32(f32x4_t* __restrict__ acc, const s16x4_t (&a_hi)[2], const s16x4_t (&a_lo)[2],
+                                             const uint4 (&r)[8]) {
+    constexpr int ELEMS = Vec<WDT>::kElems;
+    union { s16x4_t h[2]; bf16x8_t b; f16x8_t f; } ah, al;
+    ah.h[0] = a_hi[0];
+    ah.h[1] = a_hi[1];
+    al.h[0] = a_lo[0];
+    al.h[1] = a_lo[1];
+    uint32_t q[8][4];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        q[j][0] = r[j].x;
+        q[j][1] = r[j].y;
+        q[j][2] = r[j].z;
+        q[j][3] = r[j].w;
+    }
+#pragma unroll
+    for (int e = 0; e < ELEMS; ++e) {
+        union { uint32_t u32[4]; bf16x8_t b; f16x8_t f; } bop;  // rows (0,1), (2,3), (4,5), (6,7) of column element e
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+            const uint32_t* x0 = q[2 * pr];
+            const uint32_t* x1 = q[2 * pr + 1];
+            if constexpr (WDT == kBF16 || WDT == kF16) {
+                const int c = e >> 1;
+                bop.u32[pr] = (e & 1) == 0 ? ((x0[c] & 0xFFFFu) | (x1[c] << 16)) : ((x0[c] >> 16) | (x1[c] & 0xFFFF0000u));
+            } else {
+                // byte e of each row, sign-extended, as a float: its low 16 bits are zero (|v| <= 128)
+                const int c = e >> 2, sh = 24 - 8 * (e & 3);
+                const uint32_t f0 = __float_as_uint((float)(((int)(x0[c] << sh)) >> 24));
+                const uint32_t f1 = __float_as_uint((float)(((int)(x1[c] << sh)) >> 24));
+                bop.u32[pr] = (f0 >> 16) | f1;
+            }
+        }
+        if constexpr (WDT == kF16) {
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah.f, bop.f, acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al.f, bop.f, acc[e], 0, 0, 0);
+        } else {
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah.b, bop.b, acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al.b, bop.b, acc[e], 0, 0, 0);
         }
     }
 }
