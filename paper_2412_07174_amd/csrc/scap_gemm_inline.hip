@@ -358,7 +358,9 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
     return cnt;
 }
 
-template <int WDT, int FUSE>
+// X32: the 32-deep matrix instruction (bf16 / fp16 weights).  It needs 151 registers per lane against 109, i.e. one
+// workgroup per compute unit instead of two, so launches of more than 256 workgroups keep the 16-deep form.
+template <int WDT, int FUSE, bool X32>
 __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_raw_kernel(const GemvArgs a) {
     constexpr int WAVES = kInlineWaves;
     constexpr int BT = kMfmaTokens;
@@ -448,9 +450,9 @@ __global__ __launch_bounds__(kInlineWaves* kWave) void gemm_inline_raw_kernel(co
         }
         st.d = make_float4(dm[0], dm[1], dm[2], dm[3]);
     };
-    if constexpr (WDT == kI8) {
-        // int8 weights stay on the 16-deep instruction: with 16 columns per lane the 32-deep form needs 180
-        // registers and measured slower (14336 x 4096, 16 tokens: 23.3 against 24.8 us)
+    if constexpr (!X32) {
+        // (int8 weights always: with 16 columns per lane the 32-deep form needs 180 registers and measured slower,
+        // 14336 x 4096, 16 tokens: 23.3 against 24.8 us)
         auto compute = [&](const Stage& st) {
             s16x4_t a_hi, a_lo;
             split_operand<WDT>(st.d, a_hi, a_lo);
@@ -566,7 +568,7 @@ static int launch_inline(const GemvArgs& a, size_t lds, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
-template <int WDT, int FUSE>
+template <int WDT, int FUSE, bool X32>
 static int launch_inline_raw(const GemvArgs& a, size_t lds, hipStream_t stream) {
     if (lds > kInlineLdsBudget) return SCAP_ERR_SHAPE;
     if (lds > 64 * 1024) {
@@ -575,21 +577,26 @@ static int launch_inline_raw(const GemvArgs& a, size_t lds, hipStream_t stream) 
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SCAP_ERR_HIP;
         if (!asked[dev].load(std::memory_order_acquire)) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_inline_raw_kernel<WDT, FUSE>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_inline_raw_kernel<WDT, FUSE, X32>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kInlineLdsBudget) != hipSuccess)
                 return SCAP_ERR_HIP;
             asked[dev].store(true, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL((gemm_inline_raw_kernel<WDT, FUSE>), dim3((unsigned)(a.S * a.T)), dim3(kInlineWaves * kWave), lds,
-                       stream, a);
+    hipLaunchKernelGGL((gemm_inline_raw_kernel<WDT, FUSE, X32>), dim3((unsigned)(a.S * a.T)), dim3(kInlineWaves * kWave),
+                       lds, stream, a);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
 template <int WDT, int FUSE>
 static int launch_inline_wdt(const GemvArgs& a, int bt, bool raw, size_t lds, hipStream_t stream) {
     if constexpr (FUSE != kFuseList) {
-        if (raw) return launch_inline_raw<WDT, FUSE>(a, lds, stream);
+        if (raw) {
+            if constexpr (WDT != kI8) {
+                if ((long)a.S * a.T <= 256) return launch_inline_raw<WDT, FUSE, true>(a, lds, stream);
+            }
+            return launch_inline_raw<WDT, FUSE, false>(a, lds, stream);
+        }
     }
     if constexpr (WDT == kF16)  // fp16 weights: 16 token slots only (2-4 tokens stay on the vector kernel)
         return launch_inline<WDT, 16, FUSE>(a, lds, stream);
