@@ -216,9 +216,12 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
     // of this prologue.  Each wavefront therefore tests its first chunk; if at most 2 of its 64 channels are
     // dropped by every token, it lists its other chunks whole (a few rows read for nothing against three
     // quarters of the tests).  Dense mode lists everything without a test (there that is the exact union).
-    // The decision depends on the inputs only, so every column tile of a split takes the same one.  Column
-    // tile 0 tests everything when the caller asked for the size of the union, which has to be exact.
-    const bool exact_only = tile == 0 && a.union_nnz_out != nullptr;
+    // The decision depends on the inputs only, so every column tile of a split takes the same one: the list,
+    // and with it the order of every fp32 sum, never depends on which outputs the caller asked for.  When the
+    // caller wants the size of the union, which has to be exact, column tile 0 also tests the chunks it lists
+    // whole, for the count alone.
+    const bool count_exactly = tile == 0 && a.union_nnz_out != nullptr;
+    int ecount = 0;  // channels kept by at least one token among those tested (the exact union where all are)
     auto test_chunks = [&](auto bf16x) {
         constexpr bool BF16X = decltype(bf16x)::value;
         // stage chunk slot j and list all its channels (wave-uniform)
@@ -272,17 +275,25 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
                 }
                 um[j] = u;  // bit i: channel i of the chunk is kept by some token
                 ucount += __popcll(u);
+                ecount += __popcll(u);
             }
         };
         if constexpr (SUPERSET) {
             if (dense) {  // every element that exists is kept: the list is all valid channels, exactly
 #pragma unroll
                 for (int j = 0; j < MAXC; ++j) list_whole(j);
+                ecount = ucount;
                 return;
             }
             test_slot(0);
             const int nval0 = c_begin < c_end ? min((int)kWave, kend - (k0 + c_begin * kWave)) : 0;
-            if (!exact_only && __popcll(um[0]) + 2 >= nval0) {  // wave-uniform
+            if (__popcll(um[0]) + 2 >= nval0) {  // wave-uniform
+                if (count_exactly) {
+                    const int listed = ucount;
+#pragma unroll
+                    for (int j = 1; j < MAXC; ++j) test_slot(j);  // adds to ecount; the list is rebuilt below
+                    ucount = listed;
+                }
 #pragma unroll
                 for (int j = 1; j < MAXC; ++j) list_whole(j);
             } else {
@@ -298,7 +309,10 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
         test_chunks(std::true_type{});
     else
         test_chunks(std::false_type{});
-    if (lane == 0) L.hdr[w] = ucount;
+    if (lane == 0) {
+        L.hdr[w] = ucount;
+        L.hdr[(2 + BT) * WAVES + w] = ecount;  // behind the per-token rows and the flag row
+    }
     __syncthreads();  // counts published, tile staged
 
     // ---- per-token counts (column tile 0 on request): one channel per lane from the staged tile
@@ -353,7 +367,11 @@ __device__ __forceinline__ int stage_inputs_and_list(const GemvArgs& a, int tile
             if (tid == 0 && b < a.B) store_dev(&a.seg_cnt[b * a.Sl + split], ttotal);
         }
     }
-    if (tile == 0 && tid == 0) store_dev(&a.seg_cnt[a.B * a.Sl + split], cnt);  // union
+    if (tile == 0 && tid == 0) {  // size of the union: the list's length, or the exact count where the list is a superset
+        int exact = 0;
+        for (int i = 0; i < WAVES; ++i) exact += L.hdr[(2 + BT) * WAVES + i];
+        store_dev(&a.seg_cnt[a.B * a.Sl + split], count_exactly ? exact : cnt);
+    }
     __syncthreads();
     return cnt;
 }

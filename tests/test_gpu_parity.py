@@ -361,7 +361,7 @@ def test_staged_tile_kernel_lists_a_superset_of_the_union(wdt):
     """A wavefront whose first 64-channel chunk is kept entirely lists its other chunks without testing them.
     Here every fourth chunk holds large values and the three after it values that every token drops, with 1792
     channels per workgroup (4 chunks per wavefront): the lists are four times the union, and y, the per-token
-    lists and the size of the union (column tile 0 tests everything when they are asked for) must not change."""
+    lists and the size of the union (column tile 0 counts it exactly when it is asked for) must not change."""
     K, N, B = 7168, 392, 16
     W = wl.weights(K, N, 541, wdt)
     layer = Layer(W, wdt, B=16)
@@ -379,6 +379,11 @@ def test_staged_tile_kernel_lists_a_superset_of_the_union(wdt):
         say(f"superset lists wdt={wdt} cfg={cfg}")
         got, want = check_against_oracle(layer, X, wdt, 0.0, 0.5, bias, cfg=cfg, what=f"superset cfg={cfg}")
         assert want["union_nnz"] == (K // 256) * 64 - 1 + 1
+        # the rows that are read, and so the order of every sum, must not depend on which outputs were asked for
+        plain = torch.full((B, N), float("nan"), dtype=torch.float32, device="cuda")
+        scap.sparse_fc(layer.W, to_dev(X, wdt), 0.0, 0.5, f32_dev(bias), y=plain, workspace=layer.ws, cfg=cfg)
+        torch.cuda.synchronize()
+        assert np.array_equal(plain.cpu().numpy().view(np.uint32), got["y"].view(np.uint32)), "y depends on the outputs requested"
 
 
 @pytest.mark.parametrize("B", [4, 16])
