@@ -7,39 +7,50 @@ extern template int launch_gemv1_wdt<kF16>(const Gemv1Args&, int, int, hipStream
 extern template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, int, hipStream_t);
 extern template int launch_gemv1_wdt<kI8>(const Gemv1Args&, int, int, hipStream_t);
 extern template int launch_gemv1_wdt<kI8Half>(const Gemv1Args&, int, int, hipStream_t);
+#define SCAP_G1_BLOCK_EXTERN(WD)                                                             \
+    extern template int launch_gemv1_block<WD, kFuseSwiglu>(const Gemv1Args&, hipStream_t); \
+    extern template int launch_gemv1_block<WD, kFuseList>(const Gemv1Args&, hipStream_t);
+SCAP_G1_BLOCK_EXTERN(kF16)
+SCAP_G1_BLOCK_EXTERN(kBF16)
+SCAP_G1_BLOCK_EXTERN(kI8)
+SCAP_G1_BLOCK_EXTERN(kI8Half)
+#undef SCAP_G1_BLOCK_EXTERN
 
 // One token through a K x N layer (sparse, dense or bias-folding mode).  Returns a scap_status, or
 // kG1NotApplicable when the shape needs more than 2048 channels per workgroup (the caller then takes the
 // general kernel).  cfg: rows_per_group and unroll are honoured, flags bit 0 forces device-scope loads.
-int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStream_t stream) {
-    if (g.B != 1) return kG1NotApplicable;
+namespace {
+
+struct Plan1 {
+    bool i8_half;
+    int elems, tile, Kc, S, T;
+};
+
+// K split and lane width of one launch.  SCAP_OK, kG1NotApplicable or a scap_status.
+int plan_gemv1(const GemvArgs& g, int wdt, int kc, bool kc_forced, int waves, int granule_min, Plan1* out) {
     // int8 weights: 16 bytes per lane (1024-column tiles) unless that leaves at most 4 tiles -- then 8 bytes per
-    // lane, twice the tiles and half the K splits (14336 x 4096 int8: 18.8 -> ?? us dense)
-    const bool i8_half = wdt == kI8 && g.N <= 4 * 1024;
-    const int elems = wdt == kI8 && !i8_half ? 16 : 8;
-    const int tile = kWave * elems;
-    int kc = 0, unroll = 0, flags = 0, waves = 8;
-    if (cfg) {
-        if (cfg->rows_per_group) kc = cfg->rows_per_group;
-        if (cfg->unroll) unroll = cfg->unroll;
-        if (cfg->waves_per_group) waves = cfg->waves_per_group;
-        flags = cfg->flags;
-        if (kc < 0 || (kc % 8) != 0) return SCAP_ERR_CONFIG;  // whole octets of channels per workgroup
-        if (kc > kG1MaxChunks * kG1Chunk) return kG1NotApplicable;
-    }
+    // lane, twice the tiles and half the K splits (14336 x 4096 int8: 15.9 -> 14.2 us dense)
+    out->i8_half = wdt == kI8 && g.N <= 4 * 1024;
+    out->elems = wdt == kI8 && !out->i8_half ? 16 : 8;
+    out->tile = kWave * out->elems;
     GemvArgs p = g;
-    // LDS: header, the eight wavefronts' sums, then 8 bytes per listed channel
-    const size_t lds_budget = 64 * 1024 - (size_t)waves * tile * 4 - 64 + (kHdrBytes - kG1HdrBytes);
+    // LDS: header, the wavefronts' sums, then 8 bytes per listed channel
+    const size_t lds_budget = 64 * 1024 - (size_t)waves * out->tile * 4 - 64 + (kHdrBytes - kG1HdrBytes);
     // Rows per workgroup in multiples of 64, unless the input is so short that 64-row pieces would leave compute
     // units without a workgroup (1024 x 4096: 16 splits x 8 tiles; with 32-row pieces 8.5 -> 6.5 us dense)
-    p.T = (p.N + tile - 1) / tile;
-    const int granule = ((int64_t)((p.K + kWave - 1) / kWave) * p.T < 256) ? 8 : kWave;
-    const int rc = plan_splits(p, tile, 1, kc, cfg && cfg->rows_per_group, lds_budget, granule);
+    p.T = (p.N + out->tile - 1) / out->tile;
+    int granule = ((int64_t)((p.K + kWave - 1) / kWave) * p.T < 256) ? 8 : kWave;
+    if (granule < granule_min) granule = granule_min;
+    const int rc = plan_splits(p, out->tile, 1, kc, kc_forced, lds_budget, granule);
     if (rc != SCAP_OK) return rc == SCAP_ERR_SHAPE ? kG1NotApplicable : rc;
     if (p.Kc > kG1MaxChunks * kG1Chunk) return kG1NotApplicable;
+    out->Kc = p.Kc;
+    out->S = p.S;
+    out->T = p.T;
+    return SCAP_OK;
+}
 
-    // rows in flight per wavefront: 4 x 1 KB (16-byte lanes), 8 x 512 bytes (8-byte lanes)
-    if (unroll == 0) unroll = i8_half ? 8 : 4;
+Gemv1Args args_of(const GemvArgs& g, const Plan1& pl, int flags) {
     Gemv1Args a{};
     a.W = g.W;
     a.x = g.x;
@@ -54,20 +65,86 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
     a.seg_cnt = g.seg_cnt;
     a.K = g.K;
     a.N = g.N;
-    a.Kc = p.Kc;
-    a.S = p.S;
-    a.T = p.T;
+    a.Kc = pl.Kc;
+    a.S = pl.S;
+    a.T = pl.T;
     a.mode = g.mode;
     a.xdt = g.xdt;
     a.flags = flags;
     a.m = g.m;
     a.tau = g.tau;
+    return a;
+}
+
+}  // namespace
+
+// One token (B == 1) through a K x N layer (sparse, dense or bias-folding mode).  Returns a scap_status, or
+// kG1NotApplicable when the shape needs more than 2048 channels per workgroup (the caller then takes the
+// general kernel).  cfg: wavefronts (4, 8), rows_per_group and unroll are honoured, flags bit 0 forces device-scope loads.
+int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStream_t stream) {
+    if (g.B != 1) return kG1NotApplicable;
+    int kc = 0, unroll = 0, flags = 0, waves = 8;
+    if (cfg) {
+        if (cfg->rows_per_group) kc = cfg->rows_per_group;
+        if (cfg->unroll) unroll = cfg->unroll;
+        if (cfg->waves_per_group) waves = cfg->waves_per_group;
+        flags = cfg->flags;
+        if (kc < 0 || (kc % 8) != 0) return SCAP_ERR_CONFIG;  // whole octets of channels per workgroup
+        if (kc > kG1MaxChunks * kG1Chunk) return kG1NotApplicable;
+    }
+    Plan1 pl;
+    const int rc = plan_gemv1(g, wdt, kc, cfg && cfg->rows_per_group, waves, 8, &pl);
+    if (rc != SCAP_OK) return rc;
+    // rows in flight per wavefront: 4 x 1 KB (16-byte lanes), 8 x 512 bytes (8-byte lanes)
+    if (unroll == 0) unroll = pl.i8_half ? 8 : 4;
+    const Gemv1Args a = args_of(g, pl, flags);
     switch (wdt) {
         case kF16: return launch_gemv1_wdt<kF16>(a, waves, unroll, stream);
         case kBF16: return launch_gemv1_wdt<kBF16>(a, waves, unroll, stream);
-        case kI8: return i8_half ? launch_gemv1_wdt<kI8Half>(a, waves, unroll, stream) : launch_gemv1_wdt<kI8>(a, waves, unroll, stream);
+        case kI8: return pl.i8_half ? launch_gemv1_wdt<kI8Half>(a, waves, unroll, stream) : launch_gemv1_wdt<kI8>(a, waves, unroll, stream);
     }
     return SCAP_ERR_DTYPE;
+}
+
+template <int FUSE>
+static int launch_block_half(const Gemv1Args& a, int wdt, bool i8_half, hipStream_t stream) {
+    switch (wdt) {
+        case kF16: return launch_gemv1_block<kF16, FUSE>(a, stream);
+        case kBF16: return launch_gemv1_block<kBF16, FUSE>(a, stream);
+        case kI8: return i8_half ? launch_gemv1_block<kI8Half, FUSE>(a, stream) : launch_gemv1_block<kI8, FUSE>(a, stream);
+    }
+    return SCAP_ERR_DTYPE;
+}
+
+// Fused SwiGLU block of one token on the one-token kernel: the gate|up launch with the gating epilogue, then the
+// down launch reading the lists.  `up` and `down` as for launch_swiglu_block.  kG1NotApplicable when either layer
+// needs more than 2048 channels per workgroup.
+int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, hipStream_t stream) {
+    if (up.B != 1) return kG1NotApplicable;
+    Plan1 pu, pd;
+    int rc = plan_gemv1(up, wdt, 0, false, 8, kWave, &pu);
+    if (rc != SCAP_OK) return rc;
+    rc = plan_gemv1(dn, wdt, 0, false, 8, kWave, &pd);  // whole 64-channel pieces: whole list segments
+    if (rc != SCAP_OK) return rc;
+    const int segz = pu.tile / 8 / 2;  // gated channels a wavefront slice of the gate|up launch finishes: 32 or 64
+    if (pd.Kc % segz != 0 || pd.Kc / segz > kWave) return kG1NotApplicable;
+    Gemv1Args a = args_of(up, pu, 0);
+    Gemv1Args b = args_of(dn, pd, 0);
+    for (Gemv1Args* q : {&a, &b}) {
+        q->m2 = up.m2;
+        q->tau2 = up.tau2;
+        q->zl_idx = up.zl_idx;
+        q->zl_d = up.zl_d;
+        q->zl_cnt = up.zl_cnt;
+        q->F = up.F;
+        q->segz = segz;
+    }
+    a.z_out = up.z_out;
+    a.idx_out = a.nnz_out = a.union_nnz_out = nullptr;
+    b.x = nullptr;
+    rc = launch_block_half<kFuseSwiglu>(a, wdt, pu.i8_half, stream);
+    if (rc != SCAP_OK) return rc;
+    return launch_block_half<kFuseList>(b, wdt, pd.i8_half, stream);
 }
 
 }  // namespace scap

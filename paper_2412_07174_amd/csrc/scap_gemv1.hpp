@@ -97,6 +97,15 @@ struct Gemv1Args {
     int32_t* seg_cnt;    // [S] kept channels per split (only when the caller wants lists)
     int K, N, Kc, S, T, mode, xdt, flags;
     float m, tau;
+    // Fused SwiGLU block (Alg. 2), one token.  The gate|up launch (FUSE = kFuseSwiglu) leaves the gated product z,
+    // centred and thresholded, as one compacted list per `segz` channels -- the channels a wavefront slice
+    // finishes --; the down launch (kFuseList) takes those lists as its input.
+    float m2, tau2;    // mode estimate and threshold of the gated product
+    float* z_out;      // optional fp32 [F]: the gated product itself
+    int32_t* zl_idx;   // [nseg][segz] kept channels of each segment, ascending
+    float* zl_d;       // [nseg][segz] their centred values
+    int32_t* zl_cnt;   // [nseg] entries per segment
+    int F, segz;       // channels of the gated product; channels per list segment (32 or 64)
 };
 
 // id of the accelerator die (XCD) this wavefront runs on: hardware register XCC_ID (20), bits 3:0
@@ -226,16 +235,19 @@ __device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off,
 // The arguments are passed one by one, the ones the prologue needs first: the leading 16 dwords of a kernel's
 // scalar arguments can be placed in registers by the dispatcher (kernel-argument preload), which takes the
 // argument fetch -- one memory round trip -- off the path to the first input load.
-template <int WDT, int WAVES, int UNROLL, int NCH>
+template <int WDT, int WAVES, int UNROLL, int NCH, int FUSE>
 __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x, const void* W, int K, int N, int Kc, int S,
                                                            int T, int mode, int xdt, int flags, float m, float tau,
                                                            const float* bias, float* y, float* partial,
                                                            int32_t* counters, const uint16_t* col_scale, int32_t* idx_out,
-                                                           int32_t* nnz_out, int32_t* union_nnz_out, int32_t* seg_cnt) {
+                                                           int32_t* nnz_out, int32_t* union_nnz_out, int32_t* seg_cnt,
+                                                           float m2, float tau2, float* z_out, int32_t* zl_idx, float* zl_d,
+                                                           int32_t* zl_cnt, int F, int segz) {
     Gemv1Args a;
     a.W = W; a.x = x; a.col_scale = col_scale; a.bias = bias; a.y = y; a.partial = partial; a.counters = counters;
     a.idx_out = idx_out; a.nnz_out = nnz_out; a.union_nnz_out = union_nnz_out; a.seg_cnt = seg_cnt;
     a.K = K; a.N = N; a.Kc = Kc; a.S = S; a.T = T; a.mode = mode; a.xdt = xdt; a.flags = flags; a.m = m; a.tau = tau;
+    a.m2 = m2; a.tau2 = tau2; a.z_out = z_out; a.zl_idx = zl_idx; a.zl_d = zl_d; a.zl_cnt = zl_cnt; a.F = F; a.segz = segz;
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr bool IS_I8 = WDT == kI8 || WDT == kI8Half;
     constexpr int TILE = kWave * ELEMS;
@@ -262,18 +274,20 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
 
     // ------------------------------------------------------------------ 1. inputs: every wavefront, all Kc
     uint4 xv[NCH];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        xv[c] = make_uint4(0u, 0u, 0u, 0u);
-        const int kb = k0 + c * kG1Chunk + 8 * lane;
-        if (a.mode != kModeFold && kb < kend) {
-            if (kb + 8 <= a.K) {
-                xv[c] = *reinterpret_cast<const uint4*>(a.x + kb);
-            } else {  // the last octet of an input whose length is not a multiple of 8: element by element
-                uint32_t h[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) h[j] = kb + j < a.K ? (uint32_t)a.x[kb + j] : 0u;
-                xv[c] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    if constexpr (FUSE != kFuseList) {
+    #pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            xv[c] = make_uint4(0u, 0u, 0u, 0u);
+            const int kb = k0 + c * kG1Chunk + 8 * lane;
+            if (a.mode != kModeFold && kb < kend) {
+                if (kb + 8 <= a.K) {
+                    xv[c] = *reinterpret_cast<const uint4*>(a.x + kb);
+                } else {  // the last octet of an input whose length is not a multiple of 8: element by element
+                    uint32_t h[8];
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) h[j] = kb + j < a.K ? (uint32_t)a.x[kb + j] : 0u;
+                    xv[c] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                }
             }
         }
     }
@@ -290,63 +304,120 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
         }
     }
 
-    const bool want_lists = tile == 0 && w == 0 && (a.nnz_out != nullptr || a.union_nnz_out != nullptr);
+    const bool want_lists = FUSE != kFuseSwiglu && tile == 0 && w == 0 && (a.nnz_out != nullptr || a.union_nnz_out != nullptr);
     int2* mylist = s_list + w * slots;
     int cnt = 0;    // kept channels so far, in (chunk, element, lane) order -- wave-uniform
     int lcnt = 0;   // the same in ascending channel order (caller's list)
+    if constexpr (FUSE == kFuseList) {
+        // The workgroup's channels are Kc / segz list segments of the gated product.  Lane l takes the count of
+        // segment l (at most 64 segments), a prefix sum gives every entry its position; the entries are fetched 64
+        // at a time (whole segments side by side).
+        const int seg0 = k0 / a.segz;
+        const int nsegw = (kend - k0 + a.segz - 1) / a.segz;
+        const int per_it = kWave / a.segz;       // segments per fetch of 64 entries: 2 or 1
+        const int sub = lane / a.segz, r = lane - sub * a.segz;
+        constexpr int ITS = 8 * NCH;             // Kc / 64 fetches at most
+        // every entry slot of the workgroup's segments, whatever the counts will say: one memory round trip for
+        // counts and entries together (slots past a segment's count hold stale entries and are dropped below)
+        int2 ent[ITS];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        if (k0 + c * kG1Chunk < kend) {  // wave-uniform
-            const int kb = k0 + c * kG1Chunk + 8 * lane;
-            const int nvalid = kend - kb;  // elements j < nvalid of this lane exist
-            const uint32_t wd[4] = {xv[c].x, xv[c].y, xv[c].z, xv[c].w};
-            float xf[8];
-            if (a.xdt == kBF16) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) xf[j] = __uint_as_float((j & 1) ? (wd[j >> 1] & 0xFFFF0000u) : (wd[j >> 1] << 16));
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) xf[j] = f16_bits_to_f32((j & 1) ? (wd[j >> 1] >> 16) : (wd[j >> 1] & 0xFFFFu));
+        for (int it = 0; it < ITS; ++it) {
+            const int sg = it * per_it + sub;
+            ent[it] = make_int2(0, 0);
+            if (sg < nsegw) {
+                const int64_t e = (int64_t)(seg0 + sg) * a.segz + r;
+                ent[it] = make_int2(a.zl_idx[e], __float_as_int(a.zl_d[e]));
             }
-            uint64_t bal[8];
-            // position of a kept channel in the workgroup's list, and the entries this wavefront owns
-            auto place = [&](int j, float dv) {
-                const int pos = cnt + lanes_below(bal[j]);
-                if (((bal[j] >> lane) & 1) && (pos & (WAVES - 1)) == w) mylist[pos / WAVES] = make_int2(kb + j, __float_as_int(dv));
-                cnt += __popcll(bal[j]);
-            };
-            if (a.mode == kModeSparse) {
+        }
+        int c_l = lane < nsegw ? a.zl_cnt[seg0 + lane] : 0;
+        c_l = min(max(c_l, 0), a.segz);  // keeps LDS writes in range whatever the memory holds
+        const int inc = wave_inclusive_scan(c_l);
+        const int off_l = inc - c_l;
+        cnt = __shfl(inc, kWave - 1, kWave);
+        int pos[ITS];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float dv = xf[j] - a.m;                          // one fp32 subtraction
-                    bal[j] = __ballot(fabsf(dv) > a.tau && j < nvalid);    // strict; NaN is pruned
-                    place(j, dv);
-                }
-            } else {
+        for (int it = 0; it < ITS; ++it) {
+            const int sg = it * per_it + sub;
+            const int c_s = __shfl(c_l, sg & 63, kWave), o_s = __shfl(off_l, sg & 63, kWave);
+            pos[it] = (sg < nsegw && r < c_s) ? o_s + r : -1;
+        }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    bal[j] = __ballot(j < nvalid);  // dense (Eq. 1) and bias folding (Eq. 6): every channel
-                    place(j, a.mode == kModeFold ? a.m : xf[j]);
-                }
+        for (int it = 0; it < ITS; ++it)
+            if (pos[it] >= 0 && (pos[it] & (WAVES - 1)) == w) mylist[pos[it] / WAVES] = ent[it];
+        if (want_lists) {
+            // kept channels of z before this workgroup's: the counts of all earlier segments (ascending lists
+            // need no gap closing here: every workgroup can work out its own offset)
+            int before = 0;
+            for (int s0 = 0; s0 < seg0; s0 += kWave) {
+                const int sg = s0 + lane;
+                before += sg < seg0 ? min(max(a.zl_cnt[sg], 0), a.segz) : 0;
             }
-            if (want_lists) {
-                uint32_t kbits = 0;
+            before = wave_sum(before);
+            if (a.idx_out) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) kbits |= (uint32_t)((bal[j] >> lane) & 1) << j;
-                const int mine = __popc(kbits);
-                const int inc = wave_inclusive_scan(mine);
-                if (a.idx_out) {
-                    int p = k0 + lcnt + inc - mine;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if ((kbits >> j) & 1u) store_dev(&a.idx_out[p++], kb + j);
+                for (int it = 0; it < ITS; ++it)
+                    if (pos[it] >= 0) a.idx_out[before + pos[it]] = ent[it].x;
+            }
+            if (split == a.S - 1 && lane == 0) {
+                if (a.nnz_out) a.nnz_out[0] = before + cnt;
+                if (a.union_nnz_out) a.union_nnz_out[0] = before + cnt;
+            }
+        }
+    } else {
+    #pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (k0 + c * kG1Chunk < kend) {  // wave-uniform
+                const int kb = k0 + c * kG1Chunk + 8 * lane;
+                const int nvalid = kend - kb;  // elements j < nvalid of this lane exist
+                const uint32_t wd[4] = {xv[c].x, xv[c].y, xv[c].z, xv[c].w};
+                float xf[8];
+                if (a.xdt == kBF16) {
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) xf[j] = __uint_as_float((j & 1) ? (wd[j >> 1] & 0xFFFF0000u) : (wd[j >> 1] << 16));
+                } else {
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) xf[j] = f16_bits_to_f32((j & 1) ? (wd[j >> 1] >> 16) : (wd[j >> 1] & 0xFFFFu));
                 }
-                lcnt += __shfl(inc, kWave - 1, kWave);
+                uint64_t bal[8];
+                // position of a kept channel in the workgroup's list, and the entries this wavefront owns
+                auto place = [&](int j, float dv) {
+                    const int pos = cnt + lanes_below(bal[j]);
+                    if (((bal[j] >> lane) & 1) && (pos & (WAVES - 1)) == w) mylist[pos / WAVES] = make_int2(kb + j, __float_as_int(dv));
+                    cnt += __popcll(bal[j]);
+                };
+                if (a.mode == kModeSparse) {
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float dv = xf[j] - a.m;                          // one fp32 subtraction
+                        bal[j] = __ballot(fabsf(dv) > a.tau && j < nvalid);    // strict; NaN is pruned
+                        place(j, dv);
+                    }
+                } else {
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        bal[j] = __ballot(j < nvalid);  // dense (Eq. 1) and bias folding (Eq. 6): every channel
+                        place(j, a.mode == kModeFold ? a.m : xf[j]);
+                    }
+                }
+                if (want_lists) {
+                    uint32_t kbits = 0;
+    #pragma unroll
+                    for (int j = 0; j < 8; ++j) kbits |= (uint32_t)((bal[j] >> lane) & 1) << j;
+                    const int mine = __popc(kbits);
+                    const int inc = wave_inclusive_scan(mine);
+                    if (a.idx_out) {
+                        int p = k0 + lcnt + inc - mine;
+    #pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if ((kbits >> j) & 1u) store_dev(&a.idx_out[p++], kb + j);
+                    }
+                    lcnt += __shfl(inc, kWave - 1, kWave);
+                }
             }
         }
     }
     cnt = uniform(cnt);
-    if (want_lists && lane == 0) {
+    if (FUSE != kFuseList && want_lists && lane == 0) {
         if (a.S == 1) {
             if (a.nnz_out) a.nnz_out[0] = cnt;
             if (a.union_nnz_out) a.union_nnz_out[0] = cnt;
@@ -426,9 +497,56 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
     }
 
     auto finish = [&](const slice_t& s) {
+        float p[CPL];  // finished columns: scaled (int8), fused bias added
 #pragma unroll
-        for (int c = 0; c < CPL; ++c)
-            if (fcol + c < a.N) a.y[fcol + c] = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
+        for (int c = 0; c < CPL; ++c) p[c] = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
+        if constexpr (FUSE != kFuseSwiglu) {
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+                if (fcol + c < a.N) a.y[fcol + c] = p[c];
+        } else {
+            // Columns come in groups of 8: 4 gate pre-activations, then the 4 matching up pre-activations.  The
+            // lanes that hold gate columns fetch their up partners from 4 columns further on, form
+            // z = silu(gate) * up (Alg. 2), centre and threshold it like any layer input (Alg. 3 steps 1-2, strict
+            // compare of Eq. 2) and leave the slice's kept channels, compacted and ascending, as one list segment.
+            constexpr int LPG = 8 / CPL;  // lanes per group of 8 columns
+            const bool gate_lane = (lane % LPG) < LPG / 2;
+            float dz[CPL];
+            bool keep[CPL];
+            int chan[CPL];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const float up = __shfl_down(p[c], LPG / 2, kWave);
+                const int col = fcol + c;
+                chan[c] = (col >> 3) * 4 + (col & 3);
+                const bool live = gate_lane && col < a.N && chan[c] < a.F;
+                const float z = p[c] / (1.f + expf(-p[c])) * up;
+                if (live && a.z_out) a.z_out[chan[c]] = z;
+                dz[c] = z - a.m2;  // one fp32 subtraction
+                keep[c] = live && fabsf(dz[c]) > a.tau2;  // strict; NaN is pruned
+            }
+            const int seg = tile * WAVES + w;  // this slice's segment: SLICE / 2 channels from seg * (SLICE / 2) on
+            if ((int64_t)seg * (SLICE / 2) < a.F) {
+                int rank = 0, total_kept = 0;
+                uint64_t bal[CPL];
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    bal[c] = __ballot(keep[c]);
+                    rank += lanes_below(bal[c]);
+                    total_kept += __popcll(bal[c]);
+                }
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    if (keep[c]) {
+                        const int64_t e = (int64_t)seg * (SLICE / 2) + rank;
+                        a.zl_idx[e] = chan[c];
+                        a.zl_d[e] = dz[c];
+                        ++rank;  // the lane's own earlier column comes first
+                    }
+                }
+                if (lane == 0) a.zl_cnt[seg] = total_kept;
+            }
+        }
     };
     if (a.S == 1) {
         finish(sum);
@@ -476,7 +594,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
     }
     finish(total);
     if (lane == 0) store_dev(ticket, 0ull);  // ready for the next call
-    if (want_lists) close_lists_wave(a, s_off, s_cnt);
+    if (FUSE == kFusePlain && want_lists) close_lists_wave(a, s_off, s_cnt);
 }
 
 // ---------------------------------------------------------------------------------------------- launch
@@ -486,25 +604,24 @@ inline size_t gemv1_lds_bytes(int tile_cols, int Kc, int waves) {
 
 #define G1_ARGS                                                                                                    \
     a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, a.mode, a.xdt, a.flags, a.m, a.tau, a.bias, a.y, a.partial, a.counters, \
-        a.col_scale, a.idx_out, a.nnz_out, a.union_nnz_out, a.seg_cnt
-template <int WDT, int WAVES, int UNROLL>
+        a.col_scale, a.idx_out, a.nnz_out, a.union_nnz_out, a.seg_cnt, a.m2, a.tau2, a.z_out, a.zl_idx, a.zl_d,  \
+        a.zl_cnt, a.F, a.segz
+template <int WDT, int WAVES, int UNROLL, int FUSE = kFusePlain>
 static int launch_gemv1_nch(const Gemv1Args& a, hipStream_t stream) {
     constexpr int TILE = kWave * Vec<WDT>::kElems;
     const size_t lds = gemv1_lds_bytes(TILE, a.Kc, WAVES);
     if (lds > 64 * 1024) return SCAP_ERR_CONFIG;
     const dim3 grid((unsigned)(a.S * a.T)), block(WAVES * kWave);
     if (a.Kc <= kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 1>), grid, block, lds, stream, G1_ARGS);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 1, FUSE>), grid, block, lds, stream, G1_ARGS);
     else if (a.Kc <= 2 * kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 2>), grid, block, lds, stream, G1_ARGS);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 2, FUSE>), grid, block, lds, stream, G1_ARGS);
     else if (a.Kc <= 4 * kG1Chunk)
-        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 4>), grid, block, lds, stream, G1_ARGS);
+        hipLaunchKernelGGL((gemv1_kernel<WDT, WAVES, UNROLL, 4, FUSE>), grid, block, lds, stream, G1_ARGS);
     else
         return SCAP_ERR_CONFIG;
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
-#undef G1_ARGS
-
 template <int WDT, int WAVES>
 static int launch_gemv1_unroll(const Gemv1Args& a, int unroll, hipStream_t stream) {
     switch (unroll) {
@@ -521,5 +638,13 @@ int launch_gemv1_wdt(const Gemv1Args& a, int waves, int unroll, hipStream_t stre
     if (waves == 4) return launch_gemv1_unroll<WDT, 4>(a, unroll, stream);
     return SCAP_ERR_CONFIG;
 }
+
+// the two launches of the fused block: default shape only (8 wavefronts, 4 x 1 KB or 8 x 512 bytes in flight)
+template <int WDT, int FUSE>
+int launch_gemv1_block(const Gemv1Args& a, hipStream_t stream) {
+    return launch_gemv1_nch<WDT, 8, WDT == kI8Half ? 8 : 4, FUSE>(a, stream);
+}
+
+#undef G1_ARGS
 
 }  // namespace scap

@@ -3,4 +3,6 @@
 
 namespace scap {
 template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, int, hipStream_t);
+template int launch_gemv1_block<kBF16, kFuseSwiglu>(const Gemv1Args&, hipStream_t);
+template int launch_gemv1_block<kBF16, kFuseList>(const Gemv1Args&, hipStream_t);
 }  // namespace scap

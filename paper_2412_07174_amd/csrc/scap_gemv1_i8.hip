@@ -4,4 +4,8 @@
 namespace scap {
 template int launch_gemv1_wdt<kI8>(const Gemv1Args&, int, int, hipStream_t);
 template int launch_gemv1_wdt<kI8Half>(const Gemv1Args&, int, int, hipStream_t);
+template int launch_gemv1_block<kI8, kFuseSwiglu>(const Gemv1Args&, hipStream_t);
+template int launch_gemv1_block<kI8, kFuseList>(const Gemv1Args&, hipStream_t);
+template int launch_gemv1_block<kI8Half, kFuseSwiglu>(const Gemv1Args&, hipStream_t);
+template int launch_gemv1_block<kI8Half, kFuseList>(const Gemv1Args&, hipStream_t);
 }  // namespace scap

@@ -89,6 +89,8 @@ int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStrea
 // workgroup would own more channels than that kernel tests per wavefront: the caller takes launch_gemv's kernel.
 constexpr int kG1NotApplicable = 1;
 int launch_gemv1(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+// The fused block of one token on the same kernel (two launches); kG1NotApplicable likewise.
+int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
 
 // Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
 // `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.

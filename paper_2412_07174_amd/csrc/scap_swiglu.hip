@@ -76,6 +76,10 @@ int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipSt
     // Matrix cores: more than 4 tokens, and int8 from 3 tokens on, where the vector kernel is bound by its
     // per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
     // 3-4 tokens, so the choice only has to be the same for both launches.
+    if (up.B == 1) {  // one token: the one-token kernel with the gating epilogue / the list prologue
+        const int rc = launch_swiglu_block1(up, down, wdt, stream);
+        if (rc != kG1NotApplicable) return rc;
+    }
     const bool matrix = up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3);
     if (matrix) {
         const int rc = launch_swiglu_block_inline(up, down, wdt, stream);
