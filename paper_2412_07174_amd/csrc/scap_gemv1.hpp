@@ -502,8 +502,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
         for (int c = 0; c < CPL; ++c) p[c] = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
         if constexpr (FUSE != kFuseSwiglu) {
 #pragma unroll
-            for (int c = 0; c < CPL; ++c)
-                if (fcol + c < a.N) a.y[fcol + c] = p[c];
+            for (int c = 0; c < CPL; ++c)  // written through: lines left modified in L2 are paid for when the kernel ends
+                if (fcol + c < a.N) store_dev(&a.y[fcol + c], p[c]);
         } else {
             // Columns come in groups of 8: 4 gate pre-activations, then the 4 matching up pre-activations.  The
             // lanes that hold gate columns fetch their up partners from 4 columns further on, form
@@ -521,7 +521,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 chan[c] = (col >> 3) * 4 + (col & 3);
                 const bool live = gate_lane && col < a.N && chan[c] < a.F;
                 const float z = p[c] / (1.f + expf(-p[c])) * up;
-                if (live && a.z_out) a.z_out[chan[c]] = z;
+                if (live && a.z_out) store_dev(&a.z_out[chan[c]], z);
                 dz[c] = z - a.m2;  // one fp32 subtraction
                 keep[c] = live && fabsf(dz[c]) > a.tau2;  // strict; NaN is pruned
             }
@@ -539,12 +539,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 for (int c = 0; c < CPL; ++c) {
                     if (keep[c]) {
                         const int64_t e = (int64_t)seg * (SLICE / 2) + rank;
-                        a.zl_idx[e] = chan[c];
-                        a.zl_d[e] = dz[c];
+                        store_dev(&a.zl_idx[e], chan[c]);
+                        store_dev(&a.zl_d[e], dz[c]);
                         ++rank;  // the lane's own earlier column comes first
                     }
                 }
-                if (lane == 0) a.zl_cnt[seg] = total_kept;
+                if (lane == 0) store_dev(&a.zl_cnt[seg], total_kept);
             }
         }
     };

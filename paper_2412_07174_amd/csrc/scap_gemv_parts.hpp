@@ -610,7 +610,8 @@ __device__ __forceinline__ void finish_columns(const GemvArgs& a, int tile, int 
     if constexpr (FUSE == kFuseSwiglu)
         *reinterpret_cast<float4*>(s_fin + b * TILE + 4 * g) = s;
     else
-        *reinterpret_cast<float4*>(a.y + (int64_t)b * a.N + col) = s;
+        // written through to memory: lines left modified in L2 are paid for when the kernel ends
+        store_coherent16(make_raw_buffer(a.y, (uint32_t)((size_t)a.B * a.N * 4)), (uint32_t)(((int64_t)b * a.N + col) * 4), s);
 }
 
 // split-K partials of one call: [B][S][T][TILE] floats, addressed by byte offset
