@@ -99,6 +99,15 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
         return rc == SCAP_ERR_SHAPE ? SCAP_ERR_CONFIG : rc;
     }
     if (lanes == 1) return launch_gemm_mfma(a, wdt, cfg, stream);
+    // 2 tokens: the two-token form of the one-token kernel, unless the caller asks for a launch shape or the
+    // general kernels.  Measured against them (dense / 90 % sparse, us): 14336 x 4096 bf16 23.95 / 10.45 against
+    // 24.36 / 10.94, int8 15.82 / 9.51 against 17.60 / 10.60, 4096 x 4096 bf16 11.78 / 7.76 against 12.82 / 7.59; but
+    // 4096 x 14336 bf16 23.26 / 10.20 against 23.01 / 9.97: not for wide layers of 16-bit weights.
+    if (a.B == 2 && lanes == 0 && (wdt == kI8 || a.N <= 8192) &&
+        !(cfg && ((cfg->flags & SCAP_CFG_GENERAL_KERNEL) || cfg->waves_per_group || cfg->rows_per_group || cfg->unroll))) {
+        const int rc = launch_gemv1b(a, wdt, cfg ? cfg->flags : 0, stream);
+        if (rc != kG1NotApplicable) return rc;
+    }
     // 3-4 tokens in the 16-slot staged-tile kernel: faster than the 4-slot forms for int8 weights unless the layer
     // is very wide (its narrow tiles repeat the prologue), and than the vector kernel for a long input into a
     // narrow bf16 layer (14336 x 4096, 4 tokens: 28.7 -> 27.3 us dense, 22.2 -> 20.0 at 90 %).

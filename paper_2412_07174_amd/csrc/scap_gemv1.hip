@@ -1,5 +1,5 @@
 // Launch of the one-token GEMV kernel (scap_gemv1.hpp): K split, argument block, dispatch by weight type.
-#include "scap_gemv1.hpp"
+#include "scap_gemv1b.hpp"
 
 namespace scap {
 
@@ -7,6 +7,10 @@ extern template int launch_gemv1_wdt<kF16>(const Gemv1Args&, int, int, hipStream
 extern template int launch_gemv1_wdt<kBF16>(const Gemv1Args&, int, int, hipStream_t);
 extern template int launch_gemv1_wdt<kI8>(const Gemv1Args&, int, int, hipStream_t);
 extern template int launch_gemv1_wdt<kI8Half>(const Gemv1Args&, int, int, hipStream_t);
+extern template int launch_gemv1b_wdt<kF16>(const Gemv1bArgs&, hipStream_t);
+extern template int launch_gemv1b_wdt<kBF16>(const Gemv1bArgs&, hipStream_t);
+extern template int launch_gemv1b_wdt<kI8>(const Gemv1bArgs&, hipStream_t);
+extern template int launch_gemv1b_wdt<kI8Half>(const Gemv1bArgs&, hipStream_t);
 #define SCAP_G1_BLOCK_EXTERN(WD)                                                             \
     extern template int launch_gemv1_block<WD, kFuseSwiglu>(const Gemv1Args&, hipStream_t); \
     extern template int launch_gemv1_block<WD, kFuseList>(const Gemv1Args&, hipStream_t);
@@ -27,21 +31,25 @@ struct Plan1 {
 };
 
 // K split and lane width of one launch.  SCAP_OK, kG1NotApplicable or a scap_status.
-int plan_gemv1(const GemvArgs& g, int wdt, int kc, bool kc_forced, int waves, int granule_min, Plan1* out) {
+// bt = token slots: 1 (one-token kernel) or 2 (its two-token form, 8 wavefronts).
+int plan_gemv1(const GemvArgs& g, int wdt, int kc, bool kc_forced, int waves, int granule_min, int bt, Plan1* out) {
     // int8 weights: 16 bytes per lane (1024-column tiles) unless that leaves at most 4 tiles -- then 8 bytes per
     // lane, twice the tiles and half the K splits (14336 x 4096 int8: 15.9 -> 14.2 us dense)
     out->i8_half = wdt == kI8 && g.N <= 4 * 1024;
     out->elems = wdt == kI8 && !out->i8_half ? 16 : 8;
     out->tile = kWave * out->elems;
     GemvArgs p = g;
-    // LDS: header, the wavefronts' sums, then 8 bytes per listed channel
-    const size_t lds_budget = 64 * 1024 - (size_t)waves * out->tile * 4 - 64 + (kHdrBytes - kG1HdrBytes);
+    // LDS: header, the wavefronts' sums, then 8 bytes per listed channel (16 with 2 token slots)
+    const int entry = bt == 1 ? 8 : 16;
+    const size_t lds_budget = bt == 1 ? 64 * 1024 - (size_t)waves * out->tile * 4 - 64 + (kHdrBytes - kG1HdrBytes)
+                                      : (size_t)kG1bMaxLds - (size_t)bt * kG1HdrBytes - (size_t)kG1bWaves * bt * out->tile * 4 -
+                                            (size_t)kG1bWaves * 4 * entry + kHdrBytes;
     // Rows per workgroup in multiples of 64, unless the input is so short that 64-row pieces would leave compute
     // units without a workgroup (1024 x 4096: 16 splits x 8 tiles; with 32-row pieces 8.5 -> 6.5 us dense)
     p.T = (p.N + out->tile - 1) / out->tile;
     int granule = ((int64_t)((p.K + kWave - 1) / kWave) * p.T < 256) ? 8 : kWave;
     if (granule < granule_min) granule = granule_min;
-    const int rc = plan_splits(p, out->tile, 1, kc, kc_forced, lds_budget, granule);
+    const int rc = plan_splits(p, out->tile, entry / 4 - 1, kc, kc_forced, lds_budget, granule);
     if (rc != SCAP_OK) return rc == SCAP_ERR_SHAPE ? kG1NotApplicable : rc;
     if (p.Kc > kG1MaxChunks * kG1Chunk) return kG1NotApplicable;
     out->Kc = p.Kc;
@@ -93,7 +101,7 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
         if (kc > kG1MaxChunks * kG1Chunk) return kG1NotApplicable;
     }
     Plan1 pl;
-    const int rc = plan_gemv1(g, wdt, kc, cfg && cfg->rows_per_group, waves, 8, &pl);
+    const int rc = plan_gemv1(g, wdt, kc, cfg && cfg->rows_per_group, waves, 8, 1, &pl);
     if (rc != SCAP_OK) return rc;
     // rows in flight per wavefront: 4 x 1 KB (16-byte lanes), 8 x 512 bytes (8-byte lanes)
     if (unroll == 0) unroll = pl.i8_half ? 8 : 4;
@@ -102,6 +110,26 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
         case kF16: return launch_gemv1_wdt<kF16>(a, waves, unroll, stream);
         case kBF16: return launch_gemv1_wdt<kBF16>(a, waves, unroll, stream);
         case kI8: return pl.i8_half ? launch_gemv1_wdt<kI8Half>(a, waves, unroll, stream) : launch_gemv1_wdt<kI8>(a, waves, unroll, stream);
+    }
+    return SCAP_ERR_DTYPE;
+}
+
+// Two tokens through the two-token form of the one-token kernel (sparse or dense mode).  Returns a scap_status, or
+// kG1NotApplicable: another token count, bias folding, an input length that is not a multiple of 8 (the second
+// token's row would not be 16-byte aligned) or more than 2048 channels per workgroup.  flags as for launch_gemv1.
+int launch_gemv1b(const GemvArgs& g, int wdt, int flags, hipStream_t stream) {
+    if (g.B != 2 || g.mode == kModeFold || (g.K % 8) != 0) return kG1NotApplicable;
+    Gemv1bArgs b;
+    b.B = g.B;
+    b.bt = 2;
+    Plan1 pl;
+    const int rc = plan_gemv1(g, wdt, 0, false, kG1bWaves, 8, b.bt, &pl);
+    if (rc != SCAP_OK) return rc;
+    b.a = args_of(g, pl, flags);
+    switch (wdt) {
+        case kF16: return launch_gemv1b_wdt<kF16>(b, stream);
+        case kBF16: return launch_gemv1b_wdt<kBF16>(b, stream);
+        case kI8: return pl.i8_half ? launch_gemv1b_wdt<kI8Half>(b, stream) : launch_gemv1b_wdt<kI8>(b, stream);
     }
     return SCAP_ERR_DTYPE;
 }
@@ -122,9 +150,9 @@ static int launch_block_half(const Gemv1Args& a, int wdt, bool i8_half, hipStrea
 int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, hipStream_t stream) {
     if (up.B != 1) return kG1NotApplicable;
     Plan1 pu, pd;
-    int rc = plan_gemv1(up, wdt, 0, false, 8, kWave, &pu);
+    int rc = plan_gemv1(up, wdt, 0, false, 8, kWave, 1, &pu);
     if (rc != SCAP_OK) return rc;
-    rc = plan_gemv1(dn, wdt, 0, false, 8, kWave, &pd);  // whole 64-channel pieces: whole list segments
+    rc = plan_gemv1(dn, wdt, 0, false, 8, kWave, 1, &pd);  // whole 64-channel pieces: whole list segments
     if (rc != SCAP_OK) return rc;
     const int segz = pu.tile / 8 / 2;  // gated channels a wavefront slice of the gate|up launch finishes: 32 or 64
     if (pd.Kc % segz != 0 || pd.Kc / segz > kWave) return kG1NotApplicable;

@@ -185,41 +185,38 @@ template <> struct SliceVec<4> {
 // exclusive prefix sum across the 64 lanes of a wave
 __device__ __forceinline__ int wave_exclusive_scan(int v) { return wave_inclusive_scan(v) - v; }
 
-// Last arrival of (tile 0, slice 0): every split's ascending list sits at idx_out[split*Kc ...] with its count in
-// seg_cnt; write the total and close the gaps.  One wavefront; entries only move left, and a block of source
+// Close the gaps of one token's list: every split's ascending list sits at idx[split*Kc ...] with its count in
+// seg_cnt[split].  Returns the total (in every lane).  One wavefront; entries only move left, and a block of source
 // positions is read completely before any of it is written, so nothing is overwritten before it has been read.
-__device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off, int* s_cnt) {
+__device__ __forceinline__ int close_list_rows(const int32_t* seg_cnt, int32_t* idx, int S, int K, int Kc, int* s_off,
+                                               int* s_cnt) {
     const int lane = lane_id();
     int run = 0;
-    for (int s0 = 0; s0 < a.S; s0 += kWave) {
+    for (int s0 = 0; s0 < S; s0 += kWave) {
         const int sp = s0 + lane;
-        const int v = sp < a.S ? load_dev(&a.seg_cnt[sp]) : 0;
+        const int v = sp < S ? load_dev(&seg_cnt[sp]) : 0;
         const int inc = wave_inclusive_scan(v);
-        if (sp < a.S) {
+        if (sp < S) {
             s_off[sp] = run + inc - v;
             s_cnt[sp] = v;
         }
         run += __shfl(inc, kWave - 1, kWave);
     }
-    if (lane == 0) {
-        if (a.nnz_out) a.nnz_out[0] = run;
-        if (a.union_nnz_out) a.union_nnz_out[0] = run;
-    }
-    if (a.idx_out == nullptr || a.S == 1) return;
+    if (idx == nullptr || S == 1) return run;
     __builtin_amdgcn_wave_barrier();
     constexpr int PER = 16;
-    for (int c0 = 0; c0 < a.K; c0 += kWave * PER) {
+    for (int c0 = 0; c0 < K; c0 += kWave * PER) {
         int vals[PER], dsts[PER];
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
             const int p = c0 + j * kWave + lane;
             dsts[j] = -1;
             vals[j] = 0;
-            if (p < a.K) {
-                const int seg = p / a.Kc;
-                const int r = p - seg * a.Kc;
+            if (p < K) {
+                const int seg = p / Kc;
+                const int r = p - seg * Kc;
                 if (r < s_cnt[seg]) {
-                    vals[j] = load_dev(&a.idx_out[p]);
+                    vals[j] = load_dev(&idx[p]);
                     dsts[j] = s_off[seg] + r;
                 }
             }
@@ -227,8 +224,18 @@ __device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off,
         wait_memory_ops();
 #pragma unroll
         for (int j = 0; j < PER; ++j)
-            if (dsts[j] >= 0) a.idx_out[dsts[j]] = vals[j];
+            if (dsts[j] >= 0) store_dev(&idx[dsts[j]], vals[j]);
         wait_memory_ops();
+    }
+    return run;
+}
+
+// Last arrival of (tile 0, slice 0) of the one-token kernel: write the total and close the gaps.
+__device__ __forceinline__ void close_lists_wave(const Gemv1Args& a, int* s_off, int* s_cnt) {
+    const int run = close_list_rows(a.seg_cnt, a.idx_out, a.S, a.K, a.Kc, s_off, s_cnt);
+    if (lane_id() == 0) {
+        if (a.nnz_out) a.nnz_out[0] = run;
+        if (a.union_nnz_out) a.union_nnz_out[0] = run;
     }
 }
 

@@ -89,6 +89,9 @@ int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStrea
 // workgroup would own more channels than that kernel tests per wavefront: the caller takes launch_gemv's kernel.
 constexpr int kG1NotApplicable = 1;
 int launch_gemv1(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
+// Two tokens through that kernel's two-token form; kG1NotApplicable likewise (also for another token count, bias
+// folding and an input length that is not a multiple of 8).
+int launch_gemv1b(const GemvArgs& a, int wdt, int flags, hipStream_t stream);
 // The fused block of one token on the same kernel (two launches); kG1NotApplicable likewise.
 int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
 

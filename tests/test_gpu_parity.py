@@ -100,6 +100,47 @@ def test_one_token_kernel_shapes_and_both_hand_overs(K, N, dt, rows):
                              what=f"general kernel K={K} N={N} tau={tau}")
 
 
+FEW_TOKENS = [
+    # K (a multiple of 8), N, dtype: one / two / four 512-channel chunks per wavefront, ragged last chunk, column
+    # tiles that are not a multiple of the 8 accelerator dies, ragged last column tile, a single K split,
+    # int8 weights with 8 and 16 bytes per lane
+    (4096, 1544, BF16), (5000, 6144, BF16), (2048, 11008, F16), (776, 4096, F16), (336, 8, BF16), (64, 520, BF16),
+    (6000, 2064, I8), (3000, 5136, I8), (14336, 4096, BF16),
+]
+
+
+@pytest.mark.parametrize("B", [2, 3, 4])
+@pytest.mark.parametrize("K,N,dt", FEW_TOKENS)
+def test_few_tokens_kernel_shapes_and_both_hand_overs(K, N, dt, B):
+    """2 tokens on the two-token form of the one-token kernel (the library's choice when the input length is a
+    multiple of 8 and the layer is not a wide one of 16-bit weights), 3 and 4 tokens on whatever the library picks
+    for these shapes: against the oracle token by token -- y, every token's list and count, the union count --,
+    with ordinary and with device-coherent loads of the partial sums against each other bit for bit, and dense
+    mode, on repeated calls with changing inputs through one workspace."""
+    if dt == I8:
+        Wq, sc = wl.quantize_i8(K, N, 351 + K)
+        layer = Layer(Wq, I8, col_scale_bits=sc, B=4)
+        xdt = BF16
+    else:
+        layer = Layer(wl.weights(K, N, 351 + K, dt), dt, B=4)
+        xdt = dt
+    X = wl.laplace(6 * B, K, 352 + K + B, xdt, loc=0.1, scale=0.5)
+    bf = np.random.default_rng(K + N).standard_normal(N).astype(np.float32)
+    for rep, tau in enumerate((0.0, 0.3, 0.35, 0.9, 2.5, 1e6)):
+        x = X[rep * B:(rep + 1) * B]
+        say(f"few tokens K={K} N={N} dt={dt} B={B} tau={tau}")
+        near, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, what=f"few tokens K={K} N={N} B={B} tau={tau}")
+        far = gpu_sparse_fc(layer, x, xdt, 0.1, tau, bf, cfg=(0, 0, 0, 0, scap.CFG_DEVICE_SCOPE_LOADS))
+        assert np.array_equal(near["y"].view(np.uint32), far["y"].view(np.uint32)), "hand-over paths differ"
+        for b in range(B):
+            assert np.array_equal(near["idx"][b], far["idx"][b])
+    say(f"few tokens K={K} N={N} dt={dt} B={B} dense")
+    y = scap.dense_fc(layer.W, to_dev(X[:B], xdt), f32_dev(bf), col_scale=layer.scale, workspace=layer.ws)
+    torch.cuda.synchronize()
+    want = oracle.dense_fc(layer.W_host, X[:B], bf, dt, xdt, col_scale=layer.scale_host)
+    assert_y_close(y.cpu().numpy(), want, "dense, few tokens")
+
+
 def test_one_token_kernel_many_calls_in_a_row_both_hand_overs():
     """Back-to-back launches on one workspace with rotating weights and inputs (what the benchmark does): the
     ordinary-load hand-over must never see a partial sum of an earlier launch.  Every y is compared bit for bit
