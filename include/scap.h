@@ -86,8 +86,8 @@ typedef struct {
     int32_t flags;           /* bit 0 (SCAP_CFG_DEVICE_SCOPE_LOADS): the one-token kernel fetches split-K partial sums
                                 with device-coherent loads even when all their writers ran on the reader's own
                                 accelerator die (results are identical; for tests and measurements);
-                                bit 1 (SCAP_CFG_GENERAL_KERNEL): one token through the general vector kernel
-                                instead of the one-token kernel */
+                                bit 1 (SCAP_CFG_GENERAL_KERNEL): one or two tokens through the general kernels
+                                instead of the one-token kernel and its two-token form */
 } scap_launch_cfg;
 #define SCAP_CFG_DEVICE_SCOPE_LOADS 1
 #define SCAP_CFG_GENERAL_KERNEL 2
