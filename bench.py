@@ -551,11 +551,12 @@ def main() -> int:
         torch.cuda.synchronize()
         return nnz_buf.cpu().numpy().astype(np.float64)
 
-    def launcher(s):
+    def launcher(s, use_cfg="default"):
+        c = cfg if use_cfg == "default" else use_cfg
         if s is None:
-            return lambda i: scap.dense_fc(Ws[i % R], xin(i), None, y=y, workspace=ws, cfg=cfg)
+            return lambda i: scap.dense_fc(Ws[i % R], xin(i), None, y=y, workspace=ws, cfg=c)
         m, tau, bf = layer[s]
-        return lambda i: scap.sparse_fc(Ws[i % R], xin(i), m, tau, bf, y=y, workspace=ws, cfg=cfg)
+        return lambda i: scap.sparse_fc(Ws[i % R], xin(i), m, tau, bf, y=y, workspace=ws, cfg=c)
 
     if args.counter_pass:
         # reference for scaling the byte counters: torch copies W (reads and writes wbytes_total each)
@@ -623,6 +624,14 @@ def main() -> int:
             sweep.append({"target_sparsity": s, "density": round(nn / K, 4), "us": round(e_ms * 1e3, 3),
                           "GBps": round(ab / (e_ms * 1e-3) / 1e9, 1),
                           "frac_of_8TBps": round(ab / (e_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+            if B == 1 and not args.cfg:
+                # the opt-in y += result mode (fp32 atomic adds instead of the split-K hand-over; the order of the
+                # additions is not fixed): another operation than the headline's y = result, reported beside it
+                y_keep = y.clone()
+                w_ms, a_ms = time_steps(launcher(s, (0, 0, 0, 0, scap.CFG_ACCUMULATE)), sub_steps, 50)
+                y.copy_(y_keep)
+                sweep[-1]["accumulate_mode_us"] = round(a_ms * 1e3, 3)
+                sweep[-1]["accumulate_mode_frac_of_8TBps"] = round(ab / (a_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         # one launch on its own: event pair around a single eager launch of the headline call, GPU idle before
         fn = launcher(s_head)
         lat = []

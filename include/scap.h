@@ -87,10 +87,18 @@ typedef struct {
                                 with device-coherent loads even when all their writers ran on the reader's own
                                 accelerator die (results are identical; for tests and measurements);
                                 bit 1 (SCAP_CFG_GENERAL_KERNEL): one or two tokens through the general kernels
-                                instead of the one-token kernel and its two-token form */
+                                instead of the one-token kernel and its two-token form;
+                                bit 2 (SCAP_CFG_ACCUMULATE): NOT a tuning knob -- y += result instead of y = result.
+                                y must hold the addend (a residual stream, say) when the call is enqueued; every
+                                workgroup adds its share with fp32 atomic adds, which removes the split-K hand-over
+                                (about 1.5 us of a one-token launch) and with it the fixed order of the additions:
+                                the last bits of y may differ from run to run.  One token through the one-token
+                                kernel only (sparse or dense mode); SCAP_ERR_CONFIG where that kernel does not
+                                apply.  idx_out / nnz_out are exact as always */
 } scap_launch_cfg;
 #define SCAP_CFG_DEVICE_SCOPE_LOADS 1
 #define SCAP_CFG_GENERAL_KERNEL 2
+#define SCAP_CFG_ACCUMULATE 4
 
 /* Static, NUL-terminated description of a status code.  Never freed. */
 const char* scap_status_string(int status);

@@ -83,6 +83,17 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     while (bt < a.B) bt <<= 1;
     if (bt > SCAP_MAX_TOKENS) return SCAP_ERR_SHAPE;
 
+    // y += result: a property of the one-token kernel alone.  Anything that would take another kernel is refused
+    // rather than run with the wrong meaning.
+    if (cfg && (cfg->flags & SCAP_CFG_ACCUMULATE)) {
+        if (a.B != 1 || a.mode == kModeFold || (cfg->flags & SCAP_CFG_GENERAL_KERNEL) ||
+            (cfg->waves_per_group && cfg->waves_per_group != 8 && cfg->waves_per_group != 4) ||
+            (cfg->lanes_per_row && cfg->lanes_per_row != 64))
+            return SCAP_ERR_CONFIG;
+        const int rc = launch_gemv1(a, wdt, cfg, stream);
+        return rc == kG1NotApplicable ? SCAP_ERR_CONFIG : rc;
+    }
+
     // Several tokens: the gathered rows form a dense sub-GEMM -> matrix cores (bf16 and int8 weights from 2
     // tokens; fp16 weights from 5, on the single-launch kernel only).
     // lanes_per_row = 16 asks for the single-launch matrix-core kernel (its lane layout), 1 for the

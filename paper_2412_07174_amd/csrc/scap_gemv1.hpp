@@ -40,6 +40,7 @@ constexpr int kG1HdrBytes = 2048;    // offsets and counts of up to 256 splits (
 constexpr int kG1TicketWords = 32;   // int32 words between the tickets of a tile's slices (128 bytes)
 
 constexpr int kG1FlagDeviceScope = 1;  // always fetch the partials with device-coherent loads
+constexpr int kG1FlagAccumulate = 4;   // y += result: every workgroup adds its share to y with fp32 atomics
 
 // int8 weights read 8 bytes per lane instead of 16 (internal to this kernel): the column tile is 512 columns
 // instead of 1024, so a layer with few columns gets twice the tiles and half the K splits.  With 4096 columns
@@ -555,6 +556,29 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
             }
         }
     };
+    if constexpr (FUSE != kFuseSwiglu) {
+        if (a.flags & kG1FlagAccumulate) {
+            // y already holds what the result is to be added to (a residual stream, say).  Every workgroup adds its
+            // share of the slice with device-scope fp32 atomic adds and is done: no partial sums, no ticket, no
+            // last arrival -- and no fixed order of the additions, so the last bits of y differ from run to run.
+            // The workgroups of split 0 bring the fused bias (Eq. 6).
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const float p = (IS_I8 ? sum.v[c] * cscale[c] : sum.v[c]) + (split == 0 ? cbias[c] : 0.f);
+                if (fcol + c < a.N) __hip_atomic_fetch_add(&a.y[fcol + c], p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (FUSE != kFusePlain || !want_lists || a.S == 1) return;
+            // the caller's lists still need the last arrival of (tile 0, slice 0) to close their gaps
+            wait_memory_ops();
+            unsigned long long* lt = reinterpret_cast<unsigned long long*>(a.counters);
+            unsigned long long got = 0;
+            if (lane == 0) got = __hip_atomic_fetch_add(lt, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull;
+            if (__builtin_amdgcn_readfirstlane((int)(uint32_t)got) != a.S) return;
+            if (lane == 0) store_dev(lt, 0ull);
+            close_lists_wave(a, s_off, s_cnt);
+            return;
+        }
+    }
     if (a.S == 1) {
         finish(sum);
         return;

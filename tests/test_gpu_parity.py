@@ -100,6 +100,48 @@ def test_one_token_kernel_shapes_and_both_hand_overs(K, N, dt, rows):
                              what=f"general kernel K={K} N={N} tau={tau}")
 
 
+@pytest.mark.parametrize("K,N,dt", [(4099, 1544, BF16), (777, 4096, F16), (64, 520, BF16), (6000, 2064, I8), (14336, 4096, BF16)])
+def test_accumulate_into_y(K, N, dt):
+    """The opt-in y += result mode of the one-token kernel (fp32 atomic adds, no split-K hand-over): y starts as a
+    given addend, the result is the oracle's y plus that addend at the float tolerance (the order of the additions
+    is not fixed), lists and counts are exact; dense mode likewise; calls that would need another kernel are refused."""
+    if dt == I8:
+        Wq, sc = wl.quantize_i8(K, N, 361 + K)
+        layer = Layer(Wq, I8, col_scale_bits=sc, B=2)
+        xdt = BF16
+    else:
+        layer = Layer(wl.weights(K, N, 361 + K, dt), dt, B=2)
+        xdt = dt
+    X = wl.laplace(4, K, 362 + K, xdt, loc=0.1, scale=0.5)
+    bf = np.random.default_rng(K + N).standard_normal(N).astype(np.float32)
+    addend = np.random.default_rng(7 * K + N).standard_normal(N).astype(np.float32)
+    cfg = (0, 0, 0, 0, scap.CFG_ACCUMULATE)
+    for rep, tau in enumerate((0.0, 0.3, 0.9, 1e6)):
+        say(f"accumulate K={K} N={N} dt={dt} tau={tau}")
+        want = oracle.sparse_fc(layer.W_host, X[rep], 0.1, tau, bf, dt, xdt, col_scale=layer.scale_host)
+        y = f32_dev(addend).reshape(1, N).clone()
+        idx = torch.full((1, K), -7, dtype=torch.int32, device="cuda")
+        nnz = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        unz = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        scap.sparse_fc(layer.W, to_dev(X[rep], xdt), 0.1, tau, f32_dev(bf), col_scale=layer.scale, y=y, idx_out=idx,
+                       nnz_out=nnz, union_nnz_out=unz, workspace=layer.ws, cfg=cfg)
+        torch.cuda.synchronize()
+        assert int(nnz.item()) == int(want["nnz"][0]) == int(unz.item())
+        assert np.array_equal(idx.cpu().numpy()[0, :int(nnz.item())], want["idx"][0])
+        assert_y_close(y.cpu().numpy()[0], want["y"][0] + addend, f"accumulate tau={tau}")
+    say(f"accumulate K={K} N={N} dt={dt} dense, then an ordinary call on the same workspace")
+    y = f32_dev(addend).reshape(1, N).clone()
+    scap.dense_fc(layer.W, to_dev(X[0], xdt), f32_dev(bf), col_scale=layer.scale, y=y, workspace=layer.ws, cfg=cfg)
+    torch.cuda.synchronize()
+    assert_y_close(y.cpu().numpy()[0], oracle.dense_fc(layer.W_host, X[0], bf, dt, xdt, col_scale=layer.scale_host)[0] + addend, "accumulate dense")
+    check_against_oracle(layer, X[1], xdt, 0.1, 0.3, bf, what="ordinary call after accumulate calls")
+    with pytest.raises(scap.ScapError):
+        scap.sparse_fc(layer.W, to_dev(X[:2], xdt), 0.1, 0.3, None, col_scale=layer.scale, workspace=layer.ws, cfg=cfg)
+    with pytest.raises(scap.ScapError):
+        scap.sparse_fc(layer.W, to_dev(X[0], xdt), 0.1, 0.3, None, col_scale=layer.scale, workspace=layer.ws,
+                       cfg=(0, 0, 0, 0, scap.CFG_ACCUMULATE | scap.CFG_GENERAL_KERNEL))
+
+
 FEW_TOKENS = [
     # K (a multiple of 8), N, dtype: one / two / four 512-channel chunks per wavefront, ragged last chunk, column
     # tiles that are not a multiple of the 8 accelerator dies, ragged last column tile, a single K split,
