@@ -688,8 +688,8 @@ def test_calibrate_every_code_pattern(dt):
 
 def test_hip_graph_replays_match_eager_launches():
     """bench.py times launches replayed from a HIP graph: every replay must give what the eager launch gives.
-    One-token kernel, both matrix-core forms (single launch, union kernel + product kernel), the one-token and the
-    8-token SwiGLU block, replayed several times with eager work and synchronisation in between, on inputs that change
+    One-token kernel (also in its y += result mode), the two-token kernel, both matrix-core forms (single launch, union
+    kernel + product kernel), the one-token and the 8-token SwiGLU block, replayed several times with eager work and synchronisation in between, on inputs that change
     between replays."""
     K, F, N = 1500, 2056, 1032
     W = to_dev(wl.weights(K, N, 971, BF16), BF16)
@@ -707,9 +707,19 @@ def test_hip_graph_replays_match_eager_launches():
     yb8 = torch.zeros((8, N), dtype=torch.float32, device="cuda")
     nnz = torch.zeros(8, dtype=torch.int32, device="cuda")
     two_launch = scap.LaunchCfg(0, 0, 0, 1)
+    K2 = 1504  # a multiple of 8: two tokens run on the two-token kernel
+    W2 = to_dev(wl.weights(K2, N, 976, BF16), BF16)
+    ws2 = scap.Workspace(K2, N, 2)
+    x2 = to_dev(wl.laplace(2, K2, 977, BF16, loc=0.0, scale=1.0), BF16)
+    y2 = torch.zeros((2, N), dtype=torch.float32, device="cuda")
+    nnz2 = torch.zeros(2, dtype=torch.int32, device="cuda")
+    ya = torch.zeros((1, N), dtype=torch.float32, device="cuda")
 
     def work():
         scap.sparse_fc(W, x1, 0.0, 0.5, None, y=y1, workspace=ws)
+        scap.sparse_fc(W2, x2, 0.0, 0.5, None, y=y2, nnz_out=nnz2, workspace=ws2)     # 2 tokens
+        ya.fill_(1.0)
+        scap.sparse_fc(W, x1, 0.0, 0.5, None, y=ya, workspace=ws, cfg=(0, 0, 0, 0, scap.CFG_ACCUMULATE))
         scap.sparse_fc(W, xb, 0.0, 0.5, None, y=y8, nnz_out=nnz, workspace=ws)        # 8 tokens: matrix cores
         scap.sparse_fc(W, xb, 0.0, 0.5, None, y=y8l, workspace=ws, cfg=two_launch)
         scap.swiglu_block(W_gu, Wd, x1, 0.0, 0.5, None, 0.0, 0.02, None, y=yb, workspace=ws)
@@ -724,10 +734,13 @@ def test_hip_graph_replays_match_eager_launches():
         say(f"graph replay {rep}")
         x1.copy_(X[(rep + 1) % 8])
         xb.copy_(torch.roll(X, rep + 1, dims=0))
+        x2.copy_(torch.roll(x2, 1, dims=1))
         work()
         torch.cuda.synchronize()
-        outs = (y1, y8, y8l, yb, yb8, nnz)
+        outs = (y1, y8, y8l, yb, yb8, nnz, y2, nnz2)
         want = tuple(t.clone() for t in outs)
+        want_a = ya.clone()
+        assert float((ya - 1.0 - y1).abs().max()) < 1e-4, "y += result differs from 1 + (y = result)"
         assert torch.equal(y8, y8l) or float((y8 - y8l).abs().max()) < 1e-4
         for t in outs:
             t.zero_()
@@ -736,6 +749,7 @@ def test_hip_graph_replays_match_eager_launches():
         torch.cuda.synchronize()
         for a, b in zip(want, outs):
             assert torch.equal(a, b), f"replay {rep} differs from the eager launch"
+        assert float((ya - want_a).abs().max()) < 1e-4  # atomic adds: the order of the additions is not fixed
 
 
 @pytest.mark.parametrize("K,N,B", [(1 << 20, 8, 1), (1 << 20, 16, 3), (64, 1 << 19, 1), (72, 1 << 19, 16), (1 << 20, 136, 8)])
