@@ -274,6 +274,35 @@ def test_ties_nonfinite_and_empty_mask():
     assert np.array_equal(got["y"][0], bf)
 
 
+def test_two_tokens_ties_nonfinite_and_one_empty_mask():
+    """The two-token kernel on the awkward inputs: ties at |d| == tau in one token, NaN and Inf in the other (its
+    Inf row must not leak into the first token, whose value there is finite), then one token with nothing kept
+    beside one with everything kept, then nothing kept at all."""
+    K, N = 256, 64
+    W = wl.weights(K, N, 411, BF16)
+    layer = Layer(W, BF16, B=2)
+    xs = np.random.default_rng(412).choice(np.array([0.5, -0.5, 0.50390625, 0.25, 1.0, -2.0], dtype=np.float32), size=K)
+    xs2 = np.roll(xs, 5).copy()
+    xs2[3], xs2[77] = np.nan, np.inf
+    x = np.stack([wl.encode(xs, BF16), wl.encode(xs2, BF16)])
+    say("two tokens: ties, NaN and Inf")
+    got, want = check_against_oracle(layer, x, BF16, 0.0, 0.5, None, what="two tokens, ties and nonfinite")
+    assert int(want["nnz"][0]) == int((np.abs(xs) > 0.5).sum())
+    assert np.all(np.isfinite(got["y"][0])) and not np.all(np.isfinite(got["y"][1]))
+    say("two tokens: one keeps nothing, one keeps everything")
+    big = np.full(K, 3.0, dtype=np.float32)
+    big[::2] = -3.0
+    x = np.stack([wl.encode(np.zeros(K, dtype=np.float32), BF16), wl.encode(big, BF16)])
+    bf = np.random.default_rng(413).standard_normal(N).astype(np.float32)
+    got, want = check_against_oracle(layer, x, BF16, 0.0, 1.0, bf, what="two tokens, empty and full")
+    assert list(got["nnz"]) == [0, K] and got["union_nnz"] == K
+    assert np.array_equal(got["y"][0], bf)
+    say("two tokens: nothing kept")
+    got = gpu_sparse_fc(layer, x, BF16, 0.0, 100.0, bf)
+    assert list(got["nnz"]) == [0, 0] and got["union_nnz"] == 0
+    assert np.array_equal(got["y"][0], bf) and np.array_equal(got["y"][1], bf)
+
+
 def test_rerun_is_bit_identical_and_workspace_is_reusable():
     site = wl.sites(1)[0]
     W = site.make_weights()
