@@ -345,7 +345,6 @@ def run_suite(args, torch, scap, wl, dev):
         n_side = 4
         side = [torch.cuda.Stream() for _ in range(n_side)]
         side_ws = [scap.Workspace(K, N, 8, F=F) for _ in range(n_side)]
-        side_y = [torch.empty((8, N), dtype=torch.float32, device=dev) for _ in range(n_side)]
         m_x, tau_x = scap.calibrate(calib, 0.4, scap.MODE_MEDIAN, workspace=ws)
         bgu = [scap.fold_bias(Wgu[e], m_x, None, col_scale=sgu[e], workspace=ws) for e in range(E)]
         ygu = torch.empty((8, 2 * F), dtype=torch.float32, device=dev)
@@ -363,52 +362,62 @@ def run_suite(args, torch, scap, wl, dev):
         for B in (1, 8):
             nsteps = max(50, steps // 2)
             order, gatew = wl.top2_route(wl.router_logits(B * nsteps, E, 5004 + B))
+            # Routing as a serving stack does it: the step's (token, expert) pairs are sorted by expert once, the
+            # inputs of all experts are gathered in one go, every expert works on its contiguous slice, and the
+            # gate-weighted outputs are scattered back and added in one go.
             plans = []
             for i in range(nsteps):
-                groups = []
+                groups, src_all, dst_all, gw_all, off = [], [], [], [], 0
                 for e in range(E):
                     tok, slot = np.nonzero(order[i * B:(i + 1) * B] == e)
                     if tok.size:
-                        groups.append((e, torch.from_numpy(tok + (i * B) % (256 - B)).to(dev),
-                                       torch.from_numpy(tok).to(dev),
-                                       torch.from_numpy(gatew[i * B + tok, slot].astype(np.float32)).to(dev)))
-                plans.append(groups)
+                        groups.append((e, off, int(tok.size)))
+                        src_all.append(tok + (i * B) % (256 - B))
+                        dst_all.append(tok)
+                        gw_all.append(gatew[i * B + tok, slot].astype(np.float32))
+                        off += int(tok.size)
+                plans.append((groups, torch.from_numpy(np.concatenate(src_all)).to(dev),
+                              torch.from_numpy(np.concatenate(dst_all)).to(dev),
+                              torch.from_numpy(np.concatenate(gw_all)).to(dev)))
             out = torch.zeros((B, N), dtype=torch.float32, device=dev)
-            ybuf = torch.empty((8, N), dtype=torch.float32, device=dev)
+            ybuf = torch.empty((2 * B, N), dtype=torch.float32, device=dev)  # top-2: two rows per token
+
+            def expert(e, xg, y, sparse, fused, wsx):
+                n = xg.shape[0]
+                if sparse and fused:
+                    scap.swiglu_block(Wgu[e], Wdn[e], xg, m_x, tau_x, bgu[e], 0.0, tau_z, None, gu_scale=sgu[e],
+                                      down_scale=sdn[e], y=y, workspace=wsx)
+                elif sparse:
+                    scap.sparse_fc(Wgu[e], xg, m_x, tau_x, bgu[e], col_scale=sgu[e], y=ygu[:n], workspace=wsx)
+                    scap.sparse_fc(Wdn[e], gate(ygu[:n]), 0.0, tau_z, None, col_scale=sdn[e], y=y, workspace=wsx)
+                else:
+                    scap.dense_fc(Wgu[e], xg, None, col_scale=sgu[e], y=ygu[:n], workspace=wsx)
+                    scap.dense_fc(Wdn[e], gate(ygu[:n]), None, col_scale=sdn[e], y=y, workspace=wsx)
 
             def step(i, sparse, fused):
+                groups, src, dst, gw = plans[i % nsteps]
+                xg = X.index_select(0, src)
+                for e, off, n in groups:
+                    expert(e, xg[off:off + n], ybuf[off:off + n], sparse, fused, wsb if fused else ws)
                 out.zero_()
-                for e, src, dst, gw in plans[i % nsteps]:
-                    n = src.numel()
-                    xg = X.index_select(0, src)
-                    y = ybuf[:n]
-                    if sparse and fused:
-                        scap.swiglu_block(Wgu[e], Wdn[e], xg, m_x, tau_x, bgu[e], 0.0, tau_z, None, gu_scale=sgu[e],
-                                          down_scale=sdn[e], y=y, workspace=wsb)
-                    elif sparse:
-                        scap.sparse_fc(Wgu[e], xg, m_x, tau_x, bgu[e], col_scale=sgu[e], y=ygu[:n], workspace=ws)
-                        scap.sparse_fc(Wdn[e], gate(ygu[:n]), 0.0, tau_z, None, col_scale=sdn[e], y=y, workspace=ws)
-                    else:
-                        scap.dense_fc(Wgu[e], xg, None, col_scale=sgu[e], y=ygu[:n], workspace=ws)
-                        scap.dense_fc(Wdn[e], gate(ygu[:n]), None, col_scale=sdn[e], y=y, workspace=ws)
-                    out.index_add_(0, dst, y * gw[:, None])
+                out.index_add_(0, dst, ybuf[:src.numel()] * gw[:, None])
 
             def step_streams(i):
                 main = torch.cuda.current_stream()
-                out.zero_()
+                groups, src, dst, gw = plans[i % nsteps]
+                xg = X.index_select(0, src)
                 used = []
-                for j, (e, src, dst, gw) in enumerate(plans[i % nsteps]):
+                for j, (e, off, n) in enumerate(groups):
                     k = j % n_side
                     if k not in used:
                         side[k].wait_stream(main)
                         used.append(k)
                     with torch.cuda.stream(side[k]):
-                        y = side_y[k][:src.numel()]
-                        scap.swiglu_block(Wgu[e], Wdn[e], X.index_select(0, src), m_x, tau_x, bgu[e], 0.0, tau_z, None,
-                                          gu_scale=sgu[e], down_scale=sdn[e], y=y, workspace=side_ws[k])
-                        out.index_add_(0, dst, y * gw[:, None])  # atomic adds: two streams may touch one row
+                        expert(e, xg[off:off + n], ybuf[off:off + n], True, True, side_ws[k])
                 for k in used:
                     main.wait_stream(side[k])
+                out.zero_()
+                out.index_add_(0, dst, ybuf[:src.numel()] * gw[:, None])
 
             saved = steps_box[0]
             steps_box[0] = nsteps
@@ -417,7 +426,7 @@ def run_suite(args, torch, scap, wl, dev):
             t_fused = timed(lambda i: step(i, True, True))
             t_streams = timed(step_streams)
             steps_box[0] = saved
-            active = float(np.mean([len(p) for p in plans]))
+            active = float(np.mean([len(p[0]) for p in plans]))
             moe_rows.append({"tokens": B, "experts": E, "top_k": 2, "active_experts_per_step": round(active, 2),
                              "target_x": 0.4, "target_z": 0.7, "dense_us": round(t_dense, 1),
                              "sparse_separate_calls_us": round(t_sep, 1), "sparse_fused_blocks_us": round(t_fused, 1),
