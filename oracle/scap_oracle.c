@@ -40,10 +40,12 @@
  *     the last call of Alg. 2 takes it, not x, as its input;
  *   - int8 weights are symmetric with one fp16 scale per output channel: w = scale[o]*q[i,o].
  *
- * Parity unpinned: the histogram mode estimator (ORACLE_MODE_HIST).  The paper names kernel
- * density estimation but fixes neither bandwidth nor grid, so there is no printed value to
- * pin it to; it is only checked to land within one bin of the closed-form mode of synthetic
- * laws.
+ * Parity unpinned: none.  The histogram mode estimator (ORACLE_MODE_HIST) is pinned, by samples
+ * built by hand on a grid whose bin contents and winning bin are worked out on paper, against
+ * the definition written at hist_mode() below.  That definition is itself a stand-in: the paper
+ * (Section 3, "Determination of mode value") names kernel density estimation but fixes neither
+ * bandwidth nor grid, so there is no printed value of the paper's own estimator to compare with;
+ * the stand-in is also checked to land within one bin of the closed-form mode of synthetic laws.
  */
 #include <math.h>
 #include <stdint.h>
