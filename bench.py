@@ -233,9 +233,16 @@ def run_suite(args, torch, scap, wl, dev):
                 scap.swiglu_block(Wgu[0], Wd[0], X[i], m_x, tau_x, bgu, 0.0, tau_z, None, y=y, nnz_z_out=nz, workspace=ws)
                 dx += nx.item() / K / 8
                 dz += nz.item() / F / 8
+            def fused_residual(i):  # y += block output (another operation: the residual addition taken into the block)
+                scap.swiglu_block(Wgu[i % R], Wd[i % R], X[i % 64], m_x, tau_x, bgu, 0.0, tau_z, None, y=y, workspace=ws,
+                                  residual=True)
+
             t_u, t_f = timed(unfused), timed(fused)
+            y.zero_()
+            t_r = timed(fused_residual)
             nbytes = dx * K * 2 * F * 2 + dz * F * N * 2 + K * 2 + 2 * F * 4 + N * 4
-            for variant, t in (("sparse, 2 calls + torch silu*up", t_u), ("sparse, fused block", t_f)):
+            for variant, t in (("sparse, 2 calls + torch silu*up", t_u), ("sparse, fused block", t_f),
+                               ("sparse, fused block adding to y (fp32 atomic adds)", t_r)):
                 blocks.append({"block": name, "K": K, "F": F, "N": N, "variant": variant, "target": s,
                                "density_x": round(dx, 4), "density_z": round(dz, 4), "us": round(t, 2),
                                "GBps": round(nbytes / t / 1e3, 1), "vs_dense": round(t_dense / t, 3)})

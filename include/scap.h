@@ -255,6 +255,20 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
                       void* stream);
 
 /*
+ * ASYNC.  The same block of ONE token with its output ADDED to y: y[o] += block(x)[o], y holding the residual
+ * stream when the call is enqueued (the feed-forward block of a decoder layer ends in that addition).  The down
+ * launch then adds every workgroup's share to y with fp32 atomic adds instead of collecting split-K partial sums:
+ * one dependent memory round trip instead of three at the end of the block, and no fixed order of the additions
+ * (the last bits of y may differ from run to run).  Arguments as in scap_swiglu_block; B must be 1 and both layers
+ * must fit the one-token kernel (SCAP_ERR_CONFIG otherwise).  z_out, idx_z_out and nnz_z_out are exact as always.
+ */
+int scap_swiglu_block_residual(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale,
+                               int64_t K, int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x,
+                               float tau_x, const float* b_gu_fused, float m_z, float tau_z,
+                               const float* b_down_fused, float* y, float* z_out, int32_t* idx_z_out,
+                               int32_t* nnz_z_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ASYNC.  Streaming-read probe used to measure the HBM read ceiling of the box: reads `bytes` bytes at
  * `src` (DEVICE, 16-byte aligned, bytes a multiple of 16) with 2048 workgroups and stores one uint32
  * checksum per workgroup to out (DEVICE, uint32 [SCAP_PROBE_SLOTS]).

@@ -145,9 +145,10 @@ static int launch_block_half(const Gemv1Args& a, int wdt, bool i8_half, hipStrea
 }
 
 // Fused SwiGLU block of one token on the one-token kernel: the gate|up launch with the gating epilogue, then the
-// down launch reading the lists.  `up` and `down` as for launch_swiglu_block.  kG1NotApplicable when either layer
-// needs more than 2048 channels per workgroup.
-int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, hipStream_t stream) {
+// down launch reading the lists.  `up` and `down` as for launch_swiglu_block; down_flags: the down launch's flags
+// (kG1FlagAccumulate: y += block output).  kG1NotApplicable when either layer needs more than 2048 channels per
+// workgroup.
+int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int down_flags, hipStream_t stream) {
     if (up.B != 1) return kG1NotApplicable;
     Plan1 pu, pd;
     int rc = plan_gemv1(up, wdt, 0, false, 8, kWave, 1, &pu);
@@ -157,7 +158,7 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, hipStr
     const int segz = pu.tile / 8 / 2;  // gated channels a wavefront slice of the gate|up launch finishes: 32 or 64
     if (pd.Kc % segz != 0 || pd.Kc / segz > kWave) return kG1NotApplicable;
     Gemv1Args a = args_of(up, pu, 0);
-    Gemv1Args b = args_of(dn, pd, 0);
+    Gemv1Args b = args_of(dn, pd, down_flags);
     for (Gemv1Args* q : {&a, &b}) {
         q->m2 = up.m2;
         q->tau2 = up.tau2;

@@ -93,7 +93,7 @@ int launch_gemv1(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStre
 // folding and an input length that is not a multiple of 8).
 int launch_gemv1b(const GemvArgs& a, int wdt, int flags, hipStream_t stream);
 // The fused block of one token on the same kernel (two launches); kG1NotApplicable likewise.
-int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
+int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, int down_flags, hipStream_t stream);
 
 // Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
 // `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.

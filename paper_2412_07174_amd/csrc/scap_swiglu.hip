@@ -77,7 +77,7 @@ int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipSt
     // per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
     // 3-4 tokens, so the choice only has to be the same for both launches.
     if (up.B == 1) {  // one token: the one-token kernel with the gating epilogue / the list prologue
-        const int rc = launch_swiglu_block1(up, down, wdt, stream);
+        const int rc = launch_swiglu_block1(up, down, wdt, 0, stream);
         if (rc != kG1NotApplicable) return rc;
     }
     const bool matrix = up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3);

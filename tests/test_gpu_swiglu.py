@@ -71,15 +71,17 @@ class Block:
             w = w * wl.decode(self.sd, F16).astype(np.float64)[None, :]
         return w
 
-    def run(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, want_lists=True, want_z=True):
+    def run(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, want_lists=True, want_z=True, addend=None):
         b_gu = None if bg is None else scap.pack_gate_up(f32_dev(bg), f32_dev(bu))
         z = torch.full((self.F,), float("nan"), dtype=torch.float32, device="cuda") if want_z else None
         idx = torch.full((self.F,), -7, dtype=torch.int32, device="cuda") if want_lists else None
         nnz = torch.full((1,), -7, dtype=torch.int32, device="cuda") if want_lists else None
-        y = torch.full((1, self.N), float("nan"), dtype=torch.float32, device="cuda")
+        # addend given: the residual form, y starts as the addend and the block's output is added to it
+        y = (torch.full((1, self.N), float("nan"), dtype=torch.float32, device="cuda") if addend is None
+             else f32_dev(addend).reshape(1, self.N).clone())
         scap.swiglu_block(self.W_gu, self.W_down, to_dev(x_bits, xdt), m_x, tau_x, b_gu, m_z, tau_z, f32_dev(bd),
                           gu_scale=self.gu_scale, down_scale=self.down_scale, y=y, z_out=z, idx_z_out=idx,
-                          nnz_z_out=nnz, workspace=self.ws)
+                          nnz_z_out=nnz, workspace=self.ws, residual=addend is not None)
         torch.cuda.synchronize()
         out = {"y": y.cpu().numpy()[0]}
         if want_z:
@@ -115,14 +117,14 @@ class Block:
             # from 5 tokens (int8 weights: from 3) both launches run on the matrix cores
             self.compare(got, want, m_z, tau_z, f"{what} token {b}", matrix_cores=B_MATRIX(self.dt, len(gots)))
 
-    def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what):
+    def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what, addend=None):
         want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, x_bits, m_x, tau_x, m_z, tau_z, self.dt, xdt,
                                    b_gate=bg, b_up=bu, b_down=bd, gate_scale=self.sg, up_scale=self.su,
                                    down_scale=self.sd, nthreads=8)
-        got = self.run(x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd)
-        return got, want, self.compare(got, want, m_z, tau_z, what)
+        got = self.run(x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, addend=addend)
+        return got, want, self.compare(got, want, m_z, tau_z, what, addend=addend)
 
-    def compare(self, got, want, m_z, tau_z, what, matrix_cores=False):
+    def compare(self, got, want, m_z, tau_z, what, matrix_cores=False, addend=None):
         zo = want["z"].astype(np.float64)
         fin = np.isfinite(zo)
         # vector kernel (up to 4 tokens): fp32 sums in another order than the oracle's fp64 ones;
@@ -145,6 +147,8 @@ class Block:
         assert not np.any(diff & ~band), f"{what}: {np.count_nonzero(diff & ~band)} decisions differ outside the band"
         # y for the decisions taken
         y_want = want["y"].astype(np.float64)
+        if addend is not None:
+            y_want = y_want + addend.astype(np.float64)
         extra, missing = np.nonzero(diff & g_mask)[0], np.nonzero(diff & o_mask)[0]
         if extra.size:
             y_want = y_want + d[extra].astype(np.float64) @ self.down_rows(extra)
@@ -211,6 +215,31 @@ def test_small_blocks_int8(K, F, N):
         for b in range(X.shape[0]):
             say(f"block int8 K={K} F={F} N={N} tau_x={tau_x} tau_z={tau_z:.4g} vec={b}")
             blk.check(X[b], BF16, 0.0, tau_x, None, None, 0.0, tau_z, None, f"int8 K={K} F={F} N={N}")
+
+
+@pytest.mark.parametrize("K,F,N,dt", [(256, 512, 128, BF16), (1000, 2056, 528, F16), (520, 1032, 2064, I8), (4096, 14336, 4096, BF16)])
+def test_residual_block_adds_to_y(K, F, N, dt):
+    """scap_swiglu_block_residual: y starts as a given addend and ends as addend + block output (fp32 atomic adds in the
+    down launch, so compared at the float tolerance); z, the kept list and its count are exact as in the plain
+    block; an ordinary block on the same workspace afterwards; more than one token is refused."""
+    blk = Block(K, F, N, dt, seed=900 + K, std=0.02 if K >= 4096 else 0.05)
+    xdt = BF16 if dt == I8 else dt
+    X = wl.laplace(3, K, 901 + K, xdt, loc=0.0, scale=0.8)
+    rng = np.random.default_rng(K + F + N)
+    addend = rng.standard_normal(N).astype(np.float32)
+    bd = rng.standard_normal(N).astype(np.float32) * 0.05
+    sg = dict(gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd)
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.0, 0.5, 0.0, 0.0, dt, xdt, nthreads=8, **sg)["z"])
+    for b, (tau_x, tau_z) in enumerate(((0.0, 0.0), (0.5, float(np.median(zs))), (0.9, 1e9))):
+        say(f"residual block K={K} F={F} N={N} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
+        blk.check(X[b], xdt, 0.0, tau_x, None, None, 0.0, tau_z, bd, f"residual block K={K} tau_z={tau_z}", addend=addend)
+    say("an ordinary block afterwards")
+    blk.check(X[1], xdt, 0.0, 0.5, None, None, 0.0, float(np.median(zs)), bd, "block after residual blocks")
+    blk2 = Block(64, 64, 16, BF16, seed=77, B=2)
+    with pytest.raises(scap.ScapError):
+        scap.swiglu_block(blk2.W_gu, blk2.W_down, to_dev(wl.laplace(2, 64, 78, BF16, loc=0.0, scale=1.0), BF16), 0.0, 0.1, None,
+                          0.0, 0.1, None, y=torch.zeros((2, 16), dtype=torch.float32, device="cuda"), workspace=blk2.ws,
+                          residual=True)
 
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
