@@ -94,11 +94,16 @@ typedef struct {
                                 (about 1.5 us of a one-token launch) and with it the fixed order of the additions:
                                 the last bits of y may differ from run to run.  One token through the one-token
                                 kernel only (sparse or dense mode); SCAP_ERR_CONFIG where that kernel does not
-                                apply.  idx_out / nnz_out are exact as always */
+                                apply.  idx_out / nnz_out are exact as always;
+                                bit 3 (SCAP_CFG_PARTIAL_SUMS): the one-token kernel hands its split-K partial sums
+                                over as fp32 values that the last arrival collects and adds in split order, instead
+                                of adding them as fixed-point integers with one atomic per column (both are
+                                bit-reproducible; they differ in the last bits of y).  Bit 0 implies it */
 } scap_launch_cfg;
 #define SCAP_CFG_DEVICE_SCOPE_LOADS 1
 #define SCAP_CFG_GENERAL_KERNEL 2
 #define SCAP_CFG_ACCUMULATE 4
+#define SCAP_CFG_PARTIAL_SUMS 8
 
 /* Static, NUL-terminated description of a status code.  Never freed. */
 const char* scap_status_string(int status);

@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libscap.so")
 F16, BF16, I8 = 0, 1, 2
 MODE_ZERO, MODE_MEAN, MODE_MEDIAN, MODE_HIST = 0, 1, 2, 3
 MAX_TOKENS = 16
-CFG_DEVICE_SCOPE_LOADS, CFG_GENERAL_KERNEL, CFG_ACCUMULATE = 1, 2, 4
+CFG_DEVICE_SCOPE_LOADS, CFG_GENERAL_KERNEL, CFG_ACCUMULATE, CFG_PARTIAL_SUMS = 1, 2, 4, 8
 
 _TORCH_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8}
 

@@ -42,6 +42,7 @@ void fill_workspace_ptrs(GemvArgs& a, void* ws, int64_t K, int64_t N, int64_t B)
     char* base = static_cast<char*>(ws);
     a.counters = reinterpret_cast<int32_t*>(base + kOffCounters);
     a.seg_cnt = reinterpret_cast<int32_t*>(base + kOffSegCnt);
+    a.fx_acc = reinterpret_cast<unsigned long long*>(base + kOffFx);
     a.partial = reinterpret_cast<float*>(base + kOffPartial);
     a.u_idx = nullptr;
     a.u_d = nullptr;
@@ -316,6 +317,7 @@ int block_common(const void* W_gu, const void* gu_scale, const void* W_down, con
     up.tau = tau_x;
     up.counters = reinterpret_cast<int32_t*>(base + kOffCounters);
     up.seg_cnt = reinterpret_cast<int32_t*>(base + kOffSegCnt);
+    up.fx_acc = reinterpret_cast<unsigned long long*>(base + kOffFx);
     up.partial = reinterpret_cast<float*>(base + kOffPartial);
     up.m2 = m_z;
     up.tau2 = tau_z;

@@ -81,6 +81,10 @@ Gemv1Args args_of(const GemvArgs& g, const Plan1& pl, int flags) {
     a.flags = flags;
     a.m = g.m;
     a.tau = g.tau;
+    // fixed-point hand-over unless the caller asks for partial sums (either flag), the layer is wider than the
+    // words provided or a column has more arrivals than a word counts
+    const bool fx = !(flags & (kG1FlagPartials | kG1FlagDeviceScope)) && g.N <= kFxCols && pl.S <= kFxMaxSplits;
+    a.fx_acc = fx ? g.fx_acc : nullptr;
     return a;
 }
 
@@ -169,6 +173,7 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int do
         q->segz = segz;
     }
     a.z_out = up.z_out;
+    a.fx_acc = nullptr;  // the gating epilogue needs a whole slice finished by one wavefront: partial sums
     a.idx_out = a.nnz_out = a.union_nnz_out = nullptr;
     b.x = nullptr;
     rc = launch_block_half<kFuseSwiglu>(a, wdt, pu.i8_half, stream);

@@ -41,6 +41,17 @@ constexpr int kG1TicketWords = 32;   // int32 words between the tickets of a til
 
 constexpr int kG1FlagDeviceScope = 1;  // always fetch the partials with device-coherent loads
 constexpr int kG1FlagAccumulate = 4;   // y += result: every workgroup adds its share to y with fp32 atomics
+constexpr int kG1FlagPartials = 8;     // hand split-K partial sums over as fp32 values (not as fixed-point atomics)
+
+// Fixed-point hand-over: one 64-bit word per output column, updated by ONE atomic add per arrival:
+//   bits 63-57 arrivals so far, bits 56-50 how many of them escaped, bits 49-0 the sum of (partial * 2^frac + BIAS).
+constexpr int kFxMaxSplits = 64;
+constexpr int kFxRangeBits = 20;  // partial sums below 2^20 in magnitude travel as fixed point; others escape
+__host__ __device__ inline int fx_limit_bits(int S) {  // bits of one arrival's magnitude: S biased values fit 50 bits
+    int hs = 0;
+    while ((1 << hs) < S) ++hs;
+    return 49 - hs;
+}
 
 // int8 weights read 8 bytes per lane instead of 16 (internal to this kernel): the column tile is 512 columns
 // instead of 1024, so a layer with few columns gets twice the tiles and half the K splits.  With 4096 columns
@@ -107,6 +118,7 @@ struct Gemv1Args {
     float* zl_d;       // [nseg][segz] their centred values
     int32_t* zl_cnt;   // [nseg] entries per segment
     int F, segz;       // channels of the gated product; channels per list segment (32 or 64)
+    unsigned long long* fx_acc;  // fixed-point hand-over words and escape masks, or NULL: partial sums
 };
 
 // id of the accelerator die (XCD) this wavefront runs on: hardware register XCC_ID (20), bits 3:0
@@ -250,12 +262,13 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                                                            int32_t* counters, const uint16_t* col_scale, int32_t* idx_out,
                                                            int32_t* nnz_out, int32_t* union_nnz_out, int32_t* seg_cnt,
                                                            float m2, float tau2, float* z_out, int32_t* zl_idx, float* zl_d,
-                                                           int32_t* zl_cnt, int F, int segz) {
+                                                           int32_t* zl_cnt, int F, int segz, unsigned long long* fx_acc) {
     Gemv1Args a;
     a.W = W; a.x = x; a.col_scale = col_scale; a.bias = bias; a.y = y; a.partial = partial; a.counters = counters;
     a.idx_out = idx_out; a.nnz_out = nnz_out; a.union_nnz_out = union_nnz_out; a.seg_cnt = seg_cnt;
     a.K = K; a.N = N; a.Kc = Kc; a.S = S; a.T = T; a.mode = mode; a.xdt = xdt; a.flags = flags; a.m = m; a.tau = tau;
     a.m2 = m2; a.tau2 = tau2; a.z_out = z_out; a.zl_idx = zl_idx; a.zl_d = zl_d; a.zl_cnt = zl_cnt; a.F = F; a.segz = segz;
+    a.fx_acc = fx_acc;
     constexpr int ELEMS = Vec<WDT>::kElems;
     constexpr bool IS_I8 = WDT == kI8 || WDT == kI8Half;
     constexpr int TILE = kWave * ELEMS;
@@ -584,6 +597,81 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
         return;
     }
 
+    // ------------------------------------------------------------------ 4a. split-K hand-over in fixed point
+    // The S partial sums of a column are added as INTEGERS: each arrival rounds its partial to a multiple of
+    // 2^-frac (frac chosen so that S of them fit 50 bits with 2^20 of range; 2^-24 for 32 splits) and adds it,
+    // biased to be non-negative, to the column's 64-bit word together with a 1 in the arrival count -- ONE
+    // atomic with return per column.  Integer addition is associative, so the sum does not depend on the order of
+    // the arrivals (y is bit-reproducible) and nobody has to collect anything: whoever sees the count reach S holds
+    // the complete sum in the value its own atomic returned, converts it once (fp64, one rounding to fp32), applies
+    // scale and bias, stores y and clears the word.  One memory round trip after the last row instead of three.
+    // A partial that is not finite or not below 2^20 in magnitude ESCAPES: it is handed over the old way -- stored
+    // as fp32 into its partial-sum slot, its split marked in the column's escape mask, both acknowledged before the
+    // atomic, which then carries a zero and a 1 in the escape count -- and the finisher adds the escaped values, in
+    // split order, to the converted sum.  So every input gives the IEEE result the partial-sum hand-over gives, up
+    // to the rounding of the non-escaped partials to 2^-frac.
+    if constexpr (FUSE != kFuseSwiglu) {
+        if (a.fx_acc != nullptr) {
+            const int limit_bits = fx_limit_bits(a.S);
+            const int frac = limit_bits - kFxRangeBits;
+            const double to_fixed = __hiloint2double((1023 + frac) << 20, 0);     // 2^frac
+            const double from_fixed = __hiloint2double((1023 - frac) << 20, 0);   // 2^-frac
+            const unsigned long long bias = 1ull << limit_bits;
+            unsigned long long* escw = a.fx_acc + kFxCols;
+            bool esc[CPL];
+            bool any_esc = false;
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                esc[c] = fcol + c < a.N && !(fabsf(sum.v[c]) < 1048576.f);  // also NaN and Inf
+                any_esc |= esc[c];
+            }
+            if (__ballot(any_esc) != 0ull) {  // rare: some partial of this slice escapes
+                const __amdgpu_buffer_rsrc_t pbuf = make_raw_buffer(a.partial, (uint32_t)a.S * a.T * TILE * 4u);
+                const uint32_t pstride = (uint32_t)a.T * TILE * 4u;
+                const uint32_t pmine = (uint32_t)((tile * TILE + w * SLICE + lane * CPL) * 4);
+                sum.store_coherent(pbuf, split * pstride + pmine);
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    if (esc[c]) __hip_atomic_fetch_or(&escw[fcol + c], 1ull << split, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                wait_memory_ops();  // value and mask bit are in place before the arrival is counted
+            }
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                if (fcol + c >= a.N) continue;
+                const long long vfix = esc[c] ? 0ll : __double2ll_rn((double)sum.v[c] * to_fixed);
+                const unsigned long long inc = (1ull << 57) | (esc[c] ? 1ull << 50 : 0ull) | (unsigned long long)(vfix + (long long)bias);
+                const unsigned long long now =
+                    __hip_atomic_fetch_add(&a.fx_acc[fcol + c], inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + inc;
+                if ((int)(now >> 57) != a.S) continue;  // not the column's last arrival
+                const long long total = (long long)(now & ((1ull << 50) - 1)) - (long long)a.S * (long long)bias;
+                float yv = (float)((double)total * from_fixed);
+                if ((now >> 50) & 127ull) {  // escaped partials: add them in split order
+                    unsigned long long mask = load_dev(&escw[fcol + c]);
+                    const float* pcol = a.partial + (size_t)tile * TILE + (fcol + c - tile * TILE);
+                    while (mask) {
+                        const int sp = __builtin_ctzll(mask);
+                        mask &= mask - 1;
+                        yv += load_dev(pcol + (size_t)sp * a.T * TILE);
+                    }
+                    store_dev(&escw[fcol + c], 0ull);
+                }
+                yv = (IS_I8 ? yv * cscale[c] : yv) + cbias[c];
+                store_dev(&a.y[fcol + c], yv);
+                store_dev(&a.fx_acc[fcol + c], 0ull);  // zero at rest
+            }
+            if (FUSE != kFusePlain || !want_lists) return;
+            // the caller's lists still need the last arrival of (tile 0, slice 0) to close their gaps
+            wait_memory_ops();
+            unsigned long long* lt = reinterpret_cast<unsigned long long*>(a.counters);
+            unsigned long long got = 0;
+            if (lane == 0) got = __hip_atomic_fetch_add(lt, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull;
+            if (__builtin_amdgcn_readfirstlane((int)(uint32_t)got) != a.S) return;
+            if (lane == 0) store_dev(lt, 0ull);
+            close_lists_wave(a, s_off, s_cnt);
+            return;
+        }
+    }
+
     // ------------------------------------------------------------------ 4. split-K hand-over per (tile, slice)
     const __amdgpu_buffer_rsrc_t pbuf = make_raw_buffer(a.partial, (uint32_t)a.S * a.T * TILE * 4u);
     const uint32_t pstride = (uint32_t)a.T * TILE * 4u;  // bytes between consecutive splits
@@ -636,7 +724,7 @@ inline size_t gemv1_lds_bytes(int tile_cols, int Kc, int waves) {
 #define G1_ARGS                                                                                                    \
     a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, a.mode, a.xdt, a.flags, a.m, a.tau, a.bias, a.y, a.partial, a.counters, \
         a.col_scale, a.idx_out, a.nnz_out, a.union_nnz_out, a.seg_cnt, a.m2, a.tau2, a.z_out, a.zl_idx, a.zl_d,  \
-        a.zl_cnt, a.F, a.segz
+        a.zl_cnt, a.F, a.segz, a.fx_acc
 template <int WDT, int WAVES, int UNROLL, int FUSE = kFusePlain>
 static int launch_gemv1_nch(const Gemv1Args& a, hipStream_t stream) {
     constexpr int TILE = kWave * Vec<WDT>::kElems;

@@ -24,7 +24,10 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 //   [65536, +32768)      int32 seg_cnt[17][256]  kept-channel counts per (token | union, K split)
 //   [131072, +1 MiB)     int32 counter per column tile, one every 1 KiB so that the arrival tickets of
 //                        different tiles go to different memory channels; zero at rest
-//   [1179648, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums; during calibration the first
+//   [1179648, +2 MiB)    one-token kernel, fixed-point hand-over: uint64 acc[131072] (per output column: arrival
+//                        count, escape count and the biased fixed-point sum of the arrivals' partial sums), then
+//                        uint64 esc[131072] (which splits handed their partial over as fp32 instead); zero at rest
+//   [3276800, +4*B*cap)  float partial[B][S][T][tile]   split-K partial sums; during calibration the first
 //                        512 KiB hold the uint64 count of every 16-bit code
 //   [.., +68*(K+16384))  batched path (B >= 2): union list of every list segment (64 bytes of A operands and
 //                        the channel index per entry)
@@ -32,7 +35,9 @@ constexpr int kModeFold = 2;    // d = m for every channel            (Eq. 6, et
 constexpr size_t kOffSegCnt = 65536;
 constexpr size_t kOffCounters = 131072;
 constexpr int kCounterStride = 256;  // int32 words between the counters of neighbouring tiles
-constexpr size_t kOffPartial = kOffCounters + 1024 * (size_t)kCounterStride * 4;
+constexpr size_t kOffFx = kOffCounters + 1024 * (size_t)kCounterStride * 4;
+constexpr int kFxCols = 131072;  // output columns the fixed-point hand-over covers (wider layers use partial sums)
+constexpr size_t kOffPartial = kOffFx + (size_t)kFxCols * 16;
 constexpr size_t kOffCodeHist = kOffPartial;
 constexpr size_t kCalibBytes = kOffCodeHist + 65536 * 8;  // workspace bytes calibration needs
 constexpr int kMaxTiles = 1024;
@@ -65,6 +70,7 @@ struct GemvArgs {
     int32_t* union_nnz_out;
     int32_t* counters;
     int32_t* seg_cnt;
+    unsigned long long* fx_acc;  // fixed-point hand-over words [kFxCols], then the escape masks [kFxCols]; or NULL
     float* partial;
     int32_t* u_idx;  // batched path: union list of each segment, [Sl][Kl] channel indices
     float* u_d;      // batched path: the union list's centred values as MFMA A operands: per 16 entries 64 lanes x

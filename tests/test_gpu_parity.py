@@ -74,10 +74,10 @@ ONE_TOKEN = [
 
 @pytest.mark.parametrize("K,N,dt,rows", ONE_TOKEN)
 def test_one_token_kernel_shapes_and_both_hand_overs(K, N, dt, rows):
-    """The one-token kernel against the oracle, and its two ways of fetching the split-K partial sums (ordinary
-    loads when all writers ran on the reader's own accelerator die, device-coherent loads otherwise or when
-    asked for) against each other and against the general vector kernel's masks: y bit-identical between the
-    two hand-overs, on repeated calls with changing inputs through one workspace."""
+    """The one-token kernel against the oracle with each of its split-K hand-overs: fixed-point atomics (the
+    default), and fp32 partial sums collected by the last arrival with ordinary loads (when all writers ran on the
+    reader's own accelerator die) or with device-coherent loads -- those two bit-identical to each other --; and the
+    general vector kernel; on repeated calls with changing inputs through one workspace."""
     if dt == I8:
         Wq, sc = wl.quantize_i8(K, N, 331 + K)
         layer = Layer(Wq, I8, col_scale_bits=sc, B=1)
@@ -91,11 +91,15 @@ def test_one_token_kernel_shapes_and_both_hand_overs(K, N, dt, rows):
         x = X[rep]
         say(f"one-token K={K} N={N} dt={dt} rows={rows} tau={tau}")
         for unroll in (8, 16, 4):
-            near, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, 0),
-                                           what=f"one-token K={K} N={N} rows={rows} unroll={unroll} tau={tau}")
+            fx, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, 0),
+                                         what=f"one-token K={K} N={N} rows={rows} unroll={unroll} tau={tau}")
+            near, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, scap.CFG_PARTIAL_SUMS),
+                                           what=f"one-token, partial sums K={K} N={N} rows={rows} unroll={unroll} tau={tau}")
             far = gpu_sparse_fc(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, scap.CFG_DEVICE_SCOPE_LOADS))
-            assert np.array_equal(near["y"].view(np.uint32), far["y"].view(np.uint32)), "hand-over paths differ"
-            assert np.array_equal(near["idx"][0], far["idx"][0])
+            assert np.array_equal(near["y"].view(np.uint32), far["y"].view(np.uint32)), "partial-sum hand-overs differ"
+            assert np.array_equal(near["idx"][0], far["idx"][0]) and np.array_equal(fx["idx"][0], far["idx"][0])
+            again = gpu_sparse_fc(layer, x, xdt, 0.1, tau, bf, cfg=(8, rows, unroll, 64, 0))
+            assert np.array_equal(fx["y"].view(np.uint32), again["y"].view(np.uint32)), "fixed-point hand-over not reproducible"
         check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(8, 0 if rows > 1024 else rows, 8, 64, scap.CFG_GENERAL_KERNEL),
                              what=f"general kernel K={K} N={N} tau={tau}")
 
@@ -185,22 +189,27 @@ def test_few_tokens_kernel_shapes_and_both_hand_overs(K, N, dt, B):
 
 def test_one_token_kernel_many_calls_in_a_row_both_hand_overs():
     """Back-to-back launches on one workspace with rotating weights and inputs (what the benchmark does): the
-    ordinary-load hand-over must never see a partial sum of an earlier launch.  Every y is compared bit for bit
-    with the same call made with device-coherent loads."""
+    ordinary-load hand-over must never see a partial sum of an earlier launch, and the fixed-point hand-over's
+    words must be back at zero after every launch.  Every y of the partial-sum hand-over is compared bit for bit
+    with the same call made with device-coherent loads; the fixed-point series is run twice and compared with
+    itself bit for bit and with the partial-sum series at the float tolerance."""
     K, N = 14336, 4096
     Ws = [to_dev(wl.weights(K, N, 341 + i, BF16), BF16) for i in range(3)]
     X = to_dev(wl.swiglu(16, K, 345, BF16), BF16)
     ws = scap.Workspace(K, N, 1)
     calls = [(i % 3, i % 16, (0.05, 0.3, 0.8, 0.0)[i % 4]) for i in range(48)]
     ys = {}
-    for flags in (0, scap.CFG_DEVICE_SCOPE_LOADS):
+    for key, flags in (("fx", 0), ("near", scap.CFG_PARTIAL_SUMS), ("far", scap.CFG_DEVICE_SCOPE_LOADS), ("fx again", 0)):
         out = torch.empty((len(calls), N), dtype=torch.float32, device="cuda")
-        say(f"48 launches in a row, flags={flags}")
+        say(f"48 launches in a row, {key}")
         for n, (wi, xi, tau) in enumerate(calls):
             scap.sparse_fc(Ws[wi], X[xi], 0.0, tau, None, y=out[n:n + 1], workspace=ws, cfg=(8, 0, 8, 64, flags))
         torch.cuda.synchronize()
-        ys[flags] = out.cpu().numpy()
-    assert np.array_equal(ys[0].view(np.uint32), ys[scap.CFG_DEVICE_SCOPE_LOADS].view(np.uint32))
+        ys[key] = out.cpu().numpy()
+    assert np.array_equal(ys["near"].view(np.uint32), ys["far"].view(np.uint32))
+    assert np.array_equal(ys["fx"].view(np.uint32), ys["fx again"].view(np.uint32))
+    assert float(np.abs(ys["fx"] - ys["near"]).max()) < 1e-4
+    ys[0] = ys["fx"]
     # and one of them against the oracle
     want = oracle.sparse_fc(wl.weights(K, N, 341 + 2, BF16), wl.swiglu(16, K, 345, BF16)[5], 0.0, 0.3, None, BF16, BF16)
     n = calls.index((2, 5, 0.3))
@@ -301,6 +310,42 @@ def test_two_tokens_ties_nonfinite_and_one_empty_mask():
     got = gpu_sparse_fc(layer, x, BF16, 0.0, 100.0, bf)
     assert list(got["nnz"]) == [0, 0] and got["union_nnz"] == 0
     assert np.array_equal(got["y"][0], bf) and np.array_equal(got["y"][1], bf)
+
+
+def test_fixed_point_hand_over_escapes():
+    """Partial sums the fixed-point hand-over cannot carry -- 2^20 or more in magnitude, infinite, NaN -- travel as
+    fp32 beside it: columns whose partial sums are all huge, columns where only some splits escape, and
+    non-finite inputs, against the oracle at fp32 relative accuracy; the words are back at zero afterwards (an
+    ordinary call on the same workspace follows)."""
+    K, N = 4096, 1544
+    rng = np.random.default_rng(421)
+    Wf = rng.standard_normal((K, N)).astype(np.float32)
+    Wf[:, ::3] *= 1024.0     # every third column: partial sums around 2^21, most of them escape, not all
+    Wf[:512, 1::3] *= 512.0  # the next ones: only splits that cover the first channels can escape
+    W = wl.encode(Wf, BF16)
+    layer = Layer(W, BF16, B=1)
+    xs = (rng.standard_normal(K) * 300.0).astype(np.float32)
+    for name, x in (("huge", xs), ("huge and non-finite", np.where(np.arange(K) == 77, np.inf, np.where(np.arange(K) == 3000, np.nan, xs)))):
+        xb = wl.encode(x.astype(np.float32), BF16)
+        for tau in (0.0, 150.0):
+            say(f"escapes: {name} tau={tau}")
+            want = oracle.sparse_fc(W, xb, 0.0, tau, None, BF16, BF16)
+            got = gpu_sparse_fc(layer, xb, BF16, 0.0, tau, None)
+            ref = gpu_sparse_fc(layer, xb, BF16, 0.0, tau, None, cfg=(0, 0, 0, 0, scap.CFG_PARTIAL_SUMS))
+            assert np.array_equal(got["idx"][0], want["idx"][0])
+            wy, gy, ry = want["y"][0].astype(np.float64), got["y"][0].astype(np.float64), ref["y"][0].astype(np.float64)
+            assert np.array_equal(np.isnan(gy), np.isnan(wy)) and np.array_equal(np.isinf(gy), np.isinf(wy))
+            fin = np.isfinite(wy)
+            if fin.any():
+                assert np.abs(wy[fin]).max() > 2.0 ** 22  # the case is what it claims to be
+                tol = 1e-5 * np.abs(wy[fin]) + 1e-6 * np.abs(wy[fin]).max()  # fp32 sums of terms up to 2^22
+                assert np.all(np.abs(gy[fin] - wy[fin]) <= tol), (np.abs(gy[fin] - wy[fin]) / tol).max()
+                assert np.all(np.abs(ry[fin] - wy[fin]) <= tol)
+    say("an ordinary call afterwards")
+    W2 = wl.weights(K, N, 422, BF16)
+    layer2 = Layer(W2, BF16, B=1)
+    layer2.ws = layer.ws
+    check_against_oracle(layer2, wl.laplace(1, K, 423, BF16, loc=0.1, scale=0.5)[0], BF16, 0.1, 0.3, None, what="after escapes")
 
 
 def test_rerun_is_bit_identical_and_workspace_is_reusable():
