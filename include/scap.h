@@ -98,12 +98,16 @@ typedef struct {
                                 bit 3 (SCAP_CFG_PARTIAL_SUMS): the one-token kernel hands its split-K partial sums
                                 over as fp32 values that the last arrival collects and adds in split order, instead
                                 of adding them as fixed-point integers with one atomic per column (both are
-                                bit-reproducible; they differ in the last bits of y).  Bit 0 implies it */
+                                bit-reproducible; they differ in the last bits of y).  Bit 0 implies it;
+                                bit 4 (SCAP_CFG_PARK_SLICES, scap_swiglu_block_ex only, for tests): the first launch
+                                of a one-token block gates every slice by the way a slice takes when its columns were
+                                finished by more than one wavefront (through memory) */
 } scap_launch_cfg;
 #define SCAP_CFG_DEVICE_SCOPE_LOADS 1
 #define SCAP_CFG_GENERAL_KERNEL 2
 #define SCAP_CFG_ACCUMULATE 4
 #define SCAP_CFG_PARTIAL_SUMS 8
+#define SCAP_CFG_PARK_SLICES 16
 
 /* Static, NUL-terminated description of a status code.  Never freed. */
 const char* scap_status_string(int status);
@@ -258,6 +262,14 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
                       const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,
                       float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
                       void* stream);
+
+/* Same as scap_swiglu_block with launch flags for its one-token form (cfg may be NULL): of cfg only the flags
+ * SCAP_CFG_PARTIAL_SUMS and SCAP_CFG_PARK_SLICES are read, and only when B == 1.  For tests and measurements. */
+int scap_swiglu_block_ex(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale, int64_t K,
+                         int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x, float tau_x,
+                         const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,
+                         float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
+                         void* stream, const scap_launch_cfg* cfg);
 
 /*
  * ASYNC.  The same block of ONE token with its output ADDED to y: y[o] += block(x)[o], y holding the residual

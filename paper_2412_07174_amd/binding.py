@@ -13,14 +13,15 @@ _LIB_PATH = os.path.join(_HERE, "libscap.so")
 F16, BF16, I8 = 0, 1, 2
 MODE_ZERO, MODE_MEAN, MODE_MEDIAN, MODE_HIST = 0, 1, 2, 3
 MAX_TOKENS = 16
-CFG_DEVICE_SCOPE_LOADS, CFG_GENERAL_KERNEL, CFG_ACCUMULATE, CFG_PARTIAL_SUMS = 1, 2, 4, 8
+CFG_DEVICE_SCOPE_LOADS, CFG_GENERAL_KERNEL, CFG_ACCUMULATE, CFG_PARTIAL_SUMS, CFG_PARK_SLICES = 1, 2, 4, 8, 16
 
 _TORCH_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.int8: I8}
 
 EXPORTS = (
     "scap_status_string", "scap_version", "scap_workspace_bytes", "scap_workspace_init", "scap_calibrate",
     "scap_fold_bias", "scap_sparse_fc", "scap_sparse_fc_ex", "scap_sparse_fc_static", "scap_dense_fc", "scap_read_probe",
-    "scap_pack_gate_up", "scap_swiglu_workspace_bytes", "scap_swiglu_block", "scap_swiglu_block_residual",
+    "scap_pack_gate_up", "scap_swiglu_workspace_bytes", "scap_swiglu_block", "scap_swiglu_block_ex",
+    "scap_swiglu_block_residual",
 )
 
 
@@ -84,6 +85,9 @@ def load_library() -> ctypes.CDLL:
     lib.scap_swiglu_block_residual.restype = i32
     lib.scap_swiglu_block_residual.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i32, i64, f32, f32, vp, f32, f32, vp, vp,
                                       vp, vp, vp, vp, sz, vp]
+    lib.scap_swiglu_block_ex.restype = i32
+    lib.scap_swiglu_block_ex.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i32, i64, f32, f32, vp, f32, f32, vp, vp,
+                                      vp, vp, vp, vp, sz, vp, vp]
     lib.scap_read_probe.restype = i32
     lib.scap_read_probe.argtypes = [vp, sz, vp, vp]
     _lib = lib
@@ -355,9 +359,10 @@ def pack_gate_up(gate: torch.Tensor, up: torch.Tensor, stream=None) -> torch.Ten
 def swiglu_block(W_gu: torch.Tensor, W_down: torch.Tensor, x: torch.Tensor, m_x: float, tau_x: float,
                  b_gu_fused: Optional[torch.Tensor], m_z: float, tau_z: float, b_down_fused: Optional[torch.Tensor], *,
                  gu_scale=None, down_scale=None, y: Optional[torch.Tensor] = None, z_out=None, idx_z_out=None,
-                 nnz_z_out=None, workspace: Workspace, stream=None, residual: bool = False) -> torch.Tensor:
+                 nnz_z_out=None, workspace: Workspace, stream=None, residual: bool = False, cfg=None) -> torch.Tensor:
     """y[N] of the SwiGLU block: W_gu is the packed [K, 2F] gate|up matrix, W_down is [F, N].
-    residual=True (one token): scap_swiglu_block_residual, the block's output is added to the given y."""
+    residual=True (one token): scap_swiglu_block_residual, the block's output is added to the given y.
+    cfg: launch flags of the one-token form (scap_swiglu_block_ex), not together with residual."""
     lib = load_library()
     a = _Args()
     a.weights(W_gu, gu_scale, "W_gu")
@@ -383,11 +388,14 @@ def swiglu_block(W_gu: torch.Tensor, W_down: torch.Tensor, x: torch.Tensor, m_x:
         y = torch.empty((B, N), dtype=torch.float32, device=x.device)
     if _code(W_gu, "W_gu") != _code(W_down, "W_down"):
         raise TypeError("W_gu and W_down must have one dtype")
-    entry = lib.scap_swiglu_block_residual if residual else lib.scap_swiglu_block
+    if cfg is not None and residual:
+        raise ValueError("cfg and residual=True cannot be combined")
+    entry = lib.scap_swiglu_block_residual if residual else (lib.scap_swiglu_block if cfg is None else lib.scap_swiglu_block_ex)
+    extra = () if cfg is None else (_cfg(cfg),)
     rc = entry(_ptr(W_gu), _ptr(gu_scale), _ptr(W_down), _ptr(down_scale), K, F, N, _code(W_gu, "W_gu"),
                _ptr(x), _code(x, "x"), B, float(m_x), float(tau_x), _ptr(b_gu_fused), float(m_z),
                float(tau_z), _ptr(b_down_fused), _ptr(y), _ptr(z_out), _ptr(idx_z_out),
-               _ptr(nnz_z_out), _ptr(workspace.buf), workspace.nbytes, _stream(stream))
+               _ptr(nnz_z_out), _ptr(workspace.buf), workspace.nbytes, _stream(stream), *extra)
     _check(rc, "scap_swiglu_block_residual" if residual else "scap_swiglu_block")
     return y
 

@@ -278,7 +278,7 @@ int block_common(const void* W_gu, const void* gu_scale, const void* W_down, con
                  int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x, float tau_x,
                  const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y, float* z_out,
                  int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes, void* stream,
-                 bool residual) {
+                 bool residual, int flags1) {
     if (F < 1 || F > kMaxGated) return SCAP_ERR_SHAPE;
     int rc = check_layer(W_gu, gu_scale, K, 2 * F, wdt);
     if (rc != SCAP_OK) return rc;
@@ -344,10 +344,10 @@ int block_common(const void* W_gu, const void* gu_scale, const void* W_down, con
     dn.z_out = nullptr;
     if (residual) {
         if (B != 1) return SCAP_ERR_CONFIG;
-        const int rc = launch_swiglu_block1(up, dn, wdt, SCAP_CFG_ACCUMULATE, static_cast<hipStream_t>(stream));
+        const int rc = launch_swiglu_block1(up, dn, wdt, flags1, SCAP_CFG_ACCUMULATE, static_cast<hipStream_t>(stream));
         return rc == kG1NotApplicable ? SCAP_ERR_CONFIG : rc;
     }
-    return launch_swiglu_block(up, dn, wdt, static_cast<hipStream_t>(stream));
+    return launch_swiglu_block(up, dn, wdt, static_cast<hipStream_t>(stream), flags1);
 }
 }  // namespace
 
@@ -359,7 +359,17 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
                       float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
                       void* stream) {
     return block_common(W_gu, gu_scale, W_down, down_scale, K, F, N, wdt, x, xdt, B, m_x, tau_x, b_gu_fused, m_z, tau_z,
-                        b_down_fused, y, z_out, idx_z_out, nnz_z_out, workspace, workspace_bytes, stream, false);
+                        b_down_fused, y, z_out, idx_z_out, nnz_z_out, workspace, workspace_bytes, stream, false, 0);
+}
+
+int scap_swiglu_block_ex(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale, int64_t K,
+                         int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x, float tau_x,
+                         const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,
+                         float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
+                         void* stream, const scap_launch_cfg* cfg) {
+    const int flags1 = cfg ? cfg->flags & (SCAP_CFG_PARTIAL_SUMS | SCAP_CFG_PARK_SLICES) : 0;
+    return block_common(W_gu, gu_scale, W_down, down_scale, K, F, N, wdt, x, xdt, B, m_x, tau_x, b_gu_fused, m_z, tau_z,
+                        b_down_fused, y, z_out, idx_z_out, nnz_z_out, workspace, workspace_bytes, stream, false, flags1);
 }
 
 int scap_swiglu_block_residual(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale,
@@ -368,7 +378,7 @@ int scap_swiglu_block_residual(const void* W_gu, const void* gu_scale, const voi
                                const float* b_down_fused, float* y, float* z_out, int32_t* idx_z_out,
                                int32_t* nnz_z_out, void* workspace, size_t workspace_bytes, void* stream) {
     return block_common(W_gu, gu_scale, W_down, down_scale, K, F, N, wdt, x, xdt, B, m_x, tau_x, b_gu_fused, m_z, tau_z,
-                        b_down_fused, y, z_out, idx_z_out, nnz_z_out, workspace, workspace_bytes, stream, true);
+                        b_down_fused, y, z_out, idx_z_out, nnz_z_out, workspace, workspace_bytes, stream, true, 0);
 }
 
 int scap_read_probe(const void* src, size_t bytes, uint32_t* out, void* stream) {

@@ -149,10 +149,10 @@ static int launch_block_half(const Gemv1Args& a, int wdt, bool i8_half, hipStrea
 }
 
 // Fused SwiGLU block of one token on the one-token kernel: the gate|up launch with the gating epilogue, then the
-// down launch reading the lists.  `up` and `down` as for launch_swiglu_block; down_flags: the down launch's flags
-// (kG1FlagAccumulate: y += block output).  kG1NotApplicable when either layer needs more than 2048 channels per
+// down launch reading the lists.  `up` and `down` as for launch_swiglu_block; up_flags, down_flags: the launches'
+// flags (kG1FlagPartials; up: kG1FlagParkSlices; down: kG1FlagAccumulate, y += block output).  kG1NotApplicable when either layer needs more than 2048 channels per
 // workgroup.
-int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int down_flags, hipStream_t stream) {
+int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int up_flags, int down_flags, hipStream_t stream) {
     if (up.B != 1) return kG1NotApplicable;
     Plan1 pu, pd;
     int rc = plan_gemv1(up, wdt, 0, false, 8, kWave, 1, &pu);
@@ -161,7 +161,7 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int do
     if (rc != SCAP_OK) return rc;
     const int segz = pu.tile / 8 / 2;  // gated channels a wavefront slice of the gate|up launch finishes: 32 or 64
     if (pd.Kc % segz != 0 || pd.Kc / segz > kWave) return kG1NotApplicable;
-    Gemv1Args a = args_of(up, pu, 0);
+    Gemv1Args a = args_of(up, pu, up_flags);
     Gemv1Args b = args_of(dn, pd, down_flags);
     for (Gemv1Args* q : {&a, &b}) {
         q->m2 = up.m2;
@@ -173,7 +173,8 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int do
         q->segz = segz;
     }
     a.z_out = up.z_out;
-    a.fx_acc = nullptr;  // the gating epilogue needs a whole slice finished by one wavefront: partial sums
+    // the gating epilogue parks finished columns behind the partial-sum slots when a slice is finished piecemeal
+    if ((size_t)(pu.S + 1) * pu.T * pu.tile > partial_capacity(up.N)) a.fx_acc = nullptr;
     a.idx_out = a.nnz_out = a.union_nnz_out = nullptr;
     b.x = nullptr;
     rc = launch_block_half<kFuseSwiglu>(a, wdt, pu.i8_half, stream);

@@ -42,6 +42,7 @@ constexpr int kG1TicketWords = 32;   // int32 words between the tickets of a til
 constexpr int kG1FlagDeviceScope = 1;  // always fetch the partials with device-coherent loads
 constexpr int kG1FlagAccumulate = 4;   // y += result: every workgroup adds its share to y with fp32 atomics
 constexpr int kG1FlagPartials = 8;     // hand split-K partial sums over as fp32 values (not as fixed-point atomics)
+constexpr int kG1FlagParkSlices = 16;  // gating epilogue: always take the way through memory (for tests)
 
 // Fixed-point hand-over: one 64-bit word per output column, updated by ONE atomic add per arrival:
 //   bits 63-57 arrivals so far, bits 56-50 how many of them escaped, bits 49-0 the sum of (partial * 2^frac + BIAS).
@@ -517,10 +518,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
         for (int c = 0; c < CPL; ++c) sum.v[c] += s_red[i * TILE + w * SLICE + lane * CPL + c];
     }
 
-    auto finish = [&](const slice_t& s) {
-        float p[CPL];  // finished columns: scaled (int8), fused bias added
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) p[c] = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
+    // what happens to a slice whose columns are finished (p: scaled for int8, fused bias added) in this wavefront
+    auto emit = [&](const float* p) {
         if constexpr (FUSE != kFuseSwiglu) {
 #pragma unroll
             for (int c = 0; c < CPL; ++c)  // written through: lines left modified in L2 are paid for when the kernel ends
@@ -569,6 +568,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
             }
         }
     };
+    auto finish = [&](const slice_t& s) {
+        float p[CPL];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) p[c] = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
+        emit(p);
+    };
     if constexpr (FUSE != kFuseSwiglu) {
         if (a.flags & kG1FlagAccumulate) {
             // y already holds what the result is to be added to (a residual stream, say).  Every workgroup adds its
@@ -610,7 +615,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
     // atomic, which then carries a zero and a 1 in the escape count -- and the finisher adds the escaped values, in
     // split order, to the converted sum.  So every input gives the IEEE result the partial-sum hand-over gives, up
     // to the rounding of the non-escaped partials to 2^-frac.
-    if constexpr (FUSE != kFuseSwiglu) {
+    {
         if (a.fx_acc != nullptr) {
             const int limit_bits = fx_limit_bits(a.S);
             const int frac = limit_bits - kFxRangeBits;
@@ -635,6 +640,13 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                     if (esc[c]) __hip_atomic_fetch_or(&escw[fcol + c], 1ull << split, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 wait_memory_ops();  // value and mask bit are in place before the arrival is counted
             }
+            float fin_p[CPL];  // the gating epilogue: finished columns stay in registers
+            bool fin_done[CPL];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                fin_p[c] = 0.f;
+                fin_done[c] = false;
+            }
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
                 if (fcol + c >= a.N) continue;
@@ -656,8 +668,47 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                     store_dev(&escw[fcol + c], 0ull);
                 }
                 yv = (IS_I8 ? yv * cscale[c] : yv) + cbias[c];
-                store_dev(&a.y[fcol + c], yv);
+                if constexpr (FUSE != kFuseSwiglu) store_dev(&a.y[fcol + c], yv);
+                fin_p[c] = yv;
+                fin_done[c] = true;
                 store_dev(&a.fx_acc[fcol + c], 0ull);  // zero at rest
+            }
+            if constexpr (FUSE == kFuseSwiglu) {
+                // The gating epilogue works on a whole slice (gate and up columns side by side, one compacted list
+                // segment).  Nearly always the wavefront that finishes one column of a slice finishes all of them:
+                // then the slice is gated from registers.  Otherwise the finished columns are parked in memory and
+                // counted on the slice's ticket; whoever completes the count fetches the slice and gates it.
+                const int first = tile * TILE + w * SLICE;
+                const int live_cols = min(max(a.N - first, 0), SLICE);  // columns of this slice that exist
+                if (live_cols == 0) return;
+                bool all_done = true, any_done = false;
+                int n_done = 0;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    if (fcol + c < a.N) all_done &= fin_done[c];
+                    any_done |= fin_done[c];
+                    n_done += fin_done[c] ? 1 : 0;
+                }
+                if (__ballot(!all_done) == 0ull && !(a.flags & kG1FlagParkSlices)) {
+                    emit(fin_p);
+                    return;
+                }
+                if (__ballot(any_done) == 0ull) return;
+                float* park = a.partial + (size_t)a.S * a.T * TILE;  // behind the partial-sum slots (room checked on the host)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    if (fin_done[c]) store_dev(&park[fcol + c], fin_p[c]);
+                wait_memory_ops();
+                n_done = wave_sum(n_done);
+                unsigned long long* st = reinterpret_cast<unsigned long long*>(a.counters + tile * kCounterStride + w * kG1TicketWords);
+                unsigned long long got = 0;
+                if (lane == 0) got = __hip_atomic_fetch_add(st, (unsigned long long)n_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + (unsigned long long)n_done;
+                if (__builtin_amdgcn_readfirstlane((int)(uint32_t)got) != live_cols) return;
+                if (lane == 0) store_dev(st, 0ull);
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) fin_p[c] = fcol + c < a.N ? load_dev(&park[fcol + c]) : 0.f;
+                emit(fin_p);
+                return;
             }
             if (FUSE != kFusePlain || !want_lists) return;
             // the caller's lists still need the last arrival of (tile 0, slice 0) to close their gaps

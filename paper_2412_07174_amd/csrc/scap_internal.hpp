@@ -99,7 +99,8 @@ int launch_gemv1(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStre
 // folding and an input length that is not a multiple of 8).
 int launch_gemv1b(const GemvArgs& a, int wdt, int flags, hipStream_t stream);
 // The fused block of one token on the same kernel (two launches); kG1NotApplicable likewise.
-int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, int down_flags, hipStream_t stream);
+int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, int up_flags, int down_flags,
+                         hipStream_t stream);
 
 // Fused SwiGLU block: two launches (gate|up with the gating epilogue, then down reading the lists).
 // `up` and `down` carry the two layers' arguments; the list pointers and m2/tau2 are set in both.
@@ -107,7 +108,7 @@ constexpr int kBlockVectorTokens = 4;  // tokens per fused-block call on the vec
 constexpr int kBlockMaxTokens = 16;    // ... on the matrix cores (bf16 and int8 weights)
 // token slots of the block's lists for B tokens
 inline int block_token_slots(int64_t B) { return B <= 1 ? 1 : (B == 2 ? 2 : (B <= 4 ? 4 : 16)); }
-int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream);
+int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream, int flags1 = 0);
 
 // Interleave two [rows, F] arrays of `elem_bytes`-byte elements in groups of 4 columns: out[rows, 2F].
 int launch_pack_gate_up(const void* gate, const void* up, int64_t rows, int64_t F, int elem_bytes, void* out,

@@ -72,12 +72,13 @@ static int launch_block_wdt(const GemvArgs& up, const GemvArgs& down, hipStream_
     return SCAP_ERR_UNIMPL;
 }
 
-int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream) {
+// flags1: launch flags of the one-token form (partial sums / parked slices), ignored with more tokens
+int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream, int flags1) {
     // Matrix cores: more than 4 tokens, and int8 from 3 tokens on, where the vector kernel is bound by its
     // per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
     // 3-4 tokens, so the choice only has to be the same for both launches.
     if (up.B == 1) {  // one token: the one-token kernel with the gating epilogue / the list prologue
-        const int rc = launch_swiglu_block1(up, down, wdt, 0, stream);
+        const int rc = launch_swiglu_block1(up, down, wdt, flags1, flags1 & SCAP_CFG_PARTIAL_SUMS, stream);
         if (rc != kG1NotApplicable) return rc;
     }
     const bool matrix = up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3);

@@ -71,7 +71,7 @@ class Block:
             w = w * wl.decode(self.sd, F16).astype(np.float64)[None, :]
         return w
 
-    def run(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, want_lists=True, want_z=True, addend=None):
+    def run(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, want_lists=True, want_z=True, addend=None, cfg=None):
         b_gu = None if bg is None else scap.pack_gate_up(f32_dev(bg), f32_dev(bu))
         z = torch.full((self.F,), float("nan"), dtype=torch.float32, device="cuda") if want_z else None
         idx = torch.full((self.F,), -7, dtype=torch.int32, device="cuda") if want_lists else None
@@ -81,7 +81,7 @@ class Block:
              else f32_dev(addend).reshape(1, self.N).clone())
         scap.swiglu_block(self.W_gu, self.W_down, to_dev(x_bits, xdt), m_x, tau_x, b_gu, m_z, tau_z, f32_dev(bd),
                           gu_scale=self.gu_scale, down_scale=self.down_scale, y=y, z_out=z, idx_z_out=idx,
-                          nnz_z_out=nnz, workspace=self.ws, residual=addend is not None)
+                          nnz_z_out=nnz, workspace=self.ws, residual=addend is not None, cfg=cfg)
         torch.cuda.synchronize()
         out = {"y": y.cpu().numpy()[0]}
         if want_z:
@@ -117,11 +117,11 @@ class Block:
             # from 5 tokens (int8 weights: from 3) both launches run on the matrix cores
             self.compare(got, want, m_z, tau_z, f"{what} token {b}", matrix_cores=B_MATRIX(self.dt, len(gots)))
 
-    def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what, addend=None):
+    def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what, addend=None, cfg=None):
         want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, x_bits, m_x, tau_x, m_z, tau_z, self.dt, xdt,
                                    b_gate=bg, b_up=bu, b_down=bd, gate_scale=self.sg, up_scale=self.su,
                                    down_scale=self.sd, nthreads=8)
-        got = self.run(x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, addend=addend)
+        got = self.run(x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, addend=addend, cfg=cfg)
         return got, want, self.compare(got, want, m_z, tau_z, what, addend=addend)
 
     def compare(self, got, want, m_z, tau_z, what, matrix_cores=False, addend=None):
@@ -240,6 +240,30 @@ def test_residual_block_adds_to_y(K, F, N, dt):
         scap.swiglu_block(blk2.W_gu, blk2.W_down, to_dev(wl.laplace(2, 64, 78, BF16, loc=0.0, scale=1.0), BF16), 0.0, 0.1, None,
                           0.0, 0.1, None, y=torch.zeros((2, 16), dtype=torch.float32, device="cuda"), workspace=blk2.ws,
                           residual=True)
+
+
+@pytest.mark.parametrize("K,F,N,dt", [(256, 512, 128, BF16), (1000, 2056, 528, F16), (520, 1032, 2064, I8), (4096, 14336, 4096, BF16)])
+def test_one_token_block_hand_overs(K, F, N, dt):
+    """The one-token block with each hand-over of its two launches: fixed-point atomics (the default; the gating
+    epilogue of a slice run from registers), the same with every slice gated by the way through memory (what a slice
+    takes when more than one wavefront finished its columns) -- bit-identical to the default in z, list and y --, and
+    fp32 partial sums; each against the oracle."""
+    blk = Block(K, F, N, dt, seed=950 + K, std=0.02 if K >= 4096 else 0.05)
+    xdt = BF16 if dt == I8 else dt
+    X = wl.laplace(2, K, 951 + K, xdt, loc=0.0, scale=0.8)
+    rng = np.random.default_rng(K + F)
+    bd = rng.standard_normal(N).astype(np.float32) * 0.05
+    sg = dict(gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd)
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.0, 0.5, 0.0, 0.0, dt, xdt, nthreads=8, **sg)["z"])
+    for b, (tau_x, tau_z) in enumerate(((0.0, 0.0), (0.5, float(np.median(zs))))):
+        say(f"block hand-overs K={K} F={F} N={N} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
+        fx, _, _ = blk.check(X[b], xdt, 0.0, tau_x, None, None, 0.0, tau_z, bd, "block, fixed point")
+        parked, _, _ = blk.check(X[b], xdt, 0.0, tau_x, None, None, 0.0, tau_z, bd, "block, parked slices",
+                                 cfg=(0, 0, 0, 0, scap.CFG_PARK_SLICES))
+        blk.check(X[b], xdt, 0.0, tau_x, None, None, 0.0, tau_z, bd, "block, partial sums", cfg=(0, 0, 0, 0, scap.CFG_PARTIAL_SUMS))
+        assert np.array_equal(fx["z"].view(np.uint32), parked["z"].view(np.uint32))
+        assert np.array_equal(fx["idx_z"], parked["idx_z"])
+        assert np.array_equal(fx["y"].view(np.uint32), parked["y"].view(np.uint32))
 
 
 # ------------------------------------------------------------------ several tokens: own masks, union of rows
