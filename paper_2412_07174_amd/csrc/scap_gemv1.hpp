@@ -314,15 +314,20 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
         }
     }
     // constants of the columns this lane finishes, needed only at the very end: loaded now, behind the inputs
-    const int fcol = tile * TILE + w * SLICE + lane * CPL;
+    // Column c of this lane is fcol + c * CSTR: lanes side by side, so that every store and atomic of the hand-over
+    // covers 64 consecutive words (with the lane's columns adjacent one instruction spread over twice or four times
+    // the cache lines, and the atomics of a 2-column slice took 2 us instead of 0.7).
+    constexpr int CSTR = kWave;
+    constexpr int LSTR = 1;
+    const int fcol = tile * TILE + w * SLICE + lane * LSTR;
     float cbias[CPL], cscale[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         cbias[c] = 0.f;
         cscale[c] = 1.f;
-        if (fcol + c < a.N) {
-            if (a.bias) cbias[c] = a.bias[fcol + c];
-            if (IS_I8) cscale[c] = f16_bits_to_f32(a.col_scale[fcol + c]);
+        if (fcol + c * CSTR < a.N) {
+            if (a.bias) cbias[c] = a.bias[fcol + c * CSTR];
+            if (IS_I8) cscale[c] = f16_bits_to_f32(a.col_scale[fcol + c * CSTR]);
         }
     }
 
@@ -515,20 +520,35 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
 #pragma unroll
     for (int i = 0; i < WAVES; ++i) {
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) sum.v[c] += s_red[i * TILE + w * SLICE + lane * CPL + c];
+        for (int c = 0; c < CPL; ++c) sum.v[c] += s_red[i * TILE + w * SLICE + lane * LSTR + c * CSTR];
     }
 
     // what happens to a slice whose columns are finished (p: scaled for int8, fused bias added) in this wavefront
-    auto emit = [&](const float* p) {
+    auto emit = [&](const float* pt) {
         if constexpr (FUSE != kFuseSwiglu) {
+            const float* p = pt;
 #pragma unroll
             for (int c = 0; c < CPL; ++c)  // written through: lines left modified in L2 are paid for when the kernel ends
-                if (fcol + c < a.N) store_dev(&a.y[fcol + c], p[c]);
+                if (fcol + c * CSTR < a.N) store_dev(&a.y[fcol + c * CSTR], p[c]);
         } else {
             // Columns come in groups of 8: 4 gate pre-activations, then the 4 matching up pre-activations.  The
             // lanes that hold gate columns fetch their up partners from 4 columns further on, form
             // z = silu(gate) * up (Alg. 2), centre and threshold it like any layer input (Alg. 3 steps 1-2, strict
             // compare of Eq. 2) and leave the slice's kept channels, compacted and ascending, as one list segment.
+            // Here a lane needs CPL ADJACENT columns (a group's gate and up columns sit in neighbouring lanes): column
+            // acol + c = slice column lane * CPL + c, which lane (that number mod 64) holds as its (number / 64)-th.
+            float p[CPL];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int j = lane * CPL + c;
+                p[c] = 0.f;
+#pragma unroll
+                for (int cc = 0; cc < CPL; ++cc) {
+                    const float t = __shfl(pt[cc], j & 63, kWave);
+                    if ((j >> 6) == cc) p[c] = t;
+                }
+            }
+            const int acol = tile * TILE + w * SLICE + lane * CPL;
             constexpr int LPG = 8 / CPL;  // lanes per group of 8 columns
             const bool gate_lane = (lane % LPG) < LPG / 2;
             float dz[CPL];
@@ -537,7 +557,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
                 const float up = __shfl_down(p[c], LPG / 2, kWave);
-                const int col = fcol + c;
+                const int col = acol + c;
                 chan[c] = (col >> 3) * 4 + (col & 3);
                 const bool live = gate_lane && col < a.N && chan[c] < a.F;
                 const float z = p[c] / (1.f + expf(-p[c])) * up;
@@ -583,7 +603,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
                 const float p = (IS_I8 ? sum.v[c] * cscale[c] : sum.v[c]) + (split == 0 ? cbias[c] : 0.f);
-                if (fcol + c < a.N) __hip_atomic_fetch_add(&a.y[fcol + c], p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (fcol + c * CSTR < a.N) __hip_atomic_fetch_add(&a.y[fcol + c * CSTR], p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             if (FUSE != kFusePlain || !want_lists || a.S == 1) return;
             // the caller's lists still need the last arrival of (tile 0, slice 0) to close their gaps
@@ -627,7 +647,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
             bool any_esc = false;
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
-                esc[c] = fcol + c < a.N && !(fabsf(sum.v[c]) < 1048576.f);  // also NaN and Inf
+                esc[c] = fcol + c * CSTR < a.N && !(fabsf(sum.v[c]) < 1048576.f);  // also NaN and Inf
                 any_esc |= esc[c];
             }
             if (__ballot(any_esc) != 0ull) {  // rare: some partial of this slice escapes
@@ -637,7 +657,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 sum.store_coherent(pbuf, split * pstride + pmine);
 #pragma unroll
                 for (int c = 0; c < CPL; ++c)
-                    if (esc[c]) __hip_atomic_fetch_or(&escw[fcol + c], 1ull << split, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (esc[c]) __hip_atomic_fetch_or(&escw[fcol + c * CSTR], 1ull << split, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 wait_memory_ops();  // value and mask bit are in place before the arrival is counted
             }
             float fin_p[CPL];  // the gating epilogue: finished columns stay in registers
@@ -647,31 +667,37 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 fin_p[c] = 0.f;
                 fin_done[c] = false;
             }
+            // all of the lane's atomics first (one round trip for the lot), then what they returned
+            unsigned long long now_c[CPL];
 #pragma unroll
             for (int c = 0; c < CPL; ++c) {
-                if (fcol + c >= a.N) continue;
+                now_c[c] = 0ull;
+                if (fcol + c * CSTR >= a.N) continue;
                 const long long vfix = esc[c] ? 0ll : __double2ll_rn((double)sum.v[c] * to_fixed);
                 const unsigned long long inc = (1ull << 57) | (esc[c] ? 1ull << 50 : 0ull) | (unsigned long long)(vfix + (long long)bias);
-                const unsigned long long now =
-                    __hip_atomic_fetch_add(&a.fx_acc[fcol + c], inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + inc;
-                if ((int)(now >> 57) != a.S) continue;  // not the column's last arrival
+                now_c[c] = __hip_atomic_fetch_add(&a.fx_acc[fcol + c * CSTR], inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + inc;
+            }
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const unsigned long long now = now_c[c];
+                if ((int)(now >> 57) != a.S) continue;  // not the column's last arrival (or no column: count 0, S > 1)
                 const long long total = (long long)(now & ((1ull << 50) - 1)) - (long long)a.S * (long long)bias;
                 float yv = (float)((double)total * from_fixed);
                 if ((now >> 50) & 127ull) {  // escaped partials: add them in split order
-                    unsigned long long mask = load_dev(&escw[fcol + c]);
-                    const float* pcol = a.partial + (size_t)tile * TILE + (fcol + c - tile * TILE);
+                    unsigned long long mask = load_dev(&escw[fcol + c * CSTR]);
+                    const float* pcol = a.partial + (size_t)tile * TILE + (w * SLICE + lane * CPL + c);
                     while (mask) {
                         const int sp = __builtin_ctzll(mask);
                         mask &= mask - 1;
                         yv += load_dev(pcol + (size_t)sp * a.T * TILE);
                     }
-                    store_dev(&escw[fcol + c], 0ull);
+                    store_dev(&escw[fcol + c * CSTR], 0ull);
                 }
                 yv = (IS_I8 ? yv * cscale[c] : yv) + cbias[c];
-                if constexpr (FUSE != kFuseSwiglu) store_dev(&a.y[fcol + c], yv);
+                if constexpr (FUSE != kFuseSwiglu) store_dev(&a.y[fcol + c * CSTR], yv);
                 fin_p[c] = yv;
                 fin_done[c] = true;
-                store_dev(&a.fx_acc[fcol + c], 0ull);  // zero at rest
+                store_dev(&a.fx_acc[fcol + c * CSTR], 0ull);  // zero at rest
             }
             if constexpr (FUSE == kFuseSwiglu) {
                 // The gating epilogue works on a whole slice (gate and up columns side by side, one compacted list
@@ -685,7 +711,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 int n_done = 0;
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) {
-                    if (fcol + c < a.N) all_done &= fin_done[c];
+                    if (fcol + c * CSTR < a.N) all_done &= fin_done[c];
                     any_done |= fin_done[c];
                     n_done += fin_done[c] ? 1 : 0;
                 }
@@ -697,7 +723,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 float* park = a.partial + (size_t)a.S * a.T * TILE;  // behind the partial-sum slots (room checked on the host)
 #pragma unroll
                 for (int c = 0; c < CPL; ++c)
-                    if (fin_done[c]) store_dev(&park[fcol + c], fin_p[c]);
+                    if (fin_done[c]) store_dev(&park[fcol + c * CSTR], fin_p[c]);
                 wait_memory_ops();
                 n_done = wave_sum(n_done);
                 unsigned long long* st = reinterpret_cast<unsigned long long*>(a.counters + tile * kCounterStride + w * kG1TicketWords);
@@ -706,7 +732,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemv1_kernel(const uint16_t* x,
                 if (__builtin_amdgcn_readfirstlane((int)(uint32_t)got) != live_cols) return;
                 if (lane == 0) store_dev(st, 0ull);
 #pragma unroll
-                for (int c = 0; c < CPL; ++c) fin_p[c] = fcol + c < a.N ? load_dev(&park[fcol + c]) : 0.f;
+                for (int c = 0; c < CPL; ++c) fin_p[c] = fcol + c * CSTR < a.N ? load_dev(&park[fcol + c * CSTR]) : 0.f;
                 emit(fin_p);
                 return;
             }

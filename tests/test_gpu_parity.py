@@ -161,8 +161,9 @@ def test_few_tokens_kernel_shapes_and_both_hand_overs(K, N, dt, B):
     """2 tokens on the two-token form of the one-token kernel (the library's choice when the input length is a
     multiple of 8 and the layer is not a wide one of 16-bit weights), 3 and 4 tokens on whatever the library picks
     for these shapes: against the oracle token by token -- y, every token's list and count, the union count --,
-    with ordinary and with device-coherent loads of the partial sums against each other bit for bit, and dense
-    mode, on repeated calls with changing inputs through one workspace."""
+    with the kernel's default hand-over (repeatable bit for bit), and with ordinary and with device-coherent loads of
+    the partial sums against each other bit for bit, and dense mode, on repeated calls with changing inputs through
+    one workspace."""
     if dt == I8:
         Wq, sc = wl.quantize_i8(K, N, 351 + K)
         layer = Layer(Wq, I8, col_scale_bits=sc, B=4)
@@ -175,9 +176,13 @@ def test_few_tokens_kernel_shapes_and_both_hand_overs(K, N, dt, B):
     for rep, tau in enumerate((0.0, 0.3, 0.35, 0.9, 2.5, 1e6)):
         x = X[rep * B:(rep + 1) * B]
         say(f"few tokens K={K} N={N} dt={dt} B={B} tau={tau}")
-        near, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, what=f"few tokens K={K} N={N} B={B} tau={tau}")
+        what = f"few tokens K={K} N={N} B={B} tau={tau}"
+        got, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, what=what)  # the default hand-over of this kernel
+        again = gpu_sparse_fc(layer, x, xdt, 0.1, tau, bf)
+        assert np.array_equal(got["y"].view(np.uint32), again["y"].view(np.uint32)), "not reproducible"
+        near, _ = check_against_oracle(layer, x, xdt, 0.1, tau, bf, cfg=(0, 0, 0, 0, scap.CFG_PARTIAL_SUMS), what=what)
         far = gpu_sparse_fc(layer, x, xdt, 0.1, tau, bf, cfg=(0, 0, 0, 0, scap.CFG_DEVICE_SCOPE_LOADS))
-        assert np.array_equal(near["y"].view(np.uint32), far["y"].view(np.uint32)), "hand-over paths differ"
+        assert np.array_equal(near["y"].view(np.uint32), far["y"].view(np.uint32)), "partial-sum hand-overs differ"
         for b in range(B):
             assert np.array_equal(near["idx"][b], far["idx"][b])
     say(f"few tokens K={K} N={N} dt={dt} B={B} dense")
@@ -442,6 +447,45 @@ def test_batched_tokens_moderate(B, path):
     for tau in (0.0, 0.15, 0.8, 50.0):
         say(f"batched B={B} path={path} tau={tau}")
         check_against_oracle(layer, X, BF16, 0.0, tau, bf, cfg=cfg, what=f"B={B} {path} tau={tau}")
+
+
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix", "lists"])
+@pytest.mark.parametrize("B", [3, 8, 16])
+def test_batched_tokens_huge_and_nonfinite_sums(B, path):
+    """Several tokens, split K, with columns whose partial sums reach 2^21 and beyond, one token with an infinite
+    and one with a NaN activation, one token whose sums stay small: against the oracle at fp32 relative accuracy,
+    then an ordinary call on the same workspace."""
+    K, N = 4099, 1544
+    cfg = {"auto": None, "vector": (8, 0, 8 if B <= 4 else 4, 64), "matrix": (0, 0, 0, 16), "lists": (0, 0, 0, 1)}[path]
+    rng = np.random.default_rng(541 + B)
+    Wf = rng.standard_normal((K, N)).astype(np.float32)
+    Wf[:, ::3] *= 1024.0
+    Wf[:512, 1::3] *= 512.0
+    Wh = wl.encode(Wf, BF16)
+    huge = Layer(Wh, BF16, B=16)
+    xs = (rng.standard_normal((B, K)) * 300.0).astype(np.float32)
+    xs[2] *= 1e-3  # one token whose sums stay small
+    xs[0, 77] = np.inf
+    if B > 3:
+        xs[3, 3000] = np.nan
+    xb = wl.encode(xs, BF16)
+    for tau in (0.0, 150.0):
+        say(f"huge sums B={B} path={path} tau={tau}")
+        want = oracle.sparse_fc(Wh, xb, 0.0, tau, None, BF16, BF16)
+        got = gpu_sparse_fc(huge, xb, BF16, 0.0, tau, None, cfg=cfg)
+        for b in range(B):
+            assert np.array_equal(got["idx"][b], want["idx"][b])
+            wy, gy = (v["y"][b].astype(np.float64) for v in (want, got))
+            assert np.array_equal(np.isnan(gy), np.isnan(wy)) and np.array_equal(np.isinf(gy), np.isinf(wy)), f"token {b}"
+            fin = np.isfinite(wy)
+            if fin.any() and np.abs(wy[fin]).max() > 0:
+                tol = 1e-5 * np.abs(wy[fin]) + 1e-6 * np.abs(wy[fin]).max()
+                assert np.all(np.abs(gy[fin] - wy[fin]) <= tol), (b, (np.abs(gy[fin] - wy[fin]) / tol).max())
+        assert np.abs(want["y"][1]).max() > 2.0 ** 22 and np.abs(want["y"][2]).max() < 2.0 ** 16  # what the case claims
+    say("an ordinary call afterwards")
+    layer = Layer(wl.weights(K, N, 540, BF16), BF16, B=16)
+    layer.ws = huge.ws
+    check_against_oracle(layer, wl.swiglu(B, K, 542 + B, BF16), BF16, 0.0, 0.2, rng.standard_normal(N).astype(np.float32), cfg=cfg, what="after huge sums")
 
 
 @pytest.mark.parametrize("wdt", [F16, BF16, I8])
