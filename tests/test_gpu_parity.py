@@ -481,7 +481,7 @@ def test_batched_tokens_huge_and_nonfinite_sums(B, path):
             if fin.any() and np.abs(wy[fin]).max() > 0:
                 tol = 1e-5 * np.abs(wy[fin]) + 1e-6 * np.abs(wy[fin]).max()
                 assert np.all(np.abs(gy[fin] - wy[fin]) <= tol), (b, (np.abs(gy[fin] - wy[fin]) / tol).max())
-        assert np.abs(want["y"][1]).max() > 2.0 ** 22 and np.abs(want["y"][2]).max() < 2.0 ** 16  # what the case claims
+        assert np.abs(want["y"][1]).max() > 2.0 ** 22 and np.abs(want["y"][2]).max() < 2.0 ** 18  # what the case claims
     say("an ordinary call afterwards")
     layer = Layer(wl.weights(K, N, 540, BF16), BF16, B=16)
     layer.ws = huge.ws
