@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # counters need the profiler.  Absent = not profiled.
 MEASURED_TRAFFIC = {
     "mistral7b_down_14336x4096_bf16_b1_s50":
-        (60225816, "recorded: profiles/gemv1_kernel_bf16_mistral_down_hbm_traffic.txt"),
+        (60225237, "recorded: profiles/gemv1_kernel_bf16_mistral_down_hbm_traffic.txt"),
     "mistral7b_down_14336x4096_bf16_b16_s90":
         (104241478, "recorded: profiles/gemm_inline_raw_kernel_bf16_mistral_down_b16_s90_hbm_traffic.txt"),
 }
