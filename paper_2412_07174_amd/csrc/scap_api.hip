@@ -367,7 +367,7 @@ int scap_swiglu_block_ex(const void* W_gu, const void* gu_scale, const void* W_d
                          const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,
                          float* z_out, int32_t* idx_z_out, int32_t* nnz_z_out, void* workspace, size_t workspace_bytes,
                          void* stream, const scap_launch_cfg* cfg) {
-    const int flags1 = cfg ? cfg->flags & (SCAP_CFG_PARTIAL_SUMS | SCAP_CFG_PARK_SLICES) : 0;
+    const int flags1 = cfg ? cfg->flags & (SCAP_CFG_PARTIAL_SUMS | SCAP_CFG_PARK_SLICES | SCAP_CFG_GENERAL_KERNEL) : 0;
     return block_common(W_gu, gu_scale, W_down, down_scale, K, F, N, wdt, x, xdt, B, m_x, tau_x, b_gu_fused, m_z, tau_z,
                         b_down_fused, y, z_out, idx_z_out, nnz_z_out, workspace, workspace_bytes, stream, false, flags1);
 }

@@ -11,6 +11,10 @@ extern template int launch_gemv1b_wdt<kF16>(const Gemv1bArgs&, hipStream_t);
 extern template int launch_gemv1b_wdt<kBF16>(const Gemv1bArgs&, hipStream_t);
 extern template int launch_gemv1b_wdt<kI8>(const Gemv1bArgs&, hipStream_t);
 extern template int launch_gemv1b_wdt<kI8Half>(const Gemv1bArgs&, hipStream_t);
+extern template int launch_gemv1b_block_wdt<kF16>(const Gemv1bArgs&, int, hipStream_t);
+extern template int launch_gemv1b_block_wdt<kBF16>(const Gemv1bArgs&, int, hipStream_t);
+extern template int launch_gemv1b_block_wdt<kI8>(const Gemv1bArgs&, int, hipStream_t);
+extern template int launch_gemv1b_block_wdt<kI8Half>(const Gemv1bArgs&, int, hipStream_t);
 #define SCAP_G1_BLOCK_EXTERN(WD)                                                             \
     extern template int launch_gemv1_block<WD, kFuseSwiglu>(const Gemv1Args&, hipStream_t); \
     extern template int launch_gemv1_block<WD, kFuseList>(const Gemv1Args&, hipStream_t);
@@ -180,6 +184,65 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int up
     rc = launch_block_half<kFuseSwiglu>(a, wdt, pu.i8_half, stream);
     if (rc != SCAP_OK) return rc;
     return launch_block_half<kFuseList>(b, wdt, pd.i8_half, stream);
+}
+
+// Fused SwiGLU block of two tokens: each of its launches can run on the two-token kernel, in the list format of the
+// batched block kernels (64-channel segments, 2 token slots), so either can be paired with the general kernel's.
+//   part 0, the gate|up launch with the gating epilogue: int8 weights in 16-byte lanes (2F > 4096; a wavefront's
+//           slice is then 128 columns = one segment), input length a multiple of 8;
+//   part 1, the down launch reading the lists: int8 weights (with 16-bit weights the general kernel's down launch
+//           measured 0.5 us faster: 4096 -> 14336 -> 4096 bf16, two tokens, 55.8 against 56.3 us at 50 %).
+// Measured on that shape with int8 weights, both launches general / gate|up on the two-token kernel / both:
+// 45.9 / 45.0 / 43.4 us with nothing pruned, 38.4 / 36.9 / 36.1 at 50 %, 22.2 / 21.5 / 20.4 at 90 %.
+// Returns SCAP_OK and fills *g, or kG1NotApplicable.
+static int plan_block2_part(const GemvArgs& up, const GemvArgs& dn, int wdt, int part, Gemv1bArgs* g, bool* i8_half) {
+    if (up.B != 2) return kG1NotApplicable;
+    const GemvArgs& src = part == 0 ? up : dn;
+    if (part == 0 && (wdt != kI8 || (src.K % 8) != 0)) return kG1NotApplicable;
+    if (part == 1 && wdt != kI8) return kG1NotApplicable;
+    Plan1 pl;
+    const int rc = plan_gemv1(src, wdt, 0, false, kG1bWaves, kWave, 2, &pl);  // whole 64-channel pieces: whole segments
+    if (rc != SCAP_OK) return kG1NotApplicable;
+    if (part == 0 && pl.i8_half) return kG1NotApplicable;
+    if (part == 1 && (pl.Kc % kWave) != 0) return kG1NotApplicable;
+    g->B = 2;
+    g->bt = 2;
+    g->a = args_of(src, pl, 0);
+    g->a.m2 = up.m2;
+    g->a.tau2 = up.tau2;
+    g->a.zl_idx = up.zl_idx;
+    g->a.zl_d = up.zl_d;
+    g->a.zl_cnt = up.zl_cnt;
+    g->a.F = up.F;
+    if (part == 0) {
+        g->a.z_out = up.z_out;
+        g->a.idx_out = g->a.nnz_out = g->a.union_nnz_out = nullptr;
+    } else {
+        g->a.x = nullptr;
+        g->a.z_out = nullptr;
+    }
+    *i8_half = pl.i8_half;
+    return SCAP_OK;
+}
+
+bool swiglu_block2_part_applies(const GemvArgs& up, const GemvArgs& dn, int wdt, int part) {
+    Gemv1bArgs g;
+    bool half = false;
+    return plan_block2_part(up, dn, wdt, part, &g, &half) == SCAP_OK;
+}
+
+int launch_swiglu_block2_part(const GemvArgs& up, const GemvArgs& dn, int wdt, int part, hipStream_t stream) {
+    Gemv1bArgs g;
+    bool half = false;
+    const int rc = plan_block2_part(up, dn, wdt, part, &g, &half);
+    if (rc != SCAP_OK) return rc;
+    const int fuse = part == 0 ? kFuseSwiglu : kFuseList;
+    switch (wdt) {
+        case kF16: return launch_gemv1b_block_wdt<kF16>(g, fuse, stream);
+        case kBF16: return launch_gemv1b_block_wdt<kBF16>(g, fuse, stream);
+        case kI8: return half ? launch_gemv1b_block_wdt<kI8Half>(g, fuse, stream) : launch_gemv1b_block_wdt<kI8>(g, fuse, stream);
+    }
+    return SCAP_ERR_DTYPE;
 }
 
 }  // namespace scap

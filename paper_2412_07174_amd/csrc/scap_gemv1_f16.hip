@@ -6,4 +6,5 @@ template int launch_gemv1_wdt<kF16>(const Gemv1Args&, int, int, hipStream_t);
 template int launch_gemv1_block<kF16, kFuseSwiglu>(const Gemv1Args&, hipStream_t);
 template int launch_gemv1_block<kF16, kFuseList>(const Gemv1Args&, hipStream_t);
 template int launch_gemv1b_wdt<kF16>(const Gemv1bArgs&, hipStream_t);
+template int launch_gemv1b_block_wdt<kF16>(const Gemv1bArgs&, int, hipStream_t);
 }  // namespace scap

@@ -10,4 +10,6 @@ template int launch_gemv1_block<kI8Half, kFuseSwiglu>(const Gemv1Args&, hipStrea
 template int launch_gemv1_block<kI8Half, kFuseList>(const Gemv1Args&, hipStream_t);
 template int launch_gemv1b_wdt<kI8>(const Gemv1bArgs&, hipStream_t);
 template int launch_gemv1b_wdt<kI8Half>(const Gemv1bArgs&, hipStream_t);
+template int launch_gemv1b_block_wdt<kI8>(const Gemv1bArgs&, int, hipStream_t);
+template int launch_gemv1b_block_wdt<kI8Half>(const Gemv1bArgs&, int, hipStream_t);
 }  // namespace scap

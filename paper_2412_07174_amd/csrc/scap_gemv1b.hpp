@@ -4,6 +4,10 @@
 // workgroup's inputs and keeps every 8th union position, the ring of row loads, one barrier and the slice-wise
 // reduction, the ticketed split-K hand-over per (tile, slice) -- with BT token slots.  Wavefront b of a tile-0
 // workgroup writes token b's ascending list; the last arrival of (tile 0, slice b) closes it.
+// FUSE gives it the two halves of the fused SwiGLU block (Alg. 2) in the list format of the batched block kernels
+// (scap_gemv_parts.hpp, "list input"; 2 token slots): kFuseSwiglu -- the wavefront that finishes a (tile, slice) of the
+// gate|up launch gates it (16-byte int8 lanes only: its slice is 128 columns = one 64-channel list segment) --, and
+// kFuseList -- the down launch takes its channels and centred values from those segments instead of x.
 // Only BT = 2 is built.  The kernel's fixed part grows with the token slots -- the last arrival of a tile pulls
 // S x BT partial slices through one compute unit's L1 (14336 x 4096 bf16: 0.9 us for one token, 2.1 for two, 3.8
 // for four) -- and with four slots it lost to the matrix-core kernels (28.1 against 24.6 us dense).
@@ -41,13 +45,14 @@ inline size_t gemv1b_lds_bytes(int tile_cols, int Kc, int bt) {
     return (size_t)kG1HdrBytes * bt + (size_t)kG1bWaves * bt * tile_cols * 4 + (size_t)kG1bWaves * g1b_slots(Kc) * 16;
 }
 
-template <int WDT, int NCH, int BT>
+template <int WDT, int NCH, int BT, int FUSE = kFusePlain>
 __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_t* x, const void* W, int K, int N, int Kc, int S,
                                                                 int T, int B, int mode, int xdt, float m, float tau, int flags,
                                                                 const float* bias, float* y, float* partial,
                                                                 int32_t* counters, const uint16_t* col_scale,
                                                                 int32_t* idx_out, int32_t* nnz_out, int32_t* union_nnz_out,
-                                                                int32_t* seg_cnt) {
+                                                                int32_t* seg_cnt, float m2, float tau2, float* z_out,
+                                                                int32_t* zl_idx, float* zl_d, int32_t* zl_cnt, int F) {
     constexpr int WAVES = kG1bWaves;
     constexpr int UNROLL = WDT == kI8Half ? 8 : 4;
     constexpr int ELEMS = Vec<WDT>::kElems;
@@ -56,6 +61,8 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
     constexpr int CPL = ELEMS / WAVES;  // columns per lane of a wavefront's slice
     constexpr int SLICE = kWave * CPL;
     static_assert(CPL == 1 || CPL == 2, "a slice is 4 or 8 bytes per lane");
+    static_assert(BT == 2, "two token slots");
+    static_assert(FUSE != kFuseSwiglu || CPL == 2, "the gating epilogue needs a slice of 128 columns: one 64-channel list segment");
     typedef SliceVec<CPL> slice_t;
 
     extern __shared__ uint4 smem_raw[];
@@ -78,13 +85,15 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
     // ------------------------------------------------------------------ 1. inputs: every wavefront, all Kc, all tokens
     // (K is a multiple of 8 -- checked on the host --, so every token's row is 16-byte aligned and no octet is ragged)
     uint4 xv[BT][NCH];
+    if constexpr (FUSE != kFuseList) {
 #pragma unroll
-    for (int b = 0; b < BT; ++b) {
+        for (int b = 0; b < BT; ++b) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            xv[b][c] = make_uint4(0u, 0u, 0u, 0u);
-            const int kb = k0 + c * kG1Chunk + 8 * lane;
-            if (b < B && kb < kend) xv[b][c] = *reinterpret_cast<const uint4*>(x + (size_t)b * K + kb);
+            for (int c = 0; c < NCH; ++c) {
+                xv[b][c] = make_uint4(0u, 0u, 0u, 0u);
+                const int kb = k0 + c * kG1Chunk + 8 * lane;
+                if (b < B && kb < kend) xv[b][c] = *reinterpret_cast<const uint4*>(x + (size_t)b * K + kb);
+            }
         }
     }
     const int fcol = tile * TILE + w * SLICE + lane * CPL;
@@ -99,11 +108,69 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
         }
     }
 
-    const bool want_lists = tile == 0 && w < B && (nnz_out != nullptr || union_nnz_out != nullptr);
+    const bool want_lists = FUSE == kFusePlain && tile == 0 && w < B && (nnz_out != nullptr || union_nnz_out != nullptr);
     const float m_eff = mode == kModeSparse ? m : 0.f;
     const uint32_t keep_all = mode == kModeSparse ? 0u : 1u;
     int cnt = 0;   // union positions so far -- wave-uniform
     int lcnt = 0;  // kept channels of token w so far (tile 0, w < B)
+    if constexpr (FUSE == kFuseList) {
+        // The workgroup's channels are Kc / 64 list segments of the gated product (K = F here; Kc is a multiple of
+        // 64).  Every entry slot of those segments and their counts are fetched together, whatever the counts will
+        // say (one memory round trip; slots past a segment's count hold stale entries and are dropped below); lane l
+        // takes the count of segment l, a prefix sum gives every entry its position in the workgroup's list.
+        constexpr int ITS = 8 * NCH;  // Kc / 64 segments at most
+        const int seg0 = k0 >> 6;
+        const int nsegw = (kend - k0 + kWave - 1) >> 6;
+        const int nsegs = (K + kWave - 1) >> 6;
+        int eidx[ITS];
+        float ed[ITS][BT];
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            eidx[it] = 0;
+            ed[it][0] = ed[it][1] = 0.f;
+            if (it < nsegw) {
+                const int64_t e = (int64_t)(seg0 + it) * kWave + lane;
+                eidx[it] = zl_idx[e];
+                const float2 dv = *reinterpret_cast<const float2*>(zl_d + e * BT);
+                ed[it][0] = dv.x;
+                ed[it][1] = dv.y;
+            }
+        }
+        int c_l = lane < nsegw ? zl_cnt[seg0 + lane] : 0;
+        c_l = min(max(c_l, 0), (int)kWave);  // keeps LDS writes in range whatever the memory holds
+        const int inc = wave_inclusive_scan(c_l);
+        const int off_l = inc - c_l;
+        cnt = __shfl(inc, kWave - 1, kWave);
+        int pos[ITS];
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int c_s = __shfl(c_l, it, kWave), o_s = __shfl(off_l, it, kWave);
+            pos[it] = (it < nsegw && lane < c_s) ? o_s + lane : -1;
+        }
+#pragma unroll
+        for (int it = 0; it < ITS; ++it)
+            if (pos[it] >= 0 && (pos[it] & (WAVES - 1)) == w) mylist.put(pos[it] / WAVES, eidx[it], ed[it]);
+        if (tile == 0 && w < B && (nnz_out != nullptr || idx_out != nullptr)) {
+            // Token w's ascending list of kept channels: an entry is the token's where its centred value is non-zero
+            // (kept means |d| > tau >= 0).  No gap closing: the entries of all earlier segments are counted in what
+            // the first launch wrote.
+            int before = 0;
+            for (int s0 = 0; s0 < seg0; s0 += kWave) {
+                const int sg = s0 + lane;
+                before += sg < seg0 ? min(max(zl_cnt[(1 + w) * nsegs + sg], 0), (int)kWave) : 0;
+            }
+            before = wave_sum(before);
+            int run = 0;
+#pragma unroll
+            for (int it = 0; it < ITS; ++it) {
+                const bool mine = pos[it] >= 0 && (w == 0 ? ed[it][0] : ed[it][1]) != 0.f;
+                const uint64_t bal = __ballot(mine);
+                if (mine && idx_out) idx_out[(int64_t)w * K + before + run + lanes_below(bal)] = eidx[it];
+                run += __popcll(bal);
+            }
+            if (split == S - 1 && lane == 0 && nnz_out) nnz_out[w] = before + run;
+        }
+    } else {
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         if (k0 + c * kG1Chunk < kend) {  // wave-uniform
@@ -165,6 +232,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
                 lcnt += __shfl(inc, kWave - 1, kWave);
             }
         }
+    }
     }
     cnt = uniform(cnt);
     lcnt = uniform(lcnt);
@@ -260,16 +328,81 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
         }
     }
 
-    auto finish = [&](int b, const slice_t& s) {  // scaled (int8), fused bias added (Eq. 6); written through to memory
+    // the finished slice of both tokens: scaled (int8), fused bias added (Eq. 6); y written through to memory, or gated
+    auto finish = [&](const slice_t* s) {
+        float p[BT][CPL];
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-            const float p = (IS_I8 ? s.v[c] * cscale[c] : s.v[c]) + cbias[c];
-            if (b < B && fcol + c < N) store_dev(&y[(size_t)b * N + fcol + c], p);
+        for (int b = 0; b < BT; ++b)
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) p[b][c] = (IS_I8 ? s[b].v[c] * cscale[c] : s[b].v[c]) + cbias[c];
+        if constexpr (FUSE != kFuseSwiglu) {
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    if (b < B && fcol + c < N) store_dev(&y[(size_t)b * N + fcol + c], p[b][c]);
+        } else {
+            // Columns come in groups of 8: 4 gate pre-activations, then the 4 matching up pre-activations; a lane holds
+            // 2 adjacent columns, so lanes 0-1 of every 4 hold a group's gate columns and fetch their up partners from
+            // 2 lanes further on.  z = silu(gate) * up (Alg. 2), centred and thresholded like any layer input (Alg. 3
+            // steps 1-2, strict compare of Eq. 2; each token its own mask); the slice's channels kept by either token
+            // become one 64-channel list segment, ascending, the tokens' centred values side by side (0 where a token
+            // pruned the channel), with the union's and the tokens' counts.
+            constexpr int LPG = 8 / CPL;
+            const bool gate_lane = (lane % LPG) < LPG / 2;
+            float dz[BT][CPL];
+            bool keep[BT][CPL], any[CPL];
+            int chan[CPL];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int col = fcol + c;
+                chan[c] = (col >> 3) * 4 + (col & 3);
+                const bool live = gate_lane && col < N && chan[c] < F;
+                any[c] = false;
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    const float up = __shfl_down(p[b][c], LPG / 2, kWave);
+                    const float z = p[b][c] / (1.f + expf(-p[b][c])) * up;
+                    if (live && b < B && z_out) store_dev(&z_out[(int64_t)b * F + chan[c]], z);
+                    const float d = z - m2;  // one fp32 subtraction
+                    keep[b][c] = live && b < B && fabsf(d) > tau2;  // strict; NaN is pruned
+                    dz[b][c] = keep[b][c] ? d : 0.f;
+                    any[c] |= keep[b][c];
+                }
+            }
+            const int seg = tile * WAVES + w;  // this slice's segment: channels seg * 64 ...
+            const int nsegs = (F + kWave - 1) >> 6;
+            if ((int64_t)seg * kWave < F) {  // wave-uniform
+                int rank = 0, total_kept = 0;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const uint64_t bal = __ballot(any[c]);
+                    rank += lanes_below(bal);
+                    total_kept += __popcll(bal);
+                }
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    if (any[c]) {
+                        const int64_t e = (int64_t)seg * kWave + rank;
+                        store_dev(&zl_idx[e], chan[c]);
+                        store_dev(reinterpret_cast<unsigned long long*>(zl_d + e * BT),
+                                  (unsigned long long)__float_as_uint(dz[0][c]) | ((unsigned long long)__float_as_uint(dz[1][c]) << 32));
+                        ++rank;  // the lane's own earlier column comes first
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    int kept_b = 0;
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) kept_b += __popcll(__ballot(keep[b][c]));
+                    if (lane == 0 && b < B) store_dev(&zl_cnt[(1 + b) * nsegs + seg], kept_b);
+                }
+                if (lane == 0) store_dev(&zl_cnt[seg], total_kept);
+            }
         }
     };
     if (S == 1) {
-#pragma unroll
-        for (int b = 0; b < BT; ++b) finish(b, sum[b]);
+        finish(sum);
         return;
     }
 
@@ -327,8 +460,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
                 }
             }
         }
-        finish(b0, total[0]);
-        finish(b0 + 1, total[1]);
+        finish(total);
     }
     if (lane == 0) store_dev(ticket, 0ull);  // ready for the next call
     if (want_lists) {
@@ -350,7 +482,7 @@ struct Gemv1bArgs {
     int B, bt;
 };
 
-template <int WDT, int NCH, int BT>
+template <int WDT, int NCH, int BT, int FUSE>
 static int launch_gemv1b_one(const Gemv1bArgs& g, size_t lds, hipStream_t stream) {
     if (lds > 64 * 1024) {  // once per device and instantiation: allow the larger dynamic LDS
         constexpr int kMaxDevices = 64;
@@ -358,7 +490,7 @@ static int launch_gemv1b_one(const Gemv1bArgs& g, size_t lds, hipStream_t stream
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SCAP_ERR_HIP;
         if (!asked[dev].load(std::memory_order_acquire)) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv1b_kernel<WDT, NCH, BT>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv1b_kernel<WDT, NCH, BT, FUSE>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kG1bMaxLds) != hipSuccess)
                 return SCAP_ERR_HIP;
             asked[dev].store(true, std::memory_order_release);
@@ -366,26 +498,37 @@ static int launch_gemv1b_one(const Gemv1bArgs& g, size_t lds, hipStream_t stream
     }
     const Gemv1Args& a = g.a;
     const dim3 grid((unsigned)(a.S * a.T)), block(kG1bWaves * kWave);
-    hipLaunchKernelGGL((gemv1b_kernel<WDT, NCH, BT>), grid, block, lds, stream, a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, g.B, a.mode,
-                       a.xdt, a.m, a.tau, a.flags, a.bias, a.y, a.partial, a.counters, a.col_scale, a.idx_out, a.nnz_out,
-                       a.union_nnz_out, a.seg_cnt);
+    hipLaunchKernelGGL((gemv1b_kernel<WDT, NCH, BT, FUSE>), grid, block, lds, stream, a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, g.B,
+                       a.mode, a.xdt, a.m, a.tau, a.flags, a.bias, a.y, a.partial, a.counters, a.col_scale, a.idx_out,
+                       a.nnz_out, a.union_nnz_out, a.seg_cnt, a.m2, a.tau2, a.z_out, a.zl_idx, a.zl_d, a.zl_cnt, a.F);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 
-template <int WDT, int BT>
+template <int WDT, int BT, int FUSE>
 static int launch_gemv1b_nch(const Gemv1bArgs& g, hipStream_t stream) {
     constexpr int TILE = kWave * Vec<WDT>::kElems;
     const size_t lds = gemv1b_lds_bytes(TILE, g.a.Kc, BT);
     if (lds > (size_t)kG1bMaxLds) return SCAP_ERR_CONFIG;
-    if (g.a.Kc <= kG1Chunk) return launch_gemv1b_one<WDT, 1, BT>(g, lds, stream);
-    if (g.a.Kc <= 2 * kG1Chunk) return launch_gemv1b_one<WDT, 2, BT>(g, lds, stream);
-    if (g.a.Kc <= 4 * kG1Chunk) return launch_gemv1b_one<WDT, 4, BT>(g, lds, stream);
+    if (g.a.Kc <= kG1Chunk) return launch_gemv1b_one<WDT, 1, BT, FUSE>(g, lds, stream);
+    if (g.a.Kc <= 2 * kG1Chunk) return launch_gemv1b_one<WDT, 2, BT, FUSE>(g, lds, stream);
+    if (g.a.Kc <= 4 * kG1Chunk) return launch_gemv1b_one<WDT, 4, BT, FUSE>(g, lds, stream);
     return SCAP_ERR_CONFIG;
 }
 
 template <int WDT>
 int launch_gemv1b_wdt(const Gemv1bArgs& g, hipStream_t stream) {
-    if (g.bt == 2) return launch_gemv1b_nch<WDT, 2>(g, stream);
+    if (g.bt == 2) return launch_gemv1b_nch<WDT, 2, kFusePlain>(g, stream);
+    return SCAP_ERR_CONFIG;
+}
+
+// the two launches of the fused block of two tokens (fuse: kFuseSwiglu -- 16-byte int8 lanes only -- or kFuseList)
+template <int WDT>
+int launch_gemv1b_block_wdt(const Gemv1bArgs& g, int fuse, hipStream_t stream) {
+    if (g.bt != 2) return SCAP_ERR_CONFIG;
+    if (fuse == kFuseList) return launch_gemv1b_nch<WDT, 2, kFuseList>(g, stream);
+    if constexpr (WDT == kI8) {
+        if (fuse == kFuseSwiglu) return launch_gemv1b_nch<WDT, 2, kFuseSwiglu>(g, stream);
+    }
     return SCAP_ERR_CONFIG;
 }
 

@@ -26,8 +26,14 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_down_kernel(const G
     gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, LPR, kFuseList>(a);
 }
 
+// wdt, flags: for the two-token block, whose launches run on the two-token kernel where that applies (unless the
+// caller asks for the general kernels)
 template <int WDT, int BT>
-static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
+static int launch_block(GemvArgs up, GemvArgs dn, int wdt, int flags, hipStream_t stream) {
+    const GemvArgs up_in = up, dn_in = dn;
+    const bool two = BT == 2 && up.B == 2 && !(flags & SCAP_CFG_GENERAL_KERNEL);
+    const bool up_two = two && swiglu_block2_part_applies(up_in, dn_in, wdt, 0);
+    const bool dn_two = two && swiglu_block2_part_applies(up_in, dn_in, wdt, 1);
     constexpr int TILE = kWave * Vec<WDT>::kElems;
     constexpr int NT = kBlockWaves * kWave;
     constexpr size_t RED = (size_t)(kBlockWaves * TILE > NT * 4 ? kBlockWaves * TILE : NT * 4);
@@ -53,8 +59,14 @@ static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
     if (lds_dn < tables) lds_dn = tables;
     if (lds_up > 64 * 1024 || lds_dn > 64 * 1024) return SCAP_ERR_SHAPE;
 
-    hipLaunchKernelGGL((swiglu_up_kernel<WDT, BT>), dim3((unsigned)(up.S * up.T)), dim3(NT), lds_up, stream, up);
-    if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
+    if (up_two) {
+        rc = launch_swiglu_block2_part(up_in, dn_in, wdt, 0, stream);
+        if (rc != SCAP_OK) return rc;
+    } else {
+        hipLaunchKernelGGL((swiglu_up_kernel<WDT, BT>), dim3((unsigned)(up.S * up.T)), dim3(NT), lds_up, stream, up);
+        if (hipGetLastError() != hipSuccess) return SCAP_ERR_HIP;
+    }
+    if (dn_two) return launch_swiglu_block2_part(up_in, dn_in, wdt, 1, stream);
     if (half) {
         hipLaunchKernelGGL((swiglu_down_kernel<WDT, BT, kWave / 2>), dim3((unsigned)(dn.S * dn.T)), dim3(NT), lds_dn,
                            stream, dn);
@@ -65,20 +77,22 @@ static int launch_block(GemvArgs up, GemvArgs dn, hipStream_t stream) {
 }
 
 template <int WDT>
-static int launch_block_wdt(const GemvArgs& up, const GemvArgs& down, hipStream_t stream) {
-    if (up.B == 1) return launch_block<WDT, 1>(up, down, stream);
-    if (up.B == 2) return launch_block<WDT, 2>(up, down, stream);
-    if (up.B <= kBlockVectorTokens) return launch_block<WDT, 4>(up, down, stream);
+static int launch_block_wdt(const GemvArgs& up, const GemvArgs& down, int flags, hipStream_t stream) {
+    if (up.B == 1) return launch_block<WDT, 1>(up, down, WDT, flags, stream);
+    if (up.B == 2) return launch_block<WDT, 2>(up, down, WDT, flags, stream);
+    if (up.B <= kBlockVectorTokens) return launch_block<WDT, 4>(up, down, WDT, flags, stream);
     return SCAP_ERR_UNIMPL;
 }
 
-// flags1: launch flags of the one-token form (partial sums / parked slices), ignored with more tokens
+// flags1: launch flags -- partial sums / parked slices for the one-token form; SCAP_CFG_GENERAL_KERNEL keeps a
+// two-token block on the general kernels
 int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipStream_t stream, int flags1) {
     // Matrix cores: more than 4 tokens, and int8 from 3 tokens on, where the vector kernel is bound by its
     // per-element converts.  Their lists use 4 or 16 token slots, like the vector kernel's for
     // 3-4 tokens, so the choice only has to be the same for both launches.
-    if (up.B == 1) {  // one token: the one-token kernel with the gating epilogue / the list prologue
-        const int rc = launch_swiglu_block1(up, down, wdt, flags1, flags1 & SCAP_CFG_PARTIAL_SUMS, stream);
+    if (up.B == 1 && !(flags1 & SCAP_CFG_GENERAL_KERNEL)) {  // the one-token kernel with the gating epilogue / the list prologue
+        const int rc = launch_swiglu_block1(up, down, wdt, flags1 & (SCAP_CFG_PARTIAL_SUMS | SCAP_CFG_PARK_SLICES),
+                                            flags1 & SCAP_CFG_PARTIAL_SUMS, stream);
         if (rc != kG1NotApplicable) return rc;
     }
     const bool matrix = up.B > kBlockVectorTokens || (wdt == kI8 && up.B >= 3);
@@ -87,9 +101,9 @@ int launch_swiglu_block(const GemvArgs& up, const GemvArgs& down, int wdt, hipSt
         if (rc != SCAP_ERR_SHAPE || up.B > kBlockVectorTokens) return rc == SCAP_ERR_SHAPE ? SCAP_ERR_UNIMPL : rc;
     }
     switch (wdt) {
-        case kF16: return launch_block_wdt<kF16>(up, down, stream);
-        case kBF16: return launch_block_wdt<kBF16>(up, down, stream);
-        case kI8: return launch_block_wdt<kI8>(up, down, stream);
+        case kF16: return launch_block_wdt<kF16>(up, down, flags1, stream);
+        case kBF16: return launch_block_wdt<kBF16>(up, down, flags1, stream);
+        case kI8: return launch_block_wdt<kI8>(up, down, flags1, stream);
     }
     return SCAP_ERR_DTYPE;
 }

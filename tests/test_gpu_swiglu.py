@@ -92,7 +92,7 @@ class Block:
             out["idx_z"] = idx.cpu().numpy()[:n].copy()
         return out
 
-    def run_batch(self, X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd):
+    def run_batch(self, X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, cfg=None):
         B = X_bits.shape[0]
         b_gu = None if bg is None else scap.pack_gate_up(f32_dev(bg), f32_dev(bu))
         z = torch.full((B, self.F), float("nan"), dtype=torch.float32, device="cuda")
@@ -101,21 +101,22 @@ class Block:
         y = torch.full((B, self.N), float("nan"), dtype=torch.float32, device="cuda")
         scap.swiglu_block(self.W_gu, self.W_down, to_dev(X_bits, xdt), m_x, tau_x, b_gu, m_z, tau_z, f32_dev(bd),
                           gu_scale=self.gu_scale, down_scale=self.down_scale, y=y, z_out=z, idx_z_out=idx,
-                          nnz_z_out=nnz, workspace=self.ws)
+                          nnz_z_out=nnz, workspace=self.ws, cfg=cfg)
         torch.cuda.synchronize()
         nn, ih, zh, yh = nnz.cpu().numpy(), idx.cpu().numpy(), z.cpu().numpy(), y.cpu().numpy()
         assert np.all((nn >= 0) & (nn <= self.F))
         return [{"y": yh[b], "z": zh[b], "idx_z": ih[b, :nn[b]].copy()} for b in range(B)]
 
-    def check_batch(self, X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what):
+    def check_batch(self, X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what, cfg=None):
         """Each token of a batch against the oracle's one-token block (tokens are independent: own masks)."""
-        gots = self.run_batch(X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd)
+        gots = self.run_batch(X_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, cfg=cfg)
         for b, got in enumerate(gots):
             want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, X_bits[b], m_x, tau_x, m_z, tau_z, self.dt, xdt,
                                        b_gate=bg, b_up=bu, b_down=bd, gate_scale=self.sg, up_scale=self.su,
                                        down_scale=self.sd, nthreads=8)
             # from 5 tokens (int8 weights: from 3) both launches run on the matrix cores
             self.compare(got, want, m_z, tau_z, f"{what} token {b}", matrix_cores=B_MATRIX(self.dt, len(gots)))
+        return gots
 
     def check(self, x_bits, xdt, m_x, tau_x, bg, bu, m_z, tau_z, bd, what, addend=None, cfg=None):
         want = oracle.swiglu_block(self.Wg, self.Wu, self.Wd, x_bits, m_x, tau_x, m_z, tau_z, self.dt, xdt,
@@ -281,6 +282,38 @@ def test_batched_blocks(B, dt):
     for tau_x, tau_z in ((0.0, 0.0), (0.5, float(np.median(zs))), (1.1, float(np.quantile(zs, 0.9))), (0.5, 1e9)):
         say(f"batched block B={B} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
         blk.check_batch(X, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"B={B} dt={dt} tau_z={tau_z}")
+
+
+@pytest.mark.parametrize("K,F,N,dt", [(1000, 2056, 1040, I8), (4096, 6144, 2080, I8), (520, 1032, 2064, I8), (256, 8, 16, I8),
+                                      (1000, 2056, 1040, BF16), (4096, 14336, 4096, BF16), (777, 4104, 528, F16),
+                                      (4096, 14336, 4096, I8)])
+def test_two_token_block_on_the_two_token_kernel_and_on_the_general_kernels(K, F, N, dt):
+    """Two tokens: by default each launch of the block runs on the two-token kernel where it applies (gate|up: int8
+    weights with 2F > 4096; down: int8 weights), in the batched kernels' list format, so that the two
+    forms mix; SCAP_CFG_GENERAL_KERNEL keeps both launches on the general kernels.  Both against the oracle token by
+    token; z and the kept lists of the two must agree wherever the gate|up launch is the same kernel."""
+    blk = Block(K, F, N, dt, seed=2600 + K, std=0.02 if K > 2000 else 0.05, B=2)
+    xdt = F16 if dt == F16 else BF16
+    X = wl.laplace(8, K, 2601 + K, xdt, loc=0.1, scale=0.8)
+    rng = np.random.default_rng(2602 + K)
+    bg, bu, bd = (rng.standard_normal(n).astype(np.float32) * 0.05 for n in (F, F, N))
+    zs = np.abs(oracle.swiglu_block(blk.Wg, blk.Wu, blk.Wd, X[0], 0.1, 0.5, 0.0, 0.0, dt, xdt, b_gate=bg, b_up=bu,
+                                    gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd)["z"])
+    full = K * F > 1 << 24
+    cases = ((0.5, float(np.median(zs))),) if full else ((0.0, 0.0), (0.5, float(np.median(zs))), (1.1, float(np.quantile(zs, 0.9))), (0.5, 1e9), (1e9, 0.0))
+    for rep, (tau_x, tau_z) in enumerate(cases):
+        x = X[2 * (rep % 4):2 * (rep % 4) + 2]
+        say(f"two-token block K={K} F={F} N={N} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
+        a = blk.check_batch(x, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"two-token kernel tau_z={tau_z}")
+        g = blk.check_batch(x, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"general kernels tau_z={tau_z}",
+                            cfg=(0, 0, 0, 0, scap.CFG_GENERAL_KERNEL))
+        again = blk.run_batch(x, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd)
+        for b in range(2):
+            assert np.array_equal(a[b]["y"].view(np.uint32), again[b]["y"].view(np.uint32)), "not reproducible"
+            assert np.array_equal(a[b]["idx_z"], again[b]["idx_z"])
+            if dt != I8:  # the same gate|up kernel on both ways: the same z, the same lists
+                assert np.array_equal(a[b]["z"].view(np.uint32), g[b]["z"].view(np.uint32))
+                assert np.array_equal(a[b]["idx_z"], g[b]["idx_z"])
 
 
 # ------------------------------------------------------------------ degenerate cases
