@@ -111,10 +111,12 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     }
     if (lanes == 1) return launch_gemm_mfma(a, wdt, cfg, stream);
     // 2 tokens: the two-token form of the one-token kernel, unless the caller asks for a launch shape or the
-    // general kernels.  Measured against them (dense / 90 % sparse, us): 14336 x 4096 bf16 23.95 / 10.45 against
-    // 24.36 / 10.94, int8 15.82 / 9.51 against 17.60 / 10.60, 4096 x 4096 bf16 11.78 / 7.76 against 12.82 / 7.59; but
-    // 4096 x 14336 bf16 23.26 / 10.20 against 23.01 / 9.97: not for wide layers of 16-bit weights.
-    if (a.B == 2 && lanes == 0 && (wdt == kI8 || a.N <= 8192) &&
+    // general kernels.  Measured against them (dense / 90 % sparse, us), with the fixed-point hand-over: 14336 x 4096
+    // bf16 22.56 / 9.26 against 24.36 / 10.94, int8 14.68 / 8.53 against 17.60 / 10.60, 4096 x 4096 bf16 10.41 / 7.01
+    // against 12.82 / 7.59, 4096 x 14336 bf16 21.58 / 8.71 against 22.96 / 9.98.  With partial sums handed over
+    // instead (layers too wide for the fixed-point words) wide 16-bit layers were faster on the general kernel
+    // (23.26 / 10.20 against 23.01 / 9.97): those keep it.
+    if (a.B == 2 && lanes == 0 && (wdt == kI8 || a.N <= 8192 || 2 * (int64_t)a.N <= (int64_t)kFxCols) &&
         !(cfg && ((cfg->flags & SCAP_CFG_GENERAL_KERNEL) || cfg->waves_per_group || cfg->rows_per_group || cfg->unroll))) {
         const int rc = launch_gemv1b(a, wdt, cfg ? cfg->flags : 0, stream);
         if (rc != kG1NotApplicable) return rc;

@@ -134,6 +134,7 @@ int launch_gemv1b(const GemvArgs& g, int wdt, int flags, hipStream_t stream) {
     const int rc = plan_gemv1(g, wdt, 0, false, kG1bWaves, 8, b.bt, &pl);
     if (rc != SCAP_OK) return rc;
     b.a = args_of(g, pl, flags);
+    if ((size_t)2 * (size_t)g.N > (size_t)kFxCols) b.a.fx_acc = nullptr;  // one fixed-point word per (token, column)
     switch (wdt) {
         case kF16: return launch_gemv1b_wdt<kF16>(b, stream);
         case kBF16: return launch_gemv1b_wdt<kBF16>(b, stream);
@@ -190,16 +191,16 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int up
 // batched block kernels (64-channel segments, 2 token slots), so either can be paired with the general kernel's.
 //   part 0, the gate|up launch with the gating epilogue: int8 weights in 16-byte lanes (2F > 4096; a wavefront's
 //           slice is then 128 columns = one segment), input length a multiple of 8;
-//   part 1, the down launch reading the lists: int8 weights (with 16-bit weights the general kernel's down launch
-//           measured 0.5 us faster: 4096 -> 14336 -> 4096 bf16, two tokens, 55.8 against 56.3 us at 50 %).
-// Measured on that shape with int8 weights, both launches general / gate|up on the two-token kernel / both:
-// 45.9 / 45.0 / 43.4 us with nothing pruned, 38.4 / 36.9 / 36.1 at 50 %, 22.2 / 21.5 / 20.4 at 90 %.
+//   part 1, the down launch reading the lists: any weights, unless 16-bit and too wide for the fixed-point hand-over
+//           (with partial sums handed over the general kernel's down launch measured 0.5 us faster).
+// Measured on 4096 -> 14336 -> 4096, two tokens, both launches general / these (us): int8 45.8 / 41.9 with nothing
+// pruned, 38.0 / 34.5 at 50 %, 21.8 / 19.6 at 90 %; bf16 (down launch only) 65.3 / 64.3, 55.9 / 54.7, 25.9 / 24.8.
 // Returns SCAP_OK and fills *g, or kG1NotApplicable.
 static int plan_block2_part(const GemvArgs& up, const GemvArgs& dn, int wdt, int part, Gemv1bArgs* g, bool* i8_half) {
     if (up.B != 2) return kG1NotApplicable;
     const GemvArgs& src = part == 0 ? up : dn;
     if (part == 0 && (wdt != kI8 || (src.K % 8) != 0)) return kG1NotApplicable;
-    if (part == 1 && wdt != kI8) return kG1NotApplicable;
+    if (part == 1 && wdt != kI8 && 2 * (int64_t)src.N > (int64_t)kFxCols) return kG1NotApplicable;
     Plan1 pl;
     const int rc = plan_gemv1(src, wdt, 0, false, kG1bWaves, kWave, 2, &pl);  // whole 64-channel pieces: whole segments
     if (rc != SCAP_OK) return kG1NotApplicable;
@@ -208,6 +209,7 @@ static int plan_block2_part(const GemvArgs& up, const GemvArgs& dn, int wdt, int
     g->B = 2;
     g->bt = 2;
     g->a = args_of(src, pl, 0);
+    if (part == 0 || (size_t)2 * (size_t)src.N > (size_t)kFxCols) g->a.fx_acc = nullptr;
     g->a.m2 = up.m2;
     g->a.tau2 = up.tau2;
     g->a.zl_idx = up.zl_idx;

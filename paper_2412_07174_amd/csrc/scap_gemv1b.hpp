@@ -52,7 +52,8 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
                                                                 int32_t* counters, const uint16_t* col_scale,
                                                                 int32_t* idx_out, int32_t* nnz_out, int32_t* union_nnz_out,
                                                                 int32_t* seg_cnt, float m2, float tau2, float* z_out,
-                                                                int32_t* zl_idx, float* zl_d, int32_t* zl_cnt, int F) {
+                                                                int32_t* zl_idx, float* zl_d, int32_t* zl_cnt, int F,
+                                                                unsigned long long* fx_acc) {
     constexpr int WAVES = kG1bWaves;
     constexpr int UNROLL = WDT == kI8Half ? 8 : 4;
     constexpr int ELEMS = Vec<WDT>::kElems;
@@ -96,15 +97,20 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
             }
         }
     }
-    const int fcol = tile * TILE + w * SLICE + lane * CPL;
+    // Column c of this lane is fcol + c * CSTR: lanes side by side (every store and atomic of the hand-over then covers
+    // 64 consecutive words), except under the gating epilogue, which pairs gate and up columns through neighbouring
+    // lanes and keeps a lane's columns adjacent.
+    constexpr int CSTR = FUSE == kFuseSwiglu ? 1 : kWave;
+    constexpr int LSTR = FUSE == kFuseSwiglu ? CPL : 1;
+    const int fcol = tile * TILE + w * SLICE + lane * LSTR;
     float cbias[CPL], cscale[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         cbias[c] = 0.f;
         cscale[c] = 1.f;
-        if (fcol + c < N) {
-            if (bias) cbias[c] = bias[fcol + c];
-            if (IS_I8) cscale[c] = f16_bits_to_f32(col_scale[fcol + c]);
+        if (fcol + c * CSTR < N) {
+            if (bias) cbias[c] = bias[fcol + c * CSTR];
+            if (IS_I8) cscale[c] = f16_bits_to_f32(col_scale[fcol + c * CSTR]);
         }
     }
 
@@ -324,7 +330,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
 #pragma unroll
         for (int i = 0; i < WAVES; ++i) {
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) sum[b].v[c] += s_red[(i * BT + b) * TILE + w * SLICE + lane * CPL + c];
+            for (int c = 0; c < CPL; ++c) sum[b].v[c] += s_red[(i * BT + b) * TILE + w * SLICE + lane * LSTR + c * CSTR];
         }
     }
 
@@ -340,7 +346,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
             for (int b = 0; b < BT; ++b)
 #pragma unroll
                 for (int c = 0; c < CPL; ++c)
-                    if (b < B && fcol + c < N) store_dev(&y[(size_t)b * N + fcol + c], p[b][c]);
+                    if (b < B && fcol + c * CSTR < N) store_dev(&y[(size_t)b * N + fcol + c * CSTR], p[b][c]);
         } else {
             // Columns come in groups of 8: 4 gate pre-activations, then the 4 matching up pre-activations; a lane holds
             // 2 adjacent columns, so lanes 0-1 of every 4 hold a group's gate columns and fetch their up partners from
@@ -404,6 +410,98 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
     if (S == 1) {
         finish(sum);
         return;
+    }
+
+    // ------------------------------------------------------------------ 4a. split-K hand-over in fixed point
+    // As in the one-token kernel (scap_gemv1.hpp, 4a), one 64-bit word per (token, column): every arrival adds its
+    // partial, rounded to 2^-frac and biased, and a 1 in the arrival count with ONE atomic; whoever completes a
+    // column's count holds its sum, converts it once, applies scale and bias and stores y.  A partial that is not
+    // finite or not below 2^20 travels as fp32 through its partial-sum slot and the column's escape mask.
+    if constexpr (FUSE != kFuseSwiglu) {
+        if (fx_acc != nullptr) {
+            const int limit_bits = fx_limit_bits(S);
+            const int frac = limit_bits - kFxRangeBits;
+            const double to_fixed = __hiloint2double((1023 + frac) << 20, 0);    // 2^frac
+            const double from_fixed = __hiloint2double((1023 - frac) << 20, 0);  // 2^-frac
+            const unsigned long long fbias = 1ull << limit_bits;
+            unsigned long long* escw = fx_acc + kFxCols;
+            const uint32_t pstride = (uint32_t)T * B * TILE * 4u;
+            const uint32_t pmine = (uint32_t)((tile * B * TILE + w * SLICE + lane * CPL) * 4);
+            const uint32_t ptok = (uint32_t)TILE * 4u;
+            bool esc[BT][CPL];
+            bool any_esc = false;
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    esc[b][c] = b < B && fcol + c * CSTR < N && !(fabsf(sum[b].v[c]) < 1048576.f);  // also NaN and Inf
+                    any_esc |= esc[b][c];
+                }
+            if (__ballot(any_esc) != 0ull) {  // rare
+                const __amdgpu_buffer_rsrc_t pbuf = make_raw_buffer(partial, (uint32_t)S * T * B * TILE * 4u);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) {
+                    if (b < B) sum[b].store_coherent(pbuf, split * pstride + pmine + b * ptok);
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c)
+                        if (esc[b][c])
+                            __hip_atomic_fetch_or(&escw[(size_t)b * N + fcol + c * CSTR], 1ull << split, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                wait_memory_ops();  // values and mask bits are in place before the arrivals are counted
+            }
+            unsigned long long now_c[BT][CPL];  // all of the lane's atomics first, then what they returned
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    now_c[b][c] = 0ull;
+                    if (!(b < B && fcol + c * CSTR < N)) continue;
+                    const long long vfix = esc[b][c] ? 0ll : __double2ll_rn((double)sum[b].v[c] * to_fixed);
+                    const unsigned long long inc = (1ull << 57) | (esc[b][c] ? 1ull << 50 : 0ull) | (unsigned long long)(vfix + (long long)fbias);
+                    now_c[b][c] = __hip_atomic_fetch_add(&fx_acc[(size_t)b * N + fcol + c * CSTR], inc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + inc;
+                }
+#pragma unroll
+            for (int b = 0; b < BT; ++b)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) {
+                    const unsigned long long now = now_c[b][c];
+                    if ((int)(now >> 57) != S) continue;  // not the column's last arrival (or no column: count 0, S > 1)
+                    const long long total = (long long)(now & ((1ull << 50) - 1)) - (long long)S * (long long)fbias;
+                    float yv = (float)((double)total * from_fixed);
+                    const size_t word = (size_t)b * N + fcol + c * CSTR;
+                    if ((now >> 50) & 127ull) {  // escaped partials: add them in split order
+                        unsigned long long mask = load_dev(&escw[word]);
+                        const float* pcol = partial + (size_t)(tile * B + b) * TILE + w * SLICE + lane * CPL + c;
+                        while (mask) {
+                            const int sp = __builtin_ctzll(mask);
+                            mask &= mask - 1;
+                            yv += load_dev(pcol + (size_t)sp * T * B * TILE);
+                        }
+                        store_dev(&escw[word], 0ull);
+                    }
+                    yv = (IS_I8 ? yv * cscale[c] : yv) + cbias[c];
+                    store_dev(&y[word], yv);
+                    store_dev(&fx_acc[word], 0ull);  // zero at rest
+                }
+            if (!want_lists || S == 1) return;
+            // token w's list (tile 0, wavefront w < B) still needs the last of its writers to close the gaps: they
+            // stored their pieces and counts before taking this ticket
+            wait_memory_ops();
+            unsigned long long* lt = reinterpret_cast<unsigned long long*>(counters + w * kG1TicketWords);
+            unsigned long long got = 0;
+            if (lane == 0) got = __hip_atomic_fetch_add(lt, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1ull;
+            if (__builtin_amdgcn_readfirstlane((int)(uint32_t)got) != S) return;
+            if (lane == 0) store_dev(lt, 0ull);
+            const int run = close_list_rows(seg_cnt + (1 + w) * kMaxSplits, idx_out ? idx_out + (int64_t)w * K : nullptr, S, K, Kc, s_off, s_cnt);
+            if (lane == 0 && nnz_out) nnz_out[w] = run;
+            if (w == 0 && union_nnz_out) {
+                int u = 0;
+                for (int s0 = 0; s0 < S; s0 += kWave) u += s0 + lane < S ? load_dev(&seg_cnt[s0 + lane]) : 0;
+                u = wave_sum(u);
+                if (lane == 0) union_nnz_out[0] = u;
+            }
+            return;
+        }
     }
 
     // ------------------------------------------------------------------ 4. split-K hand-over per (tile, slice)
@@ -500,7 +598,8 @@ static int launch_gemv1b_one(const Gemv1bArgs& g, size_t lds, hipStream_t stream
     const dim3 grid((unsigned)(a.S * a.T)), block(kG1bWaves * kWave);
     hipLaunchKernelGGL((gemv1b_kernel<WDT, NCH, BT, FUSE>), grid, block, lds, stream, a.x, a.W, a.K, a.N, a.Kc, a.S, a.T, g.B,
                        a.mode, a.xdt, a.m, a.tau, a.flags, a.bias, a.y, a.partial, a.counters, a.col_scale, a.idx_out,
-                       a.nnz_out, a.union_nnz_out, a.seg_cnt, a.m2, a.tau2, a.z_out, a.zl_idx, a.zl_d, a.zl_cnt, a.F);
+                       a.nnz_out, a.union_nnz_out, a.seg_cnt, a.m2, a.tau2, a.z_out, a.zl_idx, a.zl_d, a.zl_cnt, a.F,
+                       FUSE == kFuseSwiglu ? nullptr : a.fx_acc);
     return hipGetLastError() == hipSuccess ? SCAP_OK : SCAP_ERR_HIP;
 }
 

@@ -317,40 +317,45 @@ def test_two_tokens_ties_nonfinite_and_one_empty_mask():
     assert np.array_equal(got["y"][0], bf) and np.array_equal(got["y"][1], bf)
 
 
-def test_fixed_point_hand_over_escapes():
+@pytest.mark.parametrize("B", [1, 2])
+def test_fixed_point_hand_over_escapes(B):
     """Partial sums the fixed-point hand-over cannot carry -- 2^20 or more in magnitude, infinite, NaN -- travel as
     fp32 beside it: columns whose partial sums are all huge, columns where only some splits escape, and
-    non-finite inputs, against the oracle at fp32 relative accuracy; the words are back at zero afterwards (an
-    ordinary call on the same workspace follows)."""
+    non-finite inputs, against the oracle at fp32 relative accuracy (one token: the one-token kernel; two: its
+    two-token form, the second token with sums that stay small); the words are back at zero afterwards (an ordinary
+    call on the same workspace follows)."""
     K, N = 4096, 1544
     rng = np.random.default_rng(421)
     Wf = rng.standard_normal((K, N)).astype(np.float32)
     Wf[:, ::3] *= 1024.0     # every third column: partial sums around 2^21, most of them escape, not all
     Wf[:512, 1::3] *= 512.0  # the next ones: only splits that cover the first channels can escape
     W = wl.encode(Wf, BF16)
-    layer = Layer(W, BF16, B=1)
+    layer = Layer(W, BF16, B=B)
     xs = (rng.standard_normal(K) * 300.0).astype(np.float32)
     for name, x in (("huge", xs), ("huge and non-finite", np.where(np.arange(K) == 77, np.inf, np.where(np.arange(K) == 3000, np.nan, xs)))):
-        xb = wl.encode(x.astype(np.float32), BF16)
+        x = x.astype(np.float32)
+        xb = wl.encode(x if B == 1 else np.stack([x, xs * 1e-3]), BF16).reshape(B, K)
         for tau in (0.0, 150.0):
-            say(f"escapes: {name} tau={tau}")
+            say(f"escapes: B={B} {name} tau={tau}")
             want = oracle.sparse_fc(W, xb, 0.0, tau, None, BF16, BF16)
             got = gpu_sparse_fc(layer, xb, BF16, 0.0, tau, None)
             ref = gpu_sparse_fc(layer, xb, BF16, 0.0, tau, None, cfg=(0, 0, 0, 0, scap.CFG_PARTIAL_SUMS))
-            assert np.array_equal(got["idx"][0], want["idx"][0])
-            wy, gy, ry = want["y"][0].astype(np.float64), got["y"][0].astype(np.float64), ref["y"][0].astype(np.float64)
-            assert np.array_equal(np.isnan(gy), np.isnan(wy)) and np.array_equal(np.isinf(gy), np.isinf(wy))
-            fin = np.isfinite(wy)
-            if fin.any():
-                assert np.abs(wy[fin]).max() > 2.0 ** 22  # the case is what it claims to be
-                tol = 1e-5 * np.abs(wy[fin]) + 1e-6 * np.abs(wy[fin]).max()  # fp32 sums of terms up to 2^22
-                assert np.all(np.abs(gy[fin] - wy[fin]) <= tol), (np.abs(gy[fin] - wy[fin]) / tol).max()
-                assert np.all(np.abs(ry[fin] - wy[fin]) <= tol)
+            for t in range(B):
+                assert np.array_equal(got["idx"][t], want["idx"][t])
+                wy, gy, ry = want["y"][t].astype(np.float64), got["y"][t].astype(np.float64), ref["y"][t].astype(np.float64)
+                assert np.array_equal(np.isnan(gy), np.isnan(wy)) and np.array_equal(np.isinf(gy), np.isinf(wy))
+                fin = np.isfinite(wy)
+                if fin.any() and np.abs(wy[fin]).max() > 0:
+                    if t == 0:
+                        assert np.abs(wy[fin]).max() > 2.0 ** 22  # the case is what it claims to be
+                    tol = 1e-5 * np.abs(wy[fin]) + 1e-6 * np.abs(wy[fin]).max()  # fp32 sums of terms up to 2^22
+                    assert np.all(np.abs(gy[fin] - wy[fin]) <= tol), (np.abs(gy[fin] - wy[fin]) / tol).max()
+                    assert np.all(np.abs(ry[fin] - wy[fin]) <= tol)
     say("an ordinary call afterwards")
     W2 = wl.weights(K, N, 422, BF16)
-    layer2 = Layer(W2, BF16, B=1)
+    layer2 = Layer(W2, BF16, B=B)
     layer2.ws = layer.ws
-    check_against_oracle(layer2, wl.laplace(1, K, 423, BF16, loc=0.1, scale=0.5)[0], BF16, 0.1, 0.3, None, what="after escapes")
+    check_against_oracle(layer2, wl.laplace(B, K, 423, BF16, loc=0.1, scale=0.5), BF16, 0.1, 0.3, None, what="after escapes")
 
 
 def test_rerun_is_bit_identical_and_workspace_is_reusable():

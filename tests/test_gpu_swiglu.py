@@ -289,7 +289,7 @@ def test_batched_blocks(B, dt):
                                       (4096, 14336, 4096, I8)])
 def test_two_token_block_on_the_two_token_kernel_and_on_the_general_kernels(K, F, N, dt):
     """Two tokens: by default each launch of the block runs on the two-token kernel where it applies (gate|up: int8
-    weights with 2F > 4096; down: int8 weights), in the batched kernels' list format, so that the two
+    weights with 2F > 4096; down: all weights), in the batched kernels' list format, so that the two
     forms mix; SCAP_CFG_GENERAL_KERNEL keeps both launches on the general kernels.  Both against the oracle token by
     token; z and the kept lists of the two must agree wherever the gate|up launch is the same kernel."""
     blk = Block(K, F, N, dt, seed=2600 + K, std=0.02 if K > 2000 else 0.05, B=2)
