@@ -47,15 +47,27 @@ __global__ __launch_bounds__(kHistThreads) void code_hist_kernel(const uint16_t*
     };
     const int64_t nvec = M / 8;
     const uint4* __restrict__ X8 = reinterpret_cast<const uint4*>(X);
-    for (int64_t i = (int64_t)chunk * kHistThreads + tid; i < nvec; i += (int64_t)nchunk * kHistThreads) {
-        const uint4 v = X8[i];
+    auto count8 = [&](const uint4& v) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             count(w[q] & 0xFFFFu);
             count(w[q] >> 16);
         }
+    };
+    // four loads in flight per lane: with 16 wavefronts per compute unit (the counters fill LDS) one load per lane
+    // leaves the memory latency exposed
+    constexpr int FLY = 4;
+    const int64_t stride = (int64_t)nchunk * kHistThreads;
+    int64_t i = (int64_t)chunk * kHistThreads + tid;
+    for (; i + (FLY - 1) * stride < nvec; i += FLY * stride) {
+        uint4 v[FLY];
+#pragma unroll
+        for (int u = 0; u < FLY; ++u) v[u] = X8[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < FLY; ++u) count8(v[u]);
     }
+    for (; i < nvec; i += stride) count8(X8[i]);
     if (chunk == 0) {
         const int64_t j = nvec * 8 + tid;  // the last M % 8 codes
         if (j < M) count(X[j]);
