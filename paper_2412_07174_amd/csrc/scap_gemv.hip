@@ -116,7 +116,14 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     // against 12.82 / 7.59, 4096 x 14336 bf16 21.58 / 8.71 against 22.96 / 9.98.  With partial sums handed over
     // instead (layers too wide for the fixed-point words) wide 16-bit layers were faster on the general kernel
     // (23.26 / 10.20 against 23.01 / 9.97): those keep it.
-    if (a.B == 2 && lanes == 0 && (wdt == kI8 || a.N <= 8192 || 2 * (int64_t)a.N <= (int64_t)kFxCols) &&
+    // 3-4 tokens, 16-bit weights: its four-slot form (fixed-point hand-over only).  Measured against the kernels below
+    // (dense / 50 / 90 %, us): 4 tokens 4096 x 14336 bf16 24.4 / 23.0 / 13.4 against 26.1 / 24.9 / 14.8, 4096 x 6144
+    // 15.2 / 14.5 / 10.5 against 18.1 / 17.2 / 12.4, 14336 x 4096 25.5 / 24.6 / 14.9 against 24.7 / 25.5 / 15.6 -- so a
+    // dense call with a long input into a narrow layer stays on the staged-tile kernel.
+    const bool four_slots = (a.B == 3 || a.B == 4) && wdt != kI8 &&
+                            !(a.mode == kModeDense && (int64_t)a.K >= 2 * (int64_t)a.N);
+    if ((a.B == 2 || four_slots) && lanes == 0 &&
+        (wdt == kI8 || a.N <= 8192 || 2 * (int64_t)a.N <= (int64_t)kFxCols) &&
         !(cfg && ((cfg->flags & SCAP_CFG_GENERAL_KERNEL) || cfg->waves_per_group || cfg->rows_per_group || cfg->unroll))) {
         const int rc = launch_gemv1b(a, wdt, cfg ? cfg->flags : 0, stream);
         if (rc != kG1NotApplicable) return rc;

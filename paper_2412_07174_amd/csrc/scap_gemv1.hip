@@ -44,7 +44,7 @@ int plan_gemv1(const GemvArgs& g, int wdt, int kc, bool kc_forced, int waves, in
     out->tile = kWave * out->elems;
     GemvArgs p = g;
     // LDS: header, the wavefronts' sums, then 8 bytes per listed channel (16 with 2 token slots)
-    const int entry = bt == 1 ? 8 : 16;
+    const int entry = bt == 1 ? 8 : (bt == 2 ? 16 : 32);
     const size_t lds_budget = bt == 1 ? 64 * 1024 - (size_t)waves * out->tile * 4 - 64 + (kHdrBytes - kG1HdrBytes)
                                       : (size_t)kG1bMaxLds - (size_t)bt * kG1HdrBytes - (size_t)kG1bWaves * bt * out->tile * 4 -
                                             (size_t)kG1bWaves * 4 * entry + kHdrBytes;
@@ -122,19 +122,23 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
     return SCAP_ERR_DTYPE;
 }
 
-// Two tokens through the two-token form of the one-token kernel (sparse or dense mode).  Returns a scap_status, or
-// kG1NotApplicable: another token count, bias folding, an input length that is not a multiple of 8 (the second
-// token's row would not be 16-byte aligned) or more than 2048 channels per workgroup.  flags as for launch_gemv1.
+// Two tokens, or three to four with 16-bit weights, through the two- / four-slot form of the one-token kernel (sparse
+// or dense mode).  Returns a scap_status, or kG1NotApplicable: another token count, bias folding, an input length
+// that is not a multiple of 8 (the later tokens' rows would not be 16-byte aligned), more than 2048 channels per
+// workgroup, or four slots without the fixed-point hand-over.  flags as for launch_gemv1.
 int launch_gemv1b(const GemvArgs& g, int wdt, int flags, hipStream_t stream) {
-    if (g.B != 2 || g.mode == kModeFold || (g.K % 8) != 0) return kG1NotApplicable;
+    if (g.B < 2 || g.B > 4 || g.mode == kModeFold || (g.K % 8) != 0) return kG1NotApplicable;
+    if (g.B > 2 && wdt == kI8) return kG1NotApplicable;  // four token slots: 16-bit weights only
     Gemv1bArgs b;
     b.B = g.B;
-    b.bt = 2;
+    b.bt = g.B == 2 ? 2 : 4;
     Plan1 pl;
     const int rc = plan_gemv1(g, wdt, 0, false, kG1bWaves, 8, b.bt, &pl);
     if (rc != SCAP_OK) return rc;
     b.a = args_of(g, pl, flags);
-    if ((size_t)2 * (size_t)g.N > (size_t)kFxCols) b.a.fx_acc = nullptr;  // one fixed-point word per (token, column)
+    if ((size_t)g.B * (size_t)g.N > (size_t)kFxCols) b.a.fx_acc = nullptr;  // one fixed-point word per (token, column)
+    // with four slots the partial-sum hand-over loses to the other kernels (its last arrivals fetch 4 S slices)
+    if (b.bt == 4 && b.a.fx_acc == nullptr) return kG1NotApplicable;
     switch (wdt) {
         case kF16: return launch_gemv1b_wdt<kF16>(b, stream);
         case kBF16: return launch_gemv1b_wdt<kBF16>(b, stream);

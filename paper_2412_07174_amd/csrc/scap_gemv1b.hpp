@@ -8,9 +8,10 @@
 // (scap_gemv_parts.hpp, "list input"; 2 token slots): kFuseSwiglu -- the wavefront that finishes a (tile, slice) of the
 // gate|up launch gates it (16-byte int8 lanes only: its slice is 128 columns = one 64-channel list segment) --, and
 // kFuseList -- the down launch takes its channels and centred values from those segments instead of x.
-// Only BT = 2 is built.  The kernel's fixed part grows with the token slots -- the last arrival of a tile pulls
-// S x BT partial slices through one compute unit's L1 (14336 x 4096 bf16: 0.9 us for one token, 2.1 for two, 3.8
-// for four) -- and with four slots it lost to the matrix-core kernels (28.1 against 24.6 us dense).
+// BT = 2 token slots, and 4 for plain calls with 16-bit weights (3-4 tokens).  With the partial-sum hand-over the
+// kernel's fixed part grows with the token slots -- the last arrival of a tile pulls S x BT partial slices through one
+// compute unit's L1 (14336 x 4096 bf16: 0.9 us for one token, 2.1 for two, 3.8 for four); the fixed-point hand-over
+// has nothing to pull.
 #pragma once
 
 #include <atomic>
@@ -38,11 +39,28 @@ template <> struct G1bList<2> {
         d[1] = __int_as_float(t.z);
     }
 };
+template <> struct G1bList<4> {  // two 16-byte halves per entry
+    int4* e;
+    static constexpr int kBytes = 32;
+    __device__ __forceinline__ G1bList(char* base, int w, int slots) : e(reinterpret_cast<int4*>(base) + 2 * w * slots) {}
+    __device__ __forceinline__ void put(int p, int idx, const float* d) const {
+        e[2 * p] = make_int4(idx, __float_as_int(d[0]), __float_as_int(d[1]), __float_as_int(d[2]));
+        e[2 * p + 1] = make_int4(__float_as_int(d[3]), 0, 0, 0);
+    }
+    __device__ __forceinline__ void get(int p, int& idx, float* d) const {
+        const int4 t = e[2 * p], u = e[2 * p + 1];
+        idx = t.x;
+        d[0] = __int_as_float(t.y);
+        d[1] = __int_as_float(t.z);
+        d[2] = __int_as_float(t.w);
+        d[3] = __int_as_float(u.x);
+    }
+};
 // list slots per wavefront: a multiple of 4, so that the 16-byte parts of the lists stay aligned
 __host__ __device__ inline int g1b_slots(int Kc) { return (Kc / kG1bWaves + 4) & ~3; }
 
 inline size_t gemv1b_lds_bytes(int tile_cols, int Kc, int bt) {
-    return (size_t)kG1HdrBytes * bt + (size_t)kG1bWaves * bt * tile_cols * 4 + (size_t)kG1bWaves * g1b_slots(Kc) * 16;
+    return (size_t)kG1HdrBytes * bt + (size_t)kG1bWaves * bt * tile_cols * 4 + (size_t)kG1bWaves * g1b_slots(Kc) * (bt == 2 ? 16 : 32);
 }
 
 template <int WDT, int NCH, int BT, int FUSE = kFusePlain>
@@ -62,7 +80,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
     constexpr int CPL = ELEMS / WAVES;  // columns per lane of a wavefront's slice
     constexpr int SLICE = kWave * CPL;
     static_assert(CPL == 1 || CPL == 2, "a slice is 4 or 8 bytes per lane");
-    static_assert(BT == 2, "two token slots");
+    static_assert(BT == 2 || (BT == 4 && FUSE == kFusePlain), "two token slots; four for plain calls");
     static_assert(FUSE != kFuseSwiglu || CPL == 2, "the gating epilogue needs a slice of 128 columns: one 64-channel list segment");
     typedef SliceVec<CPL> slice_t;
 
@@ -77,6 +95,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
     float* s_red = reinterpret_cast<float*>(smem + BT * kG1HdrBytes);  // [WAVES][BT][TILE]
     const int slots = g1b_slots(Kc);
     const G1bList<BT> mylist(smem + BT * kG1HdrBytes + WAVES * BT * TILE * 4, w, slots);
+    static_assert(G1bList<BT>::kBytes == (BT == 2 ? 16 : 32), "entry size assumed by gemv1b_lds_bytes");
 
     const int tile = blockIdx.x % T;
     const int split = blockIdx.x / T;
@@ -617,6 +636,9 @@ static int launch_gemv1b_nch(const Gemv1bArgs& g, hipStream_t stream) {
 template <int WDT>
 int launch_gemv1b_wdt(const Gemv1bArgs& g, hipStream_t stream) {
     if (g.bt == 2) return launch_gemv1b_nch<WDT, 2, kFusePlain>(g, stream);
+    if constexpr (WDT == kF16 || WDT == kBF16) {  // four slots: 16-bit weights only (int8 batches go to the matrix cores)
+        if (g.bt == 4) return launch_gemv1b_nch<WDT, 4, kFusePlain>(g, stream);
+    }
     return SCAP_ERR_CONFIG;
 }
 

@@ -158,9 +158,9 @@ FEW_TOKENS = [
 @pytest.mark.parametrize("B", [2, 3, 4])
 @pytest.mark.parametrize("K,N,dt", FEW_TOKENS)
 def test_few_tokens_kernel_shapes_and_both_hand_overs(K, N, dt, B):
-    """2 tokens on the two-token form of the one-token kernel (the library's choice when the input length is a
-    multiple of 8 and the layer is not a wide one of 16-bit weights), 3 and 4 tokens on whatever the library picks
-    for these shapes: against the oracle token by token -- y, every token's list and count, the union count --,
+    """2 tokens on the two-token form of the one-token kernel, 3 and 4 tokens on its four-slot form (16-bit weights,
+    input length a multiple of 8) or on whatever else the library picks for these shapes: against the oracle token by
+    token -- y, every token's list and count, the union count --,
     with the kernel's default hand-over (repeatable bit for bit), and with ordinary and with device-coherent loads of
     the partial sums against each other bit for bit, and dense mode, on repeated calls with changing inputs through
     one workspace."""
@@ -317,13 +317,13 @@ def test_two_tokens_ties_nonfinite_and_one_empty_mask():
     assert np.array_equal(got["y"][0], bf) and np.array_equal(got["y"][1], bf)
 
 
-@pytest.mark.parametrize("B", [1, 2])
+@pytest.mark.parametrize("B", [1, 2, 3, 4])
 def test_fixed_point_hand_over_escapes(B):
     """Partial sums the fixed-point hand-over cannot carry -- 2^20 or more in magnitude, infinite, NaN -- travel as
     fp32 beside it: columns whose partial sums are all huge, columns where only some splits escape, and
-    non-finite inputs, against the oracle at fp32 relative accuracy (one token: the one-token kernel; two: its
-    two-token form, the second token with sums that stay small); the words are back at zero afterwards (an ordinary
-    call on the same workspace follows)."""
+    non-finite inputs, against the oracle at fp32 relative accuracy (one token: the one-token kernel; two to four: its
+    two- and four-slot forms, the second token with sums that stay small); the words are back at zero afterwards (an
+    ordinary call on the same workspace follows)."""
     K, N = 4096, 1544
     rng = np.random.default_rng(421)
     Wf = rng.standard_normal((K, N)).astype(np.float32)
@@ -334,7 +334,7 @@ def test_fixed_point_hand_over_escapes(B):
     xs = (rng.standard_normal(K) * 300.0).astype(np.float32)
     for name, x in (("huge", xs), ("huge and non-finite", np.where(np.arange(K) == 77, np.inf, np.where(np.arange(K) == 3000, np.nan, xs)))):
         x = x.astype(np.float32)
-        xb = wl.encode(x if B == 1 else np.stack([x, xs * 1e-3]), BF16).reshape(B, K)
+        xb = wl.encode(np.stack([x, xs * 1e-3, xs * 0.5, -xs][:B]), BF16).reshape(B, K)
         for tau in (0.0, 150.0):
             say(f"escapes: B={B} {name} tau={tau}")
             want = oracle.sparse_fc(W, xb, 0.0, tau, None, BF16, BF16)
