@@ -264,8 +264,8 @@ int scap_swiglu_block(const void* W_gu, const void* gu_scale, const void* W_down
                       void* stream);
 
 /* Same as scap_swiglu_block with launch flags for its one-token form (cfg may be NULL): of cfg only the flags
- * SCAP_CFG_PARTIAL_SUMS and SCAP_CFG_PARK_SLICES (B == 1) and SCAP_CFG_GENERAL_KERNEL (B <= 2: both launches on the
- * general kernels instead of the one-token / two-token kernel) are read.  For tests and measurements. */
+ * SCAP_CFG_PARTIAL_SUMS and SCAP_CFG_PARK_SLICES (B == 1) and SCAP_CFG_GENERAL_KERNEL (B <= 4: both launches on the
+ * general kernels instead of the one-token kernel and its two- and four-slot forms) are read.  For tests and measurements. */
 int scap_swiglu_block_ex(const void* W_gu, const void* gu_scale, const void* W_down, const void* down_scale, int64_t K,
                          int64_t F, int64_t N, int wdt, const void* x, int xdt, int64_t B, float m_x, float tau_x,
                          const float* b_gu_fused, float m_z, float tau_z, const float* b_down_fused, float* y,

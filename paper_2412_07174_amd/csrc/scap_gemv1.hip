@@ -201,19 +201,23 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int up
 // pruned, 38.0 / 34.5 at 50 %, 21.8 / 19.6 at 90 %; bf16 (down launch only) 65.3 / 64.3, 55.9 / 54.7, 25.9 / 24.8.
 // Returns SCAP_OK and fills *g, or kG1NotApplicable.
 static int plan_block2_part(const GemvArgs& up, const GemvArgs& dn, int wdt, int part, Gemv1bArgs* g, bool* i8_half) {
-    if (up.B != 2) return kG1NotApplicable;
+    // 3-4 tokens: the down launch only, 16-bit weights, on the four-slot form (the lists then carry 4 token slots)
+    const bool four = (up.B == 3 || up.B == 4) && part == 1 && wdt != kI8;
+    if (up.B != 2 && !four) return kG1NotApplicable;
     const GemvArgs& src = part == 0 ? up : dn;
     if (part == 0 && (wdt != kI8 || (src.K % 8) != 0)) return kG1NotApplicable;
-    if (part == 1 && wdt != kI8 && 2 * (int64_t)src.N > (int64_t)kFxCols) return kG1NotApplicable;
+    if (part == 1 && wdt != kI8 && (int64_t)up.B * (int64_t)src.N > (int64_t)kFxCols) return kG1NotApplicable;
     Plan1 pl;
-    const int rc = plan_gemv1(src, wdt, 0, false, kG1bWaves, kWave, 2, &pl);  // whole 64-channel pieces: whole segments
+    const int rc = plan_gemv1(src, wdt, 0, false, kG1bWaves, kWave, four ? 4 : 2, &pl);  // whole 64-channel pieces: whole segments
     if (rc != SCAP_OK) return kG1NotApplicable;
+    if (four && pl.Kc > 2 * kG1Chunk) return kG1NotApplicable;  // (its prologue holds every entry slot in registers)
     if (part == 0 && pl.i8_half) return kG1NotApplicable;
     if (part == 1 && (pl.Kc % kWave) != 0) return kG1NotApplicable;
-    g->B = 2;
-    g->bt = 2;
+    g->B = (int)up.B;
+    g->bt = four ? 4 : 2;
     g->a = args_of(src, pl, 0);
-    if (part == 0 || (size_t)2 * (size_t)src.N > (size_t)kFxCols) g->a.fx_acc = nullptr;
+    if (part == 0 || (size_t)up.B * (size_t)src.N > (size_t)kFxCols) g->a.fx_acc = nullptr;
+    if (four && g->a.fx_acc == nullptr) return kG1NotApplicable;  // four slots: fixed-point hand-over only
     g->a.m2 = up.m2;
     g->a.tau2 = up.tau2;
     g->a.zl_idx = up.zl_idx;

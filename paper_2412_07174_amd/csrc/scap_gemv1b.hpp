@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
     constexpr int CPL = ELEMS / WAVES;  // columns per lane of a wavefront's slice
     constexpr int SLICE = kWave * CPL;
     static_assert(CPL == 1 || CPL == 2, "a slice is 4 or 8 bytes per lane");
-    static_assert(BT == 2 || (BT == 4 && FUSE == kFusePlain), "two token slots; four for plain calls");
+    static_assert(BT == 2 || (BT == 4 && FUSE != kFuseSwiglu), "two token slots; four without the gating epilogue");
     static_assert(FUSE != kFuseSwiglu || CPL == 2, "the gating epilogue needs a slice of 128 columns: one 64-channel list segment");
     typedef SliceVec<CPL> slice_t;
 
@@ -152,13 +152,15 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
 #pragma unroll
         for (int it = 0; it < ITS; ++it) {
             eidx[it] = 0;
-            ed[it][0] = ed[it][1] = 0.f;
+#pragma unroll
+            for (int b = 0; b < BT; ++b) ed[it][b] = 0.f;
             if (it < nsegw) {
                 const int64_t e = (int64_t)(seg0 + it) * kWave + lane;
                 eidx[it] = zl_idx[e];
-                const float2 dv = *reinterpret_cast<const float2*>(zl_d + e * BT);
-                ed[it][0] = dv.x;
-                ed[it][1] = dv.y;
+                typedef float dvec_t __attribute__((ext_vector_type(BT)));
+                const dvec_t dv = *reinterpret_cast<const dvec_t*>(zl_d + e * BT);
+#pragma unroll
+                for (int b = 0; b < BT; ++b) ed[it][b] = dv[b];
             }
         }
         int c_l = lane < nsegw ? zl_cnt[seg0 + lane] : 0;
@@ -188,7 +190,11 @@ __global__ __launch_bounds__(kG1bWaves * kWave) void gemv1b_kernel(const uint16_
             int run = 0;
 #pragma unroll
             for (int it = 0; it < ITS; ++it) {
-                const bool mine = pos[it] >= 0 && (w == 0 ? ed[it][0] : ed[it][1]) != 0.f;
+                float dw = 0.f;  // token w's value of the entry
+#pragma unroll
+                for (int b = 0; b < BT; ++b)
+                    if (w == b) dw = ed[it][b];
+                const bool mine = pos[it] >= 0 && dw != 0.f;
                 const uint64_t bal = __ballot(mine);
                 if (mine && idx_out) idx_out[(int64_t)w * K + before + run + lanes_below(bal)] = eidx[it];
                 run += __popcll(bal);
@@ -645,6 +651,9 @@ int launch_gemv1b_wdt(const Gemv1bArgs& g, hipStream_t stream) {
 // the two launches of the fused block of two tokens (fuse: kFuseSwiglu -- 16-byte int8 lanes only -- or kFuseList)
 template <int WDT>
 int launch_gemv1b_block_wdt(const Gemv1bArgs& g, int fuse, hipStream_t stream) {
+    if constexpr (WDT == kF16 || WDT == kBF16) {  // four slots: the down launch of a 16-bit block of 3-4 tokens
+        if (g.bt == 4 && fuse == kFuseList) return launch_gemv1b_nch<WDT, 4, kFuseList>(g, stream);
+    }
     if (g.bt != 2) return SCAP_ERR_CONFIG;
     if (fuse == kFuseList) return launch_gemv1b_nch<WDT, 2, kFuseList>(g, stream);
     if constexpr (WDT == kI8) {

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_down_kernel(const G
 template <int WDT, int BT>
 static int launch_block(GemvArgs up, GemvArgs dn, int wdt, int flags, hipStream_t stream) {
     const GemvArgs up_in = up, dn_in = dn;
-    const bool two = BT == 2 && up.B == 2 && !(flags & SCAP_CFG_GENERAL_KERNEL);
+    const bool two = (BT == 2 || BT == 4) && up.B >= 2 && !(flags & SCAP_CFG_GENERAL_KERNEL);
     const bool up_two = two && swiglu_block2_part_applies(up_in, dn_in, wdt, 0);
     const bool dn_two = two && swiglu_block2_part_applies(up_in, dn_in, wdt, 1);
     constexpr int TILE = kWave * Vec<WDT>::kElems;

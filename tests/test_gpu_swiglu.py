@@ -281,7 +281,14 @@ def test_batched_blocks(B, dt):
                                     gate_scale=blk.sg, up_scale=blk.su, down_scale=blk.sd)["z"])
     for tau_x, tau_z in ((0.0, 0.0), (0.5, float(np.median(zs))), (1.1, float(np.quantile(zs, 0.9))), (0.5, 1e9)):
         say(f"batched block B={B} dt={dt} tau_x={tau_x} tau_z={tau_z:.4g}")
-        blk.check_batch(X, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"B={B} dt={dt} tau_z={tau_z}")
+        a = blk.check_batch(X, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"B={B} dt={dt} tau_z={tau_z}")
+        if B <= 4:  # 2-4 tokens: launches that run on the two- / four-slot kernel by default, and the general kernels
+            g = blk.check_batch(X, xdt, 0.1, tau_x, bg, bu, 0.002, tau_z, bd, f"general kernels B={B} dt={dt} tau_z={tau_z}",
+                                cfg=(0, 0, 0, 0, scap.CFG_GENERAL_KERNEL))
+            if dt != I8:  # the same gate|up kernel on both ways: the same z, the same lists
+                for b in range(B):
+                    assert np.array_equal(a[b]["z"].view(np.uint32), g[b]["z"].view(np.uint32))
+                    assert np.array_equal(a[b]["idx_z"], g[b]["idx_z"])
 
 
 @pytest.mark.parametrize("K,F,N,dt", [(1000, 2056, 1040, I8), (4096, 6144, 2080, I8), (520, 1032, 2064, I8), (256, 8, 16, I8),
