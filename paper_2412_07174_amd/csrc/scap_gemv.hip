@@ -119,8 +119,10 @@ int launch_gemv(const GemvArgs& a_in, int wdt, const scap_launch_cfg* cfg, hipSt
     // 3-4 tokens, 16-bit weights: its four-slot form (fixed-point hand-over only).  Measured against the kernels below
     // (dense / 50 / 90 %, us): 4 tokens 4096 x 14336 bf16 24.4 / 23.0 / 13.4 against 26.1 / 24.9 / 14.8, 4096 x 6144
     // 15.2 / 14.5 / 10.5 against 18.1 / 17.2 / 12.4, 14336 x 4096 25.5 / 24.6 / 14.9 against 24.7 / 25.5 / 15.6 -- so a
-    // dense call with a long input into a narrow layer stays on the staged-tile kernel.
-    const bool four_slots = (a.B == 3 || a.B == 4) && wdt != kI8 &&
+    // dense call with a long input into a narrow layer stays on the staged-tile kernel.  int8 weights in 8-byte lanes
+    // (N <= 4096; wider int8 layers do not fit and fall through to the matrix cores): 14336 x 4096, 4 tokens,
+    // 19.7 / 17.7 / 12.9 at 50 / 70 / 90 % against 19.9 / 18.3 / 14.0, 3 tokens 18.1 / 15.8 / 11.9 against 19.1 / 17.0 / 12.9.
+    const bool four_slots = (a.B == 3 || a.B == 4) &&
                             !(a.mode == kModeDense && (int64_t)a.K >= 2 * (int64_t)a.N);
     if ((a.B == 2 || four_slots) && lanes == 0 &&
         (wdt == kI8 || a.N <= 8192 || 2 * (int64_t)a.N <= (int64_t)kFxCols) &&

@@ -45,9 +45,12 @@ int plan_gemv1(const GemvArgs& g, int wdt, int kc, bool kc_forced, int waves, in
     GemvArgs p = g;
     // LDS: header, the wavefronts' sums, then 8 bytes per listed channel (16 with 2 token slots)
     const int entry = bt == 1 ? 8 : (bt == 2 ? 16 : 32);
-    const size_t lds_budget = bt == 1 ? 64 * 1024 - (size_t)waves * out->tile * 4 - 64 + (kHdrBytes - kG1HdrBytes)
-                                      : (size_t)kG1bMaxLds - (size_t)bt * kG1HdrBytes - (size_t)kG1bWaves * bt * out->tile * 4 -
-                                            (size_t)kG1bWaves * 4 * entry + kHdrBytes;
+    const int64_t fixed_lds = bt == 1 ? (int64_t)waves * out->tile * 4 + 64 + kG1HdrBytes
+                                      : (int64_t)bt * kG1HdrBytes + (int64_t)kG1bWaves * bt * out->tile * 4 + (int64_t)kG1bWaves * 4 * entry;
+    const int64_t lds_max = bt == 1 ? 64 * 1024 : kG1bMaxLds;
+    // (four slots of 1024-column tiles: the wavefronts' sums alone would fill LDS)
+    if (fixed_lds + (int64_t)kWave * (4 + entry) > lds_max) return kG1NotApplicable;
+    const size_t lds_budget = (size_t)(lds_max - fixed_lds) + kHdrBytes;
     // Rows per workgroup in multiples of 64, unless the input is so short that 64-row pieces would leave compute
     // units without a workgroup (1024 x 4096: 16 splits x 8 tiles; with 32-row pieces 8.5 -> 6.5 us dense)
     p.T = (p.N + out->tile - 1) / out->tile;
@@ -122,13 +125,13 @@ int launch_gemv1(const GemvArgs& g, int wdt, const scap_launch_cfg* cfg, hipStre
     return SCAP_ERR_DTYPE;
 }
 
-// Two tokens, or three to four with 16-bit weights, through the two- / four-slot form of the one-token kernel (sparse
-// or dense mode).  Returns a scap_status, or kG1NotApplicable: another token count, bias folding, an input length
+// Two tokens, or three to four (16-bit weights; int8 where N <= 4096, i.e. 8-byte lanes), through the two- /
+// four-slot form of the one-token kernel (sparse or dense mode).  Returns a scap_status, or kG1NotApplicable: another token count, bias folding, an input length
 // that is not a multiple of 8 (the later tokens' rows would not be 16-byte aligned), more than 2048 channels per
 // workgroup, or four slots without the fixed-point hand-over.  flags as for launch_gemv1.
 int launch_gemv1b(const GemvArgs& g, int wdt, int flags, hipStream_t stream) {
     if (g.B < 2 || g.B > 4 || g.mode == kModeFold || (g.K % 8) != 0) return kG1NotApplicable;
-    if (g.B > 2 && wdt == kI8) return kG1NotApplicable;  // four token slots: 16-bit weights only
+
     Gemv1bArgs b;
     b.B = g.B;
     b.bt = g.B == 2 ? 2 : 4;

@@ -8,7 +8,7 @@
 // (scap_gemv_parts.hpp, "list input"; 2 token slots): kFuseSwiglu -- the wavefront that finishes a (tile, slice) of the
 // gate|up launch gates it (16-byte int8 lanes only: its slice is 128 columns = one 64-channel list segment) --, and
 // kFuseList -- the down launch takes its channels and centred values from those segments instead of x.
-// BT = 2 token slots, and 4 for plain calls with 16-bit weights (3-4 tokens).  With the partial-sum hand-over the
+// BT = 2 token slots, and 4 (3-4 tokens) for 16-bit weights and for plain calls with int8 weights in 8-byte lanes.  With the partial-sum hand-over the
 // kernel's fixed part grows with the token slots -- the last arrival of a tile pulls S x BT partial slices through one
 // compute unit's L1 (14336 x 4096 bf16: 0.9 us for one token, 2.1 for two, 3.8 for four); the fixed-point hand-over
 // has nothing to pull.
@@ -642,7 +642,9 @@ static int launch_gemv1b_nch(const Gemv1bArgs& g, hipStream_t stream) {
 template <int WDT>
 int launch_gemv1b_wdt(const Gemv1bArgs& g, hipStream_t stream) {
     if (g.bt == 2) return launch_gemv1b_nch<WDT, 2, kFusePlain>(g, stream);
-    if constexpr (WDT == kF16 || WDT == kBF16) {  // four slots: 16-bit weights only (int8 batches go to the matrix cores)
+    // four slots: 16-bit weights and int8 in 8-byte lanes (with 16-byte int8 lanes the wavefronts' sums of four tokens
+    // do not fit LDS; those batches go to the matrix cores)
+    if constexpr (WDT == kF16 || WDT == kBF16 || WDT == kI8Half) {
         if (g.bt == 4) return launch_gemv1b_nch<WDT, 4, kFusePlain>(g, stream);
     }
     return SCAP_ERR_CONFIG;
