@@ -1,17 +1,17 @@
-// Two tokens through the structure of the one-token kernel (scap_gemv1.hpp): the rows read are the union of the
-// tokens' masks (Appendix C), every row read once and multiplied into one accumulator set per token, a token that
+// Two to four tokens through the structure of the one-token kernel (scap_gemv1.hpp): the rows read are the union of
+// the tokens' masks (Appendix C), every row read once and multiplied into one accumulator set per token, a token that
 // pruned the channel contributing a zero (Eq. 3 per token).  Same four stages -- every wavefront tests all of the
 // workgroup's inputs and keeps every 8th union position, the ring of row loads, one barrier and the slice-wise
-// reduction, the ticketed split-K hand-over per (tile, slice) -- with BT token slots.  Wavefront b of a tile-0
-// workgroup writes token b's ascending list; the last arrival of (tile 0, slice b) closes it.
+// reduction, the split-K hand-over (fixed point by default, else ticketed partial sums per (tile, slice)) -- with BT
+// token slots.  Wavefront b of a tile-0 workgroup writes token b's ascending list; the last of its writers closes it.
 // FUSE gives it the two halves of the fused SwiGLU block (Alg. 2) in the list format of the batched block kernels
-// (scap_gemv_parts.hpp, "list input"; 2 token slots): kFuseSwiglu -- the wavefront that finishes a (tile, slice) of the
+// (scap_gemv_parts.hpp, "list input"): kFuseSwiglu (2 slots) -- the wavefront that finishes a (tile, slice) of the
 // gate|up launch gates it (16-byte int8 lanes only: its slice is 128 columns = one 64-channel list segment) --, and
-// kFuseList -- the down launch takes its channels and centred values from those segments instead of x.
-// BT = 2 token slots, and 4 (3-4 tokens) for 16-bit weights and for plain calls with int8 weights in 8-byte lanes.  With the partial-sum hand-over the
-// kernel's fixed part grows with the token slots -- the last arrival of a tile pulls S x BT partial slices through one
-// compute unit's L1 (14336 x 4096 bf16: 0.9 us for one token, 2.1 for two, 3.8 for four); the fixed-point hand-over
-// has nothing to pull.
+// kFuseList (2 or 4 slots) -- the down launch takes its channels and centred values from those segments instead of x.
+// BT = 2 token slots, and 4 (3-4 tokens) for 16-bit weights and for plain calls with int8 weights in 8-byte lanes.
+// With the partial-sum hand-over the kernel's fixed part grows with the token slots -- the last arrival of a tile
+// pulls S x BT partial slices through one compute unit's L1 (14336 x 4096 bf16: 0.9 us for one token, 2.1 for two,
+// 3.8 for four); the fixed-point hand-over has nothing to pull, and four slots run with it only.
 #pragma once
 
 #include <atomic>
