@@ -86,8 +86,8 @@ typedef struct {
     int32_t flags;           /* bit 0 (SCAP_CFG_DEVICE_SCOPE_LOADS): the one-token kernel fetches split-K partial sums
                                 with device-coherent loads even when all their writers ran on the reader's own
                                 accelerator die (results are identical; for tests and measurements);
-                                bit 1 (SCAP_CFG_GENERAL_KERNEL): one or two tokens through the general kernels
-                                instead of the one-token kernel and its two-token form;
+                                bit 1 (SCAP_CFG_GENERAL_KERNEL): one to four tokens through the general kernels
+                                instead of the one-token kernel and its two- and four-slot forms;
                                 bit 2 (SCAP_CFG_ACCUMULATE): NOT a tuning knob -- y += result instead of y = result.
                                 y must hold the addend (a residual stream, say) when the call is enqueued; every
                                 workgroup adds its share with fp32 atomic adds, which removes the split-K hand-over

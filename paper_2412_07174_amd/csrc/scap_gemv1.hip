@@ -35,7 +35,7 @@ struct Plan1 {
 };
 
 // K split and lane width of one launch.  SCAP_OK, kG1NotApplicable or a scap_status.
-// bt = token slots: 1 (one-token kernel) or 2 (its two-token form, 8 wavefronts).
+// bt = token slots: 1 (one-token kernel), 2 or 4 (its multi-token forms, 8 wavefronts).
 int plan_gemv1(const GemvArgs& g, int wdt, int kc, bool kc_forced, int waves, int granule_min, int bt, Plan1* out) {
     // int8 weights: 16 bytes per lane (1024-column tiles) unless that leaves at most 4 tiles -- then 8 bytes per
     // lane, twice the tiles and half the K splits (14336 x 4096 int8: 15.9 -> 14.2 us dense)
@@ -194,7 +194,7 @@ int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& dn, int wdt, int up
     return launch_block_half<kFuseList>(b, wdt, pd.i8_half, stream);
 }
 
-// Fused SwiGLU block of two tokens: each of its launches can run on the two-token kernel, in the list format of the
+// Fused SwiGLU block of two tokens (down launch: up to four): each of its launches can run on the multi-slot kernel, in the list format of the
 // batched block kernels (64-channel segments, 2 token slots), so either can be paired with the general kernel's.
 //   part 0, the gate|up launch with the gating epilogue: int8 weights in 16-byte lanes (2F > 4096; a wavefront's
 //           slice is then 128 columns = one segment), input length a multiple of 8;

@@ -650,7 +650,8 @@ int launch_gemv1b_wdt(const Gemv1bArgs& g, hipStream_t stream) {
     return SCAP_ERR_CONFIG;
 }
 
-// the two launches of the fused block of two tokens (fuse: kFuseSwiglu -- 16-byte int8 lanes only -- or kFuseList)
+// the launches of the fused block of two tokens (fuse: kFuseSwiglu -- 16-byte int8 lanes only -- or kFuseList), and
+// the down launch of a 16-bit block of 3-4 tokens (kFuseList, four slots)
 template <int WDT>
 int launch_gemv1b_block_wdt(const Gemv1bArgs& g, int fuse, hipStream_t stream) {
     if constexpr (WDT == kF16 || WDT == kBF16) {  // four slots: the down launch of a 16-bit block of 3-4 tokens

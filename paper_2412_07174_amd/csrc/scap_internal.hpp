@@ -95,12 +95,12 @@ int launch_gemv(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStrea
 // workgroup would own more channels than that kernel tests per wavefront: the caller takes launch_gemv's kernel.
 constexpr int kG1NotApplicable = 1;
 int launch_gemv1(const GemvArgs& a, int wdt, const scap_launch_cfg* cfg, hipStream_t stream);
-// Two tokens through that kernel's two-token form; kG1NotApplicable likewise (also for another token count, bias
+// Two to four tokens through that kernel's two- / four-slot form; kG1NotApplicable likewise (also for another token count, bias
 // folding and an input length that is not a multiple of 8).
 int launch_gemv1b(const GemvArgs& a, int wdt, int flags, hipStream_t stream);
 // The fused block of one token on the same kernel (two launches); kG1NotApplicable likewise.
 // Two-token block: whether launch `part` (0: gate|up with the gating epilogue, 1: down reading the lists) can run on the
-// two-token kernel, and that launch.  Both use the batched block kernels' list format, so the parts mix with theirs.
+// two- / four-slot kernel, and that launch.  Both use the batched block kernels' list format, so the parts mix with theirs.
 bool swiglu_block2_part_applies(const GemvArgs& up, const GemvArgs& down, int wdt, int part);
 int launch_swiglu_block2_part(const GemvArgs& up, const GemvArgs& down, int wdt, int part, hipStream_t stream);
 int launch_swiglu_block1(const GemvArgs& up, const GemvArgs& down, int wdt, int up_flags, int down_flags,

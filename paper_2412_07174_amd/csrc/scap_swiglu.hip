@@ -26,7 +26,7 @@ __global__ __launch_bounds__(kBlockWaves* kWave) void swiglu_down_kernel(const G
     gemv_body<WDT, kBlockWaves, kBlockUnroll, BT, LPR, kFuseList>(a);
 }
 
-// wdt, flags: for the two-token block, whose launches run on the two-token kernel where that applies (unless the
+// wdt, flags: for blocks of 2-4 tokens, whose launches run on the two- / four-slot kernel where that applies (unless the
 // caller asks for the general kernels)
 template <int WDT, int BT>
 static int launch_block(GemvArgs up, GemvArgs dn, int wdt, int flags, hipStream_t stream) {
